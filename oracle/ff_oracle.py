@@ -1,0 +1,300 @@
+"""ctypes face of oracle/ff_oracle.c plus the step orchestration of Algorithm 1.
+
+TEST INFRASTRUCTURE ONLY (see the C file's header).  Nothing here imports the
+HIP package; the HIP package imports nothing from here.
+
+`train_step` strings the C functions together exactly in the order of
+Algorithm 1: one full int8 forward pass per data set (positive, negative) that
+records the goodness of every layer, then, for every layer, the look-ahead loss
+coefficient, the int8 local gradient, the int8 weight-gradient contraction and
+one SGD update of the fp32 master weights.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Dict, List, Sequence
+
+import numpy as np
+
+from . import build as _build
+
+ROUND_NEAREST = 0
+ROUND_STOCHASTIC = 1
+PASS_POS = +1
+PASS_NEG = -1
+KIND_ACT = 0   # stochastic-rounding stream of an activation tensor
+KIND_GRAD = 1  # stochastic-rounding stream of a local-gradient tensor
+INT32_SAFE_ROWS = (2**31 - 1) // (127 * 127)   # longest reduction that cannot overflow int32
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        L = C.CDLL(_build.build())
+        i64, u64, f32, f64, i32 = C.c_int64, C.c_uint64, C.c_float, C.c_double, C.c_int
+        P = C.c_void_p
+        L.ffo_key.restype = u64
+        L.ffo_key.argtypes = [u64, u64]
+        L.ffo_hash.restype = C.c_uint32
+        L.ffo_hash.argtypes = [u64, u64, u64]
+        L.ffo_uniform.restype = f32
+        L.ffo_uniform.argtypes = [u64, u64, u64]
+        L.ffo_quantize.argtypes = [P, i64, i32, u64, u64, f32, P, P]
+        L.ffo_dequantize.argtypes = [P, i64, f32, P]
+        L.ffo_dequantize.restype = None
+        L.ffo_dense_forward.argtypes = [P, P, i64, i64, i64, P]
+        L.ffo_conv_forward.argtypes = [P, P, i64, i64, i64, i64, i64, i64, i64, i64, P]
+        L.ffo_goodness_shift.argtypes = [i64, i64]
+        L.ffo_goodness.argtypes = [P, i64, i64, i32, i32, f32, f32, P, P, P, P]
+        L.ffo_exp_spec.restype = f32
+        L.ffo_exp_spec.argtypes = [f32]
+        L.ffo_loss_coeff.argtypes = [P, i64, i32, f32, P, P, P]
+        L.ffo_handoff.argtypes = [P, i64, i64, i32, i32, f32, f32, P, P]
+        L.ffo_lookahead.argtypes = [P, i32, i64, f32, P]
+        L.ffo_local_grad.argtypes = [P, i64, i64, i32, f32, f32, P, P]
+        L.ffo_dense_wgrad.argtypes = [P, P, i64, i64, i64, P]
+        L.ffo_conv_wgrad.argtypes = [P, P, i64, i64, i64, i64, i64, i64, i64, i64, i64, P]
+        L.ffo_update.argtypes = [P, i64, P, P, P, i32, f32, i32]
+        _lib = L
+    return _lib
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def _chk(rc: int, what: str) -> None:
+    if rc != 0:
+        raise OracleError(f"{what}: status {rc}")
+
+
+def _p(a: np.ndarray) -> C.c_void_p:
+    assert a.flags["C_CONTIGUOUS"]
+    return C.c_void_p(a.ctypes.data)
+
+
+def stream_tag(step: int, layer: int, pass_idx: int, kind: int) -> int:
+    """Unique stochastic-rounding stream per (step, layer, pass, tensor kind)."""
+    return (int(step) << 20) | (int(layer) << 4) | (int(pass_idx) << 2) | int(kind)
+
+
+def hash_u32(seed: int, tag: int, idx: int) -> int:
+    return int(lib().ffo_hash(seed, tag, idx))
+
+
+def uniform(seed: int, tag: int, idx: int) -> float:
+    return float(lib().ffo_uniform(seed, tag, idx))
+
+
+def quantize(x: np.ndarray, mode: int, seed: int = 0, tag: int = 0, amax: float = -1.0):
+    """Per-tensor symmetric int8 quantisation.  Returns (q with x's shape, scale)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    q = np.empty(x.shape, dtype=np.int8)
+    s = np.zeros(1, dtype=np.float32)
+    _chk(lib().ffo_quantize(_p(x), x.size, mode, seed, tag, amax, _p(q), _p(s)), "quantize")
+    return q, np.float32(s[0])
+
+
+def dequantize(q: np.ndarray, scale) -> np.ndarray:
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    x = np.empty(q.shape, dtype=np.float32)
+    lib().ffo_dequantize(_p(q), q.size, np.float32(scale), _p(x))
+    return x
+
+
+def exp_spec(z: float) -> np.float32:
+    return np.float32(lib().ffo_exp_spec(np.float32(z)))
+
+
+def dense_forward(a_q: np.ndarray, w_q: np.ndarray) -> np.ndarray:
+    M, K = a_q.shape
+    N, K2 = w_q.shape
+    assert K == K2
+    acc = np.empty((M, N), dtype=np.int32)
+    _chk(lib().ffo_dense_forward(_p(a_q), _p(w_q), M, K, N, _p(acc)), "dense_forward")
+    return acc
+
+
+def conv_forward(a_q: np.ndarray, w_q: np.ndarray, stride: int, pad: int) -> np.ndarray:
+    B, H, W, Cin = a_q.shape
+    Cout, ks, ks2, Cin2 = w_q.shape
+    assert ks == ks2 and Cin == Cin2
+    Ho = (H + 2 * pad - ks) // stride + 1
+    Wo = (W + 2 * pad - ks) // stride + 1
+    acc = np.empty((B, Ho, Wo, Cout), dtype=np.int32)
+    _chk(lib().ffo_conv_forward(_p(a_q), _p(w_q), B, H, W, Cin, Cout, ks, stride, pad, _p(acc)),
+         "conv_forward")
+    return acc
+
+
+def goodness_shift(K: int, terms: int) -> int:
+    return int(lib().ffo_goodness_shift(K, terms))
+
+
+def goodness(acc: np.ndarray, relu: int, r: int, s_a, s_w):
+    """acc: [B, ...]; everything after the first axis is one sample's activities.
+    Returns dict(g_int uint64[B], vmax int32[B], G float32[B], G_plain float64[B])."""
+    B = acc.shape[0]
+    terms = acc.size // B if B else 0
+    g_int = np.empty(B, dtype=np.uint64)
+    vmax = np.empty(B, dtype=np.int32)
+    G = np.empty(B, dtype=np.float32)
+    Gp = np.empty(B, dtype=np.float64)
+    _chk(lib().ffo_goodness(_p(acc), B, terms, relu, r, np.float32(s_a), np.float32(s_w),
+                            _p(g_int), _p(vmax), _p(G), _p(Gp)), "goodness")
+    return dict(g_int=g_int, vmax=vmax, G=G, G_plain=Gp)
+
+
+def loss_coeff(G: np.ndarray, pass_sign: int, theta: float):
+    G = np.ascontiguousarray(G, dtype=np.float32)
+    B = G.size
+    c = np.empty(B, dtype=np.float32)
+    loss = np.empty(B, dtype=np.float32)
+    mean = np.zeros(1, dtype=np.float64)
+    _chk(lib().ffo_loss_coeff(_p(G), B, pass_sign, np.float32(theta), _p(c), _p(loss), _p(mean)),
+         "loss_coeff")
+    return c, loss, float(mean[0])
+
+
+def handoff(acc: np.ndarray, relu: int, l2norm: int, s_a, s_w, G: np.ndarray) -> np.ndarray:
+    B = acc.shape[0]
+    terms = acc.size // B if B else 0
+    out = np.empty(acc.shape, dtype=np.float32)
+    G = np.ascontiguousarray(G, dtype=np.float32)
+    _chk(lib().ffo_handoff(_p(acc), B, terms, relu, l2norm, np.float32(s_a), np.float32(s_w),
+                           _p(G), _p(out)), "handoff")
+    return out
+
+
+def lookahead(c: np.ndarray, lam: float) -> np.ndarray:
+    """c: float32 [k, B] of dL_j/dG_j.  Returns ctil [k, B]."""
+    c = np.ascontiguousarray(c, dtype=np.float32)
+    k, B = c.shape
+    out = np.empty_like(c)
+    _chk(lib().ffo_lookahead(_p(c), k, B, np.float32(lam), _p(out)), "lookahead")
+    return out
+
+
+def local_grad(acc: np.ndarray, relu: int, s_a, s_w, ctil: np.ndarray) -> np.ndarray:
+    B = acc.shape[0]
+    terms = acc.size // B if B else 0
+    ctil = np.ascontiguousarray(ctil, dtype=np.float32)
+    g = np.empty(acc.shape, dtype=np.float32)
+    _chk(lib().ffo_local_grad(_p(acc), B, terms, relu, np.float32(s_a), np.float32(s_w),
+                              _p(ctil), _p(g)), "local_grad")
+    return g
+
+
+def dense_wgrad(gy_q: np.ndarray, a_q: np.ndarray) -> np.ndarray:
+    M, N = gy_q.shape
+    M2, K = a_q.shape
+    assert M == M2
+    dw = np.empty((N, K), dtype=np.int32)
+    _chk(lib().ffo_dense_wgrad(_p(gy_q), _p(a_q), M, K, N, _p(dw)), "dense_wgrad")
+    return dw
+
+
+def conv_wgrad(gy_q: np.ndarray, a_q: np.ndarray, ks: int, stride: int, pad: int,
+               b0: int, b1: int) -> np.ndarray:
+    B, H, W, Cin = a_q.shape
+    Cout = gy_q.shape[-1]
+    dw = np.empty((Cout, ks, ks, Cin), dtype=np.int32)
+    _chk(lib().ffo_conv_wgrad(_p(gy_q), _p(a_q), b0, b1, H, W, Cin, Cout, ks, stride, pad, _p(dw)),
+         "conv_wgrad")
+    return dw
+
+
+def update(w: np.ndarray, dws: Sequence[np.ndarray], s_g: Sequence[float], s_a: Sequence[float],
+           lr: float, total_samples: int) -> np.ndarray:
+    """Returns the updated fp32 master weights (w itself is left untouched)."""
+    w = np.array(w, dtype=np.float32, copy=True, order="C")
+    n = len(dws)
+    ptrs = (C.c_void_p * n)(*[d.ctypes.data for d in dws])
+    sg = np.asarray(s_g, dtype=np.float32)
+    sa = np.asarray(s_a, dtype=np.float32)
+    for d in dws:
+        assert d.dtype == np.int32 and d.size == w.size and d.flags["C_CONTIGUOUS"]
+    _chk(lib().ffo_update(_p(w), w.size, ptrs, _p(sg), _p(sa), n, np.float32(lr), total_samples),
+         "update")
+    return w
+
+
+def batch_chunks(B: int, rows_per_sample: int) -> List[tuple]:
+    """Sample ranges whose reduction length (rows) cannot overflow an int32 accumulator."""
+    if B * rows_per_sample <= INT32_SAFE_ROWS:
+        return [(0, B)]
+    per = max(1, INT32_SAFE_ROWS // rows_per_sample)
+    return [(b0, min(B, b0 + per)) for b0 in range(0, B, per)]
+
+
+# --------------------------------------------------------------------------------------
+# Algorithm 1, one iteration.
+# --------------------------------------------------------------------------------------
+def forward_layer(layer, a_f32: np.ndarray, w_q: np.ndarray, s_w, pass_sign: int, theta: float,
+                  seed: int, tag_act: int) -> Dict:
+    """Quantise the layer input (stochastic rounding), contract, goodness, loss coefficient,
+    and the fp32 input of the next layer."""
+    a_q, s_a = quantize(a_f32, ROUND_STOCHASTIC, seed, tag_act)
+    if layer.kind == "dense":
+        acc = dense_forward(a_q, w_q)
+    else:
+        acc = conv_forward(a_q, w_q, layer.stride, layer.pad)
+    r = goodness_shift(layer.K, layer.terms_per_sample)
+    gd = goodness(acc, layer.relu, r, s_a, s_w)
+    c, loss, loss_mean = loss_coeff(gd["G"], pass_sign, theta)
+    a_next = handoff(acc, layer.relu, layer.l2norm_out, s_a, s_w, gd["G"])
+    return dict(a_q=a_q, s_a=s_a, acc=acc, r=r, c=c, loss=loss, loss_mean=loss_mean,
+                a_next=a_next, **gd)
+
+
+def train_step(layers, w_master: List[np.ndarray], x_pos: np.ndarray, x_neg: np.ndarray,
+               theta: float, lam: float, lr: float, seed: int, step: int,
+               keep: bool = True) -> Dict:
+    """One iteration of Algorithm 1 over both data sets.  Returns the new master weights,
+    the new int8 weights and (keep=True) every intermediate, per layer and pass."""
+    k = len(layers)
+    wq = [quantize(w, ROUND_NEAREST) for w in w_master]
+    B = x_pos.shape[0]
+    fwd: List[List[Dict]] = [[None, None] for _ in range(k)]
+    for p, (x, sign) in enumerate(((x_pos, PASS_POS), (x_neg, PASS_NEG))):
+        a = np.ascontiguousarray(x, dtype=np.float32)
+        for i, layer in enumerate(layers):
+            f = forward_layer(layer, a, wq[i][0], wq[i][1], sign, theta, seed,
+                              stream_tag(step, i, p, KIND_ACT))
+            a = f.pop("a_next")
+            fwd[i][p] = f
+    ctil = [lookahead(np.stack([fwd[i][p]["c"] for i in range(k)]), lam) for p in range(2)]
+    new_w, new_wq, new_sw, grads = [], [], [], []
+    for i, layer in enumerate(layers):
+        dws, sgs, sas = [], [], []
+        per_pass = []
+        for p in range(2):
+            f = fwd[i][p]
+            g = local_grad(f["acc"], layer.relu, f["s_a"], wq[i][1], ctil[p][i])
+            gy_q, s_g = quantize(g, ROUND_STOCHASTIC, seed, stream_tag(step, i, p, KIND_GRAD))
+            chunks = batch_chunks(B, layer.rows_per_sample)
+            dw_chunks = []
+            for (b0, b1) in chunks:
+                if layer.kind == "dense":
+                    dw = dense_wgrad(gy_q[b0:b1], f["a_q"][b0:b1])
+                else:
+                    dw = conv_wgrad(gy_q, f["a_q"], layer.ksize, layer.stride, layer.pad, b0, b1)
+                dw_chunks.append(dw.reshape(-1))
+                dws.append(dw.reshape(-1))
+                sgs.append(s_g)
+                sas.append(f["s_a"])
+            per_pass.append(dict(gy_q=gy_q, s_g=s_g, dw=dw_chunks, ctil=ctil[p][i]))
+        w_new = update(w_master[i], dws, sgs, sas, lr, 2 * B)
+        q_new, s_new = quantize(w_new, ROUND_NEAREST)
+        new_w.append(w_new)
+        new_wq.append(q_new)
+        new_sw.append(s_new)
+        grads.append(per_pass)
+    out = dict(w_master=new_w, w_q=new_wq, s_w=new_sw,
+               loss=np.array([[fwd[i][p]["loss_mean"] for p in range(2)] for i in range(k)]),
+               goodness=np.stack([np.stack([fwd[i][p]["G"] for p in range(2)]) for i in range(k)]))
+    if keep:
+        out.update(fwd=fwd, grads=grads, w_q_in=[q for q, _ in wq], s_w_in=[s for _, s in wq])
+    return out

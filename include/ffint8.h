@@ -1,0 +1,229 @@
+/*
+ * ffint8 — C-ABI of the FF-INT8 layer-local training step for AMD MI355X (gfx950).
+ *
+ * The operations follow "FF-INT8: Efficient Forward-Forward DNN Training on Edge
+ * Devices with INT8 Precision" (arXiv 2506.22771): Section IV-B (single-layer
+ * dataflow), Eq. (1)/(2) (losses), Section IV-C with Eq. (3)/(4) and Algorithm 1
+ * (look-ahead, one forward pass that updates every layer), Section V-A
+ * (theta = 2.0, lambda schedule).
+ *
+ * Conventions common to every entry point
+ *  - Every data pointer is a DEVICE pointer unless marked [host].  Descriptors
+ *    (ff_layer_desc, ff_net_desc, ff_net_state and the pointer arrays inside
+ *    ff_net_state) are [host] memory.
+ *  - The caller owns every buffer.  The library allocates nothing, frees
+ *    nothing, and keeps no pointer after a call returns.
+ *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream).  Calls return without synchronising; scalars that are
+ *    produced on the device (scales, losses) stay on the device.
+ *  - Arguments are validated on the host before anything is launched; on error
+ *    nothing has been enqueued and no output has been touched.  The library
+ *    never throws, aborts or prints.
+ *  - int8 matrices are row-major with a row pitch of ff_pitch(cols) bytes
+ *    (cols rounded up to 16); the pad bytes of every int8 tensor the library
+ *    WRITES are zero, and every int8 tensor it READS must have zero pad bytes.
+ *    int32 matrices are row-major with a row pitch of ff_pitch32(cols)
+ *    elements (cols rounded up to 4).  fp32 tensors are contiguous.
+ *  - Base addresses: int8 / int32 / workspace buffers 16-byte aligned
+ *    (FF_ERR_ALIGN otherwise); fp32 buffers 4-byte aligned.
+ *  - Determinism: equal inputs and equal (seed, stream_tag / step) give
+ *    bit-identical outputs on every run; all cross-workgroup accumulations are
+ *    integer sums or maxima.
+ *  - There is no input-gradient output anywhere: the method never forms g^A
+ *    (Section IV-B).
+ */
+#ifndef FFINT8_H
+#define FFINT8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t ff_status;
+enum {
+    FF_OK = 0,
+    FF_ERR_INVALID_ARG = -1,    /* null pointer, negative size, bad enum value        */
+    FF_ERR_SHAPE = -2,          /* inconsistent or unsupported shape                  */
+    FF_ERR_ALIGN = -3,          /* a buffer is not aligned as required                */
+    FF_ERR_WORKSPACE = -4,      /* workspace too small                                */
+    FF_ERR_OVERFLOW_BOUND = -5, /* an int32 accumulator could overflow for this shape */
+    FF_ERR_UNSUPPORTED = -6,    /* valid request this build does not implement        */
+    FF_ERR_HIP = -7             /* a HIP runtime call failed                          */
+};
+enum { FF_ROUND_NEAREST_EVEN = 0, FF_ROUND_STOCHASTIC = 1 };
+enum { FF_PASS_POS = +1, FF_PASS_NEG = -1 };
+enum { FF_DENSE = 0, FF_CONV2D = 1 };
+
+/* Stochastic-rounding stream kinds used by ff_train_step (see ff_stream_tag). */
+enum { FF_KIND_ACT = 0, FF_KIND_GRAD = 1 };
+
+/* Smallest workspace accepted by the single-operation entry points. */
+#define FF_WS_MIN_BYTES 1024u
+
+/* One FF layer.  kind FF_DENSE uses batch / in_features / out_features; kind FF_CONV2D
+ * uses batch, H, W, C_in, C_out, ksize (1 or 3), stride (1 or 2), pad (= ksize/2),
+ * input NHWC, weights [C_out][ksize][ksize][C_in].
+ * batch = samples in ONE pass (positive or negative).
+ * relu: 1 = activities are ReLU(s*acc) (the default reading), 0 = identity.
+ * l2norm_out: 1 = the input handed to the next layer is y / ||y||_2 per sample. */
+typedef struct {
+    int32_t kind, batch, in_features, out_features;
+    int32_t H, W, C_in, C_out, ksize, stride, pad;
+    int32_t relu, l2norm_out;
+} ff_layer_desc;
+
+/* A stack of layers trained together by ff_train_step. [host] */
+typedef struct {
+    int32_t n_layers;
+    int32_t batch;               /* samples per pass; must equal every layer's batch */
+    const ff_layer_desc* layers; /* [host] n_layers entries */
+} ff_net_desc;
+
+/* Trainable state. [host] arrays of n_layers DEVICE pointers.
+ * w_master[i]: fp32 [N_i, K_i] contiguous (conv: [C_out][k][k][C_in]).
+ * w_q[i]:      int8 [N_i, ff_pitch(K_i)], s_w[i]: one fp32.  Both must hold the nearest-even
+ *              quantisation of w_master[i] on entry to ff_train_step (ff_quantize produces it)
+ *              and hold that of the updated weights on return. */
+typedef struct {
+    float* const* w_master;
+    int8_t* const* w_q;
+    float* const* s_w;
+} ff_net_state;
+
+/* Row pitch in bytes of an int8 matrix with `cols` columns; row pitch in elements of an int32 one. */
+int64_t ff_pitch(int64_t cols);
+int64_t ff_pitch32(int64_t cols);
+
+/* Stream tag ff_train_step uses for (step, layer, pass index 0=pos/1=neg, kind). */
+uint64_t ff_stream_tag(uint64_t step, uint32_t layer, uint32_t pass_idx, uint32_t kind);
+
+const char* ff_status_string(ff_status s);
+const char* ff_version(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * ff_quantize — per-tensor symmetric uniform int8 quantiser (Section IV; Section IV-B: stochastic
+ * rounding for the layer input A; nearest-even is used for weights).
+ *   x      [rows, cols] fp32 contiguous (in)
+ *   q      [rows, ff_pitch(cols)] int8 (out, may be NULL)
+ *   q_t    [cols, ff_pitch(rows)] int8, the transposed copy the weight-gradient contraction reads
+ *          (out, may be NULL; at least one of q, q_t must be given)
+ *   scale  one fp32 (out): absmax/127, or 1 when the tensor is all zero
+ * codes = clamp(round(x * (127/absmax)), -127, 127).  Stochastic rounding draws one uniform per
+ * element from a counter-based generator keyed by (seed, stream_tag, row*cols+col).
+ * rows*cols == 0 is accepted (scale = 1).  ws: >= FF_WS_MIN_BYTES of scratch.
+ * ------------------------------------------------------------------------------------------- */
+ff_status ff_quantize(const float* x, int64_t rows, int64_t cols, int32_t round_mode, uint64_t seed,
+                      uint64_t stream_tag, int8_t* q, int8_t* q_t, float* scale, void* ws,
+                      size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * ff_layer_forward — the int8 x int8 -> int32 contraction of one layer for one pass
+ * (Section IV-B: "INT8 inputs and INT32 accumulation"), with the per-sample reductions the
+ * goodness needs fused into its epilogue (Algorithm 1: G = ||y||^2).
+ *   a_q      int8 [M, ff_pitch(K)] (dense: M = batch, K = in_features)               (in)
+ *   w_q      int8 [N, ff_pitch(K)]                                                   (in)
+ *   acc      int32 [M, ff_pitch32(N)]: acc[m][n] = sum_k a_q[m][k] * w_q[n][k]       (out)
+ *   gsum_int uint64 [batch]: sum over the sample of (v*v >> r), v = act(acc) as an integer,
+ *            r = ff_goodness_shift(layer)                                            (out)
+ *   vmax     int32 [batch]: max over the sample of |v|                               (out)
+ * Returns FF_ERR_OVERFLOW_BOUND if K * 127^2 could exceed int32.
+ * ------------------------------------------------------------------------------------------- */
+ff_status ff_layer_forward(const ff_layer_desc* layer, const int8_t* a_q, const int8_t* w_q,
+                           int32_t* acc, uint64_t* gsum_int, int32_t* vmax, void* ws,
+                           size_t ws_bytes, void* stream);
+
+/* Right shift applied to each squared integer activity before it is summed into gsum_int:
+ * the smallest r >= 0 with (127^2 K)^2 * T / 2^r < 2^64, T = activities per sample.  [host only] */
+int32_t ff_goodness_shift(const ff_layer_desc* layer);
+
+/* ---------------------------------------------------------------------------------------------
+ * ff_goodness_loss — goodness, FF loss and its derivative for one layer and one pass.
+ *   goodness[b]  = fp32( gsum_int[b] * 2^r * s_y^2 ),  s_y = s_a * s_w   (Section III, Algorithm 1)
+ *   positive pass (Eq. (1)): L = log(1 + exp(-(G - theta))), coeff = dL/dG = -sigmoid(-(G - theta))
+ *   negative pass (Eq. (2)): L = log(1 + exp(+(G - theta))), coeff = dL/dG = +sigmoid(+(G - theta))
+ *   loss_mean    = mean of L over the batch (one fp32)
+ *   next_amax    = absmax of the tensor this layer hands to the next one, act(s_y*acc) or its
+ *                  L2-normalised form (one fp32; may be NULL)
+ * s_a, s_w: device scalars (in).  vmax: as produced by ff_layer_forward (in).
+ * ------------------------------------------------------------------------------------------- */
+ff_status ff_goodness_loss(const ff_layer_desc* layer, const uint64_t* gsum_int, const int32_t* vmax,
+                           const float* s_a, const float* s_w, int32_t pass_sign, float theta,
+                           float* goodness, float* coeff, float* loss_mean, float* next_amax,
+                           void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * ff_layer_handoff — the next layer's int8 input straight from this layer's accumulators
+ * (Algorithm 1: the forward pass continues through all layers): a = act(s_y * acc), divided by
+ * sqrt(goodness[b]) when layer->l2norm_out, quantised with `round_mode` against `amax`
+ * (the value ff_goodness_loss wrote to next_amax).
+ *   q   [M, ff_pitch(N)] (may be NULL), q_t [N, ff_pitch(M)] (may be NULL), scale: one fp32.
+ * For a conv layer the rows are output pixels (NHWC), M = batch * H_out * W_out.
+ * ------------------------------------------------------------------------------------------- */
+ff_status ff_layer_handoff(const ff_layer_desc* layer, const int32_t* acc, const float* s_a,
+                           const float* s_w, const float* goodness, const float* amax,
+                           int32_t round_mode, uint64_t seed, uint64_t stream_tag, int8_t* q,
+                           int8_t* q_t, float* scale, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * ff_lookahead — look-ahead combination of the per-sample loss derivatives (Eq. (3), Eq. (4)):
+ *   coeff_total[i][b] = coeff[i][b] + lambda * sum_{j > i} coeff[j][b]
+ * evaluated as S_k = 0, S_i = S_{i+1} + coeff[i+1], coeff_total[i] = fma(lambda, S_i, coeff[i]).
+ * coeff, coeff_total: fp32 [n_layers, batch].  lambda = 0 returns coeff bit for bit.
+ * ------------------------------------------------------------------------------------------- */
+ff_status ff_lookahead(const float* coeff, int32_t n_layers, int64_t batch, float lambda,
+                       float* coeff_total, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * ff_layer_backward_local — int8 local gradient and int8 weight-gradient contraction of one layer
+ * for one pass (Section IV-B: g^Y is quantised to int8; only g^W is formed).
+ *   g[m][n]      = (2 * coeff_total[b(m)]) * act(s_y * acc[m][n])
+ *   gy_q_t       int8 [N, ff_pitch(M)]: quantised g, transposed, scale s_g               (out)
+ *   dw_acc       int32 [N, ff_pitch32(K)]: dw_acc[n][k] = sum_m gy_q[m][n] * a_q[m][k]   (out)
+ *   a_q_t        int8 [K, ff_pitch(M)]: the transposed copy ff_quantize / ff_layer_handoff wrote (in)
+ * Returns FF_ERR_OVERFLOW_BOUND if M * 127^2 could exceed int32 (split the batch instead).
+ * ------------------------------------------------------------------------------------------- */
+ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc, const int32_t* vmax,
+                                  const float* s_a, const float* s_w, const float* coeff_total,
+                                  int32_t round_mode, uint64_t seed, uint64_t stream_tag,
+                                  const int8_t* a_q_t, int8_t* gy_q_t, float* s_g, int32_t* dw_acc,
+                                  void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * ff_layer_update — SGD step on the fp32 master weights from both passes' integer accumulators
+ * and requantisation (Algorithm 1: "update weights using gradients in INT8 precision"):
+ *   g = fp32(dw_pos) * (s_g_pos * s_a_pos);  g = fma(fp32(dw_neg), s_g_neg * s_a_neg, g)
+ *   w = fma(-(lr / total_samples), g, w)
+ *   w_q, s_w = nearest-even quantisation of the new w.
+ * w_master fp32 [N, K] (in/out); dw_* int32 [N, ff_pitch32(K)]; w_q int8 [N, ff_pitch(K)].
+ * ------------------------------------------------------------------------------------------- */
+ff_status ff_layer_update(const ff_layer_desc* layer, float* w_master, const int32_t* dw_acc_pos,
+                          const float* s_g_pos, const float* s_a_pos, const int32_t* dw_acc_neg,
+                          const float* s_g_neg, const float* s_a_neg, float lr, int32_t total_samples,
+                          int8_t* w_q, float* s_w, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * ff_train_step — one iteration of Algorithm 1 over the positive and the negative set:
+ * one int8 forward pass through all layers per set, goodness of every layer, then for every layer
+ * the look-ahead loss derivative, the int8 local gradient, the int8 weight gradient and one
+ * combined update.  Every layer's update uses activations computed with the pre-step weights.
+ *   x_pos, x_neg  fp32 [batch, in_features] (dense first layer) or NHWC (conv)        (in)
+ *   loss          fp32 [n_layers, 2]: mean loss per layer, [.,0] positive, [.,1] negative (out)
+ *   goodness      fp32 [n_layers, 2, batch]                                           (out)
+ *   ws            >= ff_workspace_bytes(net) bytes
+ * Stochastic rounding streams: ff_stream_tag(step, layer, pass, kind) under `seed`.
+ * ------------------------------------------------------------------------------------------- */
+ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const float* x_pos,
+                        const float* x_neg, float theta, float lambda, float lr, uint64_t seed,
+                        uint64_t step, float* loss, float* goodness, void* ws, size_t ws_bytes,
+                        void* stream);
+
+/* Bytes of workspace ff_train_step needs for `net`; 0 if the descriptor is invalid. [host only] */
+size_t ff_workspace_bytes(const ff_net_desc* net);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FFINT8_H */

@@ -1,0 +1,11 @@
+"""MI355X-native FF-INT8 layer-local train step: thin ctypes binding over libffint8.so.
+
+Every step of the path runs in the library's HIP kernels; this package only marshals
+arguments (torch is used for device memory and streams).  There is no CPU fallback:
+importing the binding without a built library raises."""
+from .binding import (  # noqa: F401
+    FFError, Net, lib, layer_desc, ff_pitch, ff_pitch32, ff_stream_tag, ff_status_string, ff_version,
+    ff_goodness_shift, ff_quantize, ff_layer_forward, ff_goodness_loss, ff_layer_handoff, ff_lookahead,
+    ff_layer_backward_local, ff_layer_update, ff_train_step, ff_workspace_bytes,
+    ROUND_NEAREST, ROUND_STOCHASTIC, PASS_POS, PASS_NEG, KIND_ACT, KIND_GRAD, WS_MIN_BYTES,
+)

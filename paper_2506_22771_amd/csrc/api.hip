@@ -1,0 +1,685 @@
+// C-ABI entry points of libffint8: argument validation on the host, then kernel launches on the
+// caller's stream.  Nothing here allocates device memory or synchronises.
+#include <string.h>
+
+#include "ff_internal.hpp"
+
+namespace ffi {
+
+static uint64_t fin64(uint64_t z)
+{
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+SrKey make_sr_key(uint64_t seed, uint64_t tag)
+{
+    const uint64_t key = fin64(seed + 0x9E3779B97F4A7C15ull * (tag + 1ull));
+    SrKey k;
+    k.k0 = (uint32_t)key;
+    k.k1 = (uint32_t)(key >> 32) | 1u;
+    return k;
+}
+
+constexpr int64_t INT32_SAFE_LEN = 2147483647ll / (127 * 127);  // longest reduction that cannot overflow int32
+constexpr int MAX_LAYERS = 32;
+
+struct Dims {
+    int64_t B, M, K, N, rps, in_cols;  // M rows per pass, rps rows per sample, in_cols = columns of the 2-D input view
+};
+
+static ff_status layer_dims(const ff_layer_desc* L, Dims* d)
+{
+    if (!L) return FF_ERR_INVALID_ARG;
+    if (L->batch < 0) return FF_ERR_INVALID_ARG;
+    if (L->kind == FF_DENSE) {
+        if (L->in_features <= 0 || L->out_features <= 0) return FF_ERR_SHAPE;
+        d->B = L->batch;
+        d->M = L->batch;
+        d->K = L->in_features;
+        d->N = L->out_features;
+        d->rps = 1;
+        d->in_cols = L->in_features;
+        return FF_OK;
+    }
+    if (L->kind == FF_CONV2D) return FF_ERR_UNSUPPORTED;
+    return FF_ERR_INVALID_ARG;
+}
+
+static bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
+static bool aligned4(const void* p) { return (((uintptr_t)p) & 3) == 0; }
+#define HIPCHK(e) do { if ((e) != hipSuccess) return FF_ERR_HIP; } while (0)
+
+static int32_t goodness_shift(int64_t K, int64_t terms)
+{
+    const unsigned __int128 a = (unsigned __int128)16129u * (unsigned __int128)K;
+    const unsigned __int128 bound = a * a * (unsigned __int128)terms;
+    int r = 0;
+    while ((bound >> r) >> 64) ++r;
+    return r;
+}
+
+// ---- workspace of ff_train_step ------------------------------------------------------------------
+struct WsLayout {
+    int k;
+    int64_t B;
+    Dims d[MAX_LAYERS];
+    // byte offsets
+    size_t off_slots;      // uint32: act_amax[k][2], g_amax[k][2], w_amax[k]
+    size_t off_gsum;       // uint64 [k][2][B]
+    size_t off_vmax;       // int32  [k][2][B]
+    size_t zero_bytes;     // the region [0, zero_bytes) is cleared at the start of a step
+    size_t off_scales;     // fp32: s_a[k][2], s_g[k][2]
+    size_t off_c, off_ct;  // fp32 [k][2][B]
+    size_t off_aq, st_aq;  // int8 scratch [2][st_aq]
+    size_t off_gy, st_gy;  // int8 scratch [2][st_gy]
+    size_t off_dw, st_dw;  // int32 scratch [2][st_dw] (bytes)
+    size_t off_aqt[MAX_LAYERS], st_aqt[MAX_LAYERS];  // int8 [2][st]
+    size_t off_acc[MAX_LAYERS], st_acc[MAX_LAYERS];  // int32 [2][st] (bytes)
+    size_t total;
+};
+
+static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
+{
+    if (!net || !net->layers) return FF_ERR_INVALID_ARG;
+    if (net->n_layers < 1 || net->n_layers > MAX_LAYERS) return FF_ERR_SHAPE;
+    if (net->batch < 1) return FF_ERR_SHAPE;
+    w->k = net->n_layers;
+    w->B = net->batch;
+    for (int i = 0; i < w->k; ++i) {
+        const ff_status st = layer_dims(&net->layers[i], &w->d[i]);
+        if (st != FF_OK) return st;
+        if (net->layers[i].batch != net->batch) return FF_ERR_SHAPE;
+        if (i > 0 && w->d[i].K != w->d[i - 1].N) return FF_ERR_SHAPE;
+        if (w->d[i].K > INT32_SAFE_LEN || w->d[i].M > INT32_SAFE_LEN) return FF_ERR_OVERFLOW_BOUND;
+    }
+    const size_t A = 256;
+    size_t off = 0;
+    const size_t k = (size_t)w->k, B = (size_t)w->B;
+    w->off_slots = off;
+    off = align_up(off + sizeof(uint32_t) * (k * 5), A);
+    w->off_gsum = off;
+    off = align_up(off + sizeof(uint64_t) * k * 2 * B, A);
+    w->off_vmax = off;
+    off = align_up(off + sizeof(int32_t) * k * 2 * B, A);
+    w->zero_bytes = off;
+    w->off_scales = off;
+    off = align_up(off + sizeof(float) * k * 4, A);
+    w->off_c = off;
+    off = align_up(off + sizeof(float) * k * 2 * B, A);
+    w->off_ct = off;
+    off = align_up(off + sizeof(float) * k * 2 * B, A);
+    size_t aq = 0, gy = 0, dw = 0;
+    for (int i = 0; i < w->k; ++i) {
+        const Dims& d = w->d[i];
+        aq = max(aq, (size_t)(d.M * pitch8(d.K)));
+        gy = max(gy, (size_t)(d.N * pitch8(d.M)));
+        dw = max(dw, (size_t)(d.N * pitch32(d.K)) * sizeof(int32_t));
+    }
+    w->st_aq = align_up(aq, A);
+    w->off_aq = off;
+    off += 2 * w->st_aq;
+    w->st_gy = align_up(gy, A);
+    w->off_gy = off;
+    off += 2 * w->st_gy;
+    w->st_dw = align_up(dw, A);
+    w->off_dw = off;
+    off += 2 * w->st_dw;
+    for (int i = 0; i < w->k; ++i) {
+        const Dims& d = w->d[i];
+        w->st_aqt[i] = align_up((size_t)(d.K * pitch8(d.M)), A);
+        w->off_aqt[i] = off;
+        off += 2 * w->st_aqt[i];
+        w->st_acc[i] = align_up((size_t)(d.M * pitch32(d.N)) * sizeof(int32_t), A);
+        w->off_acc[i] = off;
+        off += 2 * w->st_acc[i];
+    }
+    w->total = off;
+    return FF_OK;
+}
+
+}  // namespace ffi
+
+using namespace ffi;
+
+extern "C" {
+
+int64_t ff_pitch(int64_t cols) { return pitch8(cols); }
+int64_t ff_pitch32(int64_t cols) { return pitch32(cols); }
+
+uint64_t ff_stream_tag(uint64_t step, uint32_t layer, uint32_t pass_idx, uint32_t kind)
+{
+    return (step << 20) | ((uint64_t)layer << 4) | ((uint64_t)pass_idx << 2) | (uint64_t)kind;
+}
+
+const char* ff_status_string(ff_status s)
+{
+    switch (s) {
+        case FF_OK: return "ok";
+        case FF_ERR_INVALID_ARG: return "invalid argument";
+        case FF_ERR_SHAPE: return "inconsistent or unsupported shape";
+        case FF_ERR_ALIGN: return "buffer not aligned as required";
+        case FF_ERR_WORKSPACE: return "workspace too small";
+        case FF_ERR_OVERFLOW_BOUND: return "an int32 accumulator could overflow for this shape";
+        case FF_ERR_UNSUPPORTED: return "not implemented in this build";
+        case FF_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+const char* ff_version(void) { return "ffint8 0.1 (gfx950)"; }
+
+int32_t ff_goodness_shift(const ff_layer_desc* layer)
+{
+    Dims d;
+    if (layer_dims(layer, &d) != FF_OK) return -1;
+    return goodness_shift(d.K, d.rps * d.N);
+}
+
+ff_status ff_quantize(const float* x, int64_t rows, int64_t cols, int32_t round_mode, uint64_t seed,
+                      uint64_t stream_tag, int8_t* q, int8_t* q_t, float* scale, void* ws, size_t ws_bytes,
+                      void* stream)
+{
+    if (rows < 0 || cols < 0 || !scale || (!q && !q_t) || !ws) return FF_ERR_INVALID_ARG;
+    if (round_mode != FF_ROUND_NEAREST_EVEN && round_mode != FF_ROUND_STOCHASTIC) return FF_ERR_INVALID_ARG;
+    if (ws_bytes < FF_WS_MIN_BYTES) return FF_ERR_WORKSPACE;
+    if (!aligned16(ws) || (q && !aligned16(q)) || (q_t && !aligned16(q_t)) || !aligned4(scale)) return FF_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    if (rows == 0 || cols == 0) {
+        const float one = 1.0f;
+        uint32_t bits;
+        memcpy(&bits, &one, 4);
+        HIPCHK(launch_fill_u32((uint32_t*)scale, 1, bits, s));
+        return FF_OK;
+    }
+    if (!x) return FF_ERR_INVALID_ARG;
+    if (!aligned4(x)) return FF_ERR_ALIGN;
+    uint32_t* slot = (uint32_t*)ws;
+    HIPCHK(launch_fill_u32(slot, 1, 0u, s));
+    HIPCHK(launch_absmax(x, rows * cols, slot, s));
+    QuantArgs a;
+    memset(&a, 0, sizeof(a));
+    a.x = x;
+    a.amax_bits = slot;
+    a.round_mode = round_mode;
+    a.key = make_sr_key(seed, stream_tag);
+    a.rows = rows;
+    a.cols = cols;
+    a.q = q;
+    a.ldq = pitch8(cols);
+    a.q_t = q_t;
+    a.ldqt = pitch8(rows);
+    a.scale = scale;
+    a.nb = 1;
+    a.rows_per_sample = 1;
+    HIPCHK(launch_quantize(QSRC_F32, a, s));
+    return FF_OK;
+}
+
+ff_status ff_layer_forward(const ff_layer_desc* layer, const int8_t* a_q, const int8_t* w_q, int32_t* acc,
+                           uint64_t* gsum_int, int32_t* vmax, void* ws, size_t ws_bytes, void* stream)
+{
+    (void)ws;
+    (void)ws_bytes;
+    Dims d;
+    const ff_status st = layer_dims(layer, &d);
+    if (st != FF_OK) return st;
+    if (!a_q || !w_q || !acc || !gsum_int || !vmax) return FF_ERR_INVALID_ARG;
+    if (!aligned16(a_q) || !aligned16(w_q) || !aligned16(acc) || (((uintptr_t)gsum_int) & 7) || !aligned4(vmax))
+        return FF_ERR_ALIGN;
+    if (d.K > INT32_SAFE_LEN) return FF_ERR_OVERFLOW_BOUND;
+    hipStream_t s = (hipStream_t)stream;
+    if (d.B == 0) return FF_OK;
+    HIPCHK(launch_fill_u32((uint32_t*)gsum_int, 2 * d.B, 0u, s));
+    HIPCHK(launch_fill_u32((uint32_t*)vmax, d.B, 0u, s));
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.P = a_q;
+    g.Q = w_q;
+    g.C = acc;
+    g.I = (int32_t)d.M;
+    g.J = (int32_t)d.N;
+    g.R = (int32_t)d.K;
+    g.ldp = pitch8(d.K);
+    g.ldq = pitch8(d.K);
+    g.ldc = pitch32(d.N);
+    g.gsum = (unsigned long long*)gsum_int;
+    g.vmax = vmax;
+    g.rows_per_sample = (int32_t)d.rps;
+    g.relu = layer->relu ? 1 : 0;
+    g.rshift = goodness_shift(d.K, d.rps * d.N);
+    g.nb = 1;
+    HIPCHK(launch_gemm_nt_i8(g, s));
+    return FF_OK;
+}
+
+ff_status ff_goodness_loss(const ff_layer_desc* layer, const uint64_t* gsum_int, const int32_t* vmax,
+                           const float* s_a, const float* s_w, int32_t pass_sign, float theta, float* goodness,
+                           float* coeff, float* loss_mean, float* next_amax, void* stream)
+{
+    Dims d;
+    const ff_status st = layer_dims(layer, &d);
+    if (st != FF_OK) return st;
+    if (!gsum_int || !vmax || !s_a || !s_w || !goodness || !coeff || !loss_mean) return FF_ERR_INVALID_ARG;
+    if (pass_sign != FF_PASS_POS && pass_sign != FF_PASS_NEG) return FF_ERR_INVALID_ARG;
+    if ((((uintptr_t)gsum_int) & 7) || !aligned4(vmax) || !aligned4(goodness) || !aligned4(coeff)) return FF_ERR_ALIGN;
+    GoodnessArgs a;
+    memset(&a, 0, sizeof(a));
+    a.gsum = (const unsigned long long*)gsum_int;
+    a.vmax = vmax;
+    a.s_a = s_a;
+    a.s_w = s_w;
+    a.rshift = goodness_shift(d.K, d.rps * d.N);
+    a.l2norm = layer->l2norm_out ? 1 : 0;
+    a.pass_sign = pass_sign;
+    a.theta = theta;
+    a.B = d.B;
+    a.goodness = goodness;
+    a.coeff = coeff;
+    a.loss_mean = loss_mean;
+    a.next_amax_bits = (uint32_t*)next_amax;
+    a.nb = 1;
+    HIPCHK(launch_goodness_loss(a, (hipStream_t)stream));
+    return FF_OK;
+}
+
+ff_status ff_layer_handoff(const ff_layer_desc* layer, const int32_t* acc, const float* s_a, const float* s_w,
+                           const float* goodness, const float* amax, int32_t round_mode, uint64_t seed,
+                           uint64_t stream_tag, int8_t* q, int8_t* q_t, float* scale, void* stream)
+{
+    Dims d;
+    const ff_status st = layer_dims(layer, &d);
+    if (st != FF_OK) return st;
+    if (!acc || !s_a || !s_w || !amax || !scale || (!q && !q_t)) return FF_ERR_INVALID_ARG;
+    if (layer->l2norm_out && !goodness) return FF_ERR_INVALID_ARG;
+    if (round_mode != FF_ROUND_NEAREST_EVEN && round_mode != FF_ROUND_STOCHASTIC) return FF_ERR_INVALID_ARG;
+    if (!aligned16(acc) || (q && !aligned16(q)) || (q_t && !aligned16(q_t))) return FF_ERR_ALIGN;
+    QuantArgs a;
+    memset(&a, 0, sizeof(a));
+    a.acc = acc;
+    a.ldacc = pitch32(d.N);
+    a.s_a = s_a;
+    a.s_w = s_w;
+    a.per_sample = goodness;
+    a.rows_per_sample = (int32_t)d.rps;
+    a.relu = layer->relu ? 1 : 0;
+    a.l2norm = layer->l2norm_out ? 1 : 0;
+    a.amax_bits = (const uint32_t*)amax;
+    a.round_mode = round_mode;
+    a.key = make_sr_key(seed, stream_tag);
+    a.rows = d.M;
+    a.cols = d.N;
+    a.q = q;
+    a.ldq = pitch8(d.N);
+    a.q_t = q_t;
+    a.ldqt = pitch8(d.M);
+    a.scale = scale;
+    a.nb = 1;
+    HIPCHK(launch_quantize(QSRC_HANDOFF, a, (hipStream_t)stream));
+    return FF_OK;
+}
+
+ff_status ff_lookahead(const float* coeff, int32_t n_layers, int64_t batch, float lambda, float* coeff_total,
+                       void* stream)
+{
+    if (!coeff || !coeff_total || batch < 0) return FF_ERR_INVALID_ARG;
+    if (n_layers < 1 || n_layers > MAX_LAYERS) return FF_ERR_SHAPE;
+    if (batch == 0) return FF_OK;
+    LookaheadArgs a;
+    memset(&a, 0, sizeof(a));
+    a.coeff = coeff;
+    a.coeff_total = coeff_total;
+    a.k = n_layers;
+    a.np = 1;
+    a.B = batch;
+    a.st_layer = batch;
+    a.st_pass = 0;
+    a.lambda = lambda;
+    HIPCHK(launch_lookahead(a, (hipStream_t)stream));
+    return FF_OK;
+}
+
+ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc, const int32_t* vmax,
+                                  const float* s_a, const float* s_w, const float* coeff_total, int32_t round_mode,
+                                  uint64_t seed, uint64_t stream_tag, const int8_t* a_q_t, int8_t* gy_q_t,
+                                  float* s_g, int32_t* dw_acc, void* ws, size_t ws_bytes, void* stream)
+{
+    Dims d;
+    const ff_status st = layer_dims(layer, &d);
+    if (st != FF_OK) return st;
+    if (!acc || !vmax || !s_a || !s_w || !coeff_total || !a_q_t || !gy_q_t || !s_g || !dw_acc || !ws)
+        return FF_ERR_INVALID_ARG;
+    if (round_mode != FF_ROUND_NEAREST_EVEN && round_mode != FF_ROUND_STOCHASTIC) return FF_ERR_INVALID_ARG;
+    if (ws_bytes < FF_WS_MIN_BYTES) return FF_ERR_WORKSPACE;
+    if (!aligned16(acc) || !aligned16(a_q_t) || !aligned16(gy_q_t) || !aligned16(dw_acc) || !aligned16(ws))
+        return FF_ERR_ALIGN;
+    if (d.M > INT32_SAFE_LEN) return FF_ERR_OVERFLOW_BOUND;
+    hipStream_t s = (hipStream_t)stream;
+    uint32_t* slot = (uint32_t*)ws;
+    HIPCHK(launch_grad_amax(coeff_total, vmax, s_a, s_w, d.B, slot, s));
+    QuantArgs a;
+    memset(&a, 0, sizeof(a));
+    a.acc = acc;
+    a.ldacc = pitch32(d.N);
+    a.s_a = s_a;
+    a.s_w = s_w;
+    a.per_sample = coeff_total;
+    a.rows_per_sample = (int32_t)d.rps;
+    a.relu = layer->relu ? 1 : 0;
+    a.amax_bits = slot;
+    a.round_mode = round_mode;
+    a.key = make_sr_key(seed, stream_tag);
+    a.rows = d.M;
+    a.cols = d.N;
+    a.q_t = gy_q_t;
+    a.ldqt = pitch8(d.M);
+    a.scale = s_g;
+    a.nb = 1;
+    HIPCHK(launch_quantize(QSRC_GRAD, a, s));
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.P = gy_q_t;
+    g.Q = a_q_t;
+    g.C = dw_acc;
+    g.I = (int32_t)d.N;
+    g.J = (int32_t)d.K;
+    g.R = (int32_t)d.M;
+    g.ldp = pitch8(d.M);
+    g.ldq = pitch8(d.M);
+    g.ldc = pitch32(d.K);
+    g.nb = 1;
+    g.rows_per_sample = 1;
+    HIPCHK(launch_gemm_nt_i8(g, s));
+    return FF_OK;
+}
+
+ff_status ff_layer_update(const ff_layer_desc* layer, float* w_master, const int32_t* dw_acc_pos,
+                          const float* s_g_pos, const float* s_a_pos, const int32_t* dw_acc_neg,
+                          const float* s_g_neg, const float* s_a_neg, float lr, int32_t total_samples,
+                          int8_t* w_q, float* s_w, void* ws, size_t ws_bytes, void* stream)
+{
+    Dims d;
+    const ff_status st = layer_dims(layer, &d);
+    if (st != FF_OK) return st;
+    if (!w_master || !dw_acc_pos || !s_g_pos || !s_a_pos || !dw_acc_neg || !s_g_neg || !s_a_neg || !w_q || !s_w || !ws)
+        return FF_ERR_INVALID_ARG;
+    if (total_samples < 1) return FF_ERR_INVALID_ARG;
+    if (ws_bytes < FF_WS_MIN_BYTES) return FF_ERR_WORKSPACE;
+    if (!aligned4(w_master) || !aligned16(dw_acc_pos) || !aligned16(dw_acc_neg) || !aligned16(w_q) || !aligned16(ws))
+        return FF_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    uint32_t* slot = (uint32_t*)ws;
+    HIPCHK(launch_fill_u32(slot, 1, 0u, s));
+    UpdateArgs u;
+    memset(&u, 0, sizeof(u));
+    u.w = w_master;
+    u.N = d.N;
+    u.K = d.K;
+    u.lddw = pitch32(d.K);
+    u.n_terms = 2;
+    u.dw[0] = dw_acc_pos;
+    u.s_g[0] = s_g_pos;
+    u.s_a[0] = s_a_pos;
+    u.dw[1] = dw_acc_neg;
+    u.s_g[1] = s_g_neg;
+    u.s_a[1] = s_a_neg;
+    u.lr = lr;
+    u.total_samples = total_samples;
+    u.w_amax_bits = slot;
+    HIPCHK(launch_update(u, s));
+    QuantArgs a;
+    memset(&a, 0, sizeof(a));
+    a.x = w_master;
+    a.amax_bits = slot;
+    a.round_mode = FF_ROUND_NEAREST_EVEN;
+    a.rows = d.N;
+    a.cols = d.K;
+    a.q = w_q;
+    a.ldq = pitch8(d.K);
+    a.scale = s_w;
+    a.nb = 1;
+    a.rows_per_sample = 1;
+    HIPCHK(launch_quantize(QSRC_F32, a, s));
+    return FF_OK;
+}
+
+size_t ff_workspace_bytes(const ff_net_desc* net)
+{
+    WsLayout w;
+    if (make_layout(net, &w) != FF_OK) return 0;
+    return w.total;
+}
+
+ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const float* x_pos, const float* x_neg,
+                        float theta, float lambda, float lr, uint64_t seed, uint64_t step, float* loss,
+                        float* goodness, void* ws, size_t ws_bytes, void* stream)
+{
+    WsLayout w;
+    const ff_status st = make_layout(net, &w);
+    if (st != FF_OK) return st;
+    if (!state || !state->w_master || !state->w_q || !state->s_w || !x_pos || !x_neg || !loss || !goodness || !ws)
+        return FF_ERR_INVALID_ARG;
+    for (int i = 0; i < w.k; ++i) {
+        if (!state->w_master[i] || !state->w_q[i] || !state->s_w[i]) return FF_ERR_INVALID_ARG;
+        if (!aligned4(state->w_master[i]) || !aligned16(state->w_q[i])) return FF_ERR_ALIGN;
+    }
+    if (ws_bytes < w.total) return FF_ERR_WORKSPACE;
+    if (!aligned16(ws) || !aligned4(x_pos) || !aligned4(x_neg) || !aligned4(loss) || !aligned4(goodness))
+        return FF_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    char* base = (char*)ws;
+    const int k = w.k;
+    const int64_t B = w.B;
+    uint32_t* act_amax = (uint32_t*)(base + w.off_slots);  // [k][2]
+    uint32_t* g_amax = act_amax + 2 * k;                   // [k][2]
+    uint32_t* w_amax = g_amax + 2 * k;                     // [k]
+    unsigned long long* gsum = (unsigned long long*)(base + w.off_gsum);
+    int32_t* vmax = (int32_t*)(base + w.off_vmax);
+    float* s_a = (float*)(base + w.off_scales);  // [k][2]
+    float* s_g = s_a + 2 * k;                    // [k][2]
+    float* c = (float*)(base + w.off_c);
+    float* ct = (float*)(base + w.off_ct);
+
+    HIPCHK(launch_fill_u32((uint32_t*)base, (int64_t)(w.zero_bytes / 4), 0u, s));
+    const int64_t n_in = w.d[0].M * w.d[0].in_cols;
+    HIPCHK(launch_absmax(x_pos, n_in, act_amax + 0, s));
+    HIPCHK(launch_absmax(x_neg, n_in, act_amax + 1, s));
+
+    // ---- forward pass through all layers, both data sets together (Algorithm 1) -----------------
+    for (int i = 0; i < k; ++i) {
+        const Dims& d = w.d[i];
+        const ff_layer_desc& L = net->layers[i];
+        QuantArgs a;
+        memset(&a, 0, sizeof(a));
+        int src;
+        if (i == 0) {
+            src = QSRC_F32;
+            a.x = x_pos;
+            a.st_x = ((intptr_t)x_neg - (intptr_t)x_pos) / (intptr_t)sizeof(float);
+            a.rows_per_sample = 1;
+        } else {
+            const Dims& dp = w.d[i - 1];
+            const ff_layer_desc& Lp = net->layers[i - 1];
+            src = QSRC_HANDOFF;
+            a.acc = (const int32_t*)(base + w.off_acc[i - 1]);
+            a.st_acc = (int64_t)(w.st_acc[i - 1] / sizeof(int32_t));
+            a.ldacc = pitch32(dp.N);
+            a.s_a = s_a + 2 * (i - 1);
+            a.st_s_a = 1;
+            a.s_w = state->s_w[i - 1];
+            a.st_s_w = 0;
+            a.per_sample = goodness + (int64_t)(i - 1) * 2 * B;
+            a.st_per_sample = B;
+            a.rows_per_sample = (int32_t)dp.rps;
+            a.relu = Lp.relu ? 1 : 0;
+            a.l2norm = Lp.l2norm_out ? 1 : 0;
+        }
+        a.amax_bits = act_amax + 2 * i;
+        a.st_amax = 1;
+        a.round_mode = FF_ROUND_STOCHASTIC;
+        a.key = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 0, FF_KIND_ACT));
+        a.key2 = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 1, FF_KIND_ACT));
+        a.rows = d.M;
+        a.cols = d.in_cols;
+        a.q = (int8_t*)(base + w.off_aq);
+        a.st_q = (int64_t)w.st_aq;
+        a.ldq = pitch8(d.K);
+        a.q_t = (int8_t*)(base + w.off_aqt[i]);
+        a.st_qt = (int64_t)w.st_aqt[i];
+        a.ldqt = pitch8(d.M);
+        a.scale = s_a + 2 * i;
+        a.st_scale = 1;
+        a.nb = 2;
+        HIPCHK(launch_quantize(src, a, s));
+
+        GemmArgs g;
+        memset(&g, 0, sizeof(g));
+        g.P = (const int8_t*)(base + w.off_aq);
+        g.st_p = (int64_t)w.st_aq;
+        g.Q = state->w_q[i];
+        g.st_q = 0;
+        g.C = (int32_t*)(base + w.off_acc[i]);
+        g.st_c = (int64_t)(w.st_acc[i] / sizeof(int32_t));
+        g.I = (int32_t)d.M;
+        g.J = (int32_t)d.N;
+        g.R = (int32_t)d.K;
+        g.ldp = pitch8(d.K);
+        g.ldq = pitch8(d.K);
+        g.ldc = pitch32(d.N);
+        g.gsum = gsum + (int64_t)i * 2 * B;
+        g.vmax = vmax + (int64_t)i * 2 * B;
+        g.st_g = B;
+        g.rows_per_sample = (int32_t)d.rps;
+        g.relu = L.relu ? 1 : 0;
+        g.rshift = goodness_shift(d.K, d.rps * d.N);
+        g.nb = 2;
+        HIPCHK(launch_gemm_nt_i8(g, s));
+
+        GoodnessArgs ga;
+        memset(&ga, 0, sizeof(ga));
+        ga.gsum = gsum + (int64_t)i * 2 * B;
+        ga.vmax = vmax + (int64_t)i * 2 * B;
+        ga.s_a = s_a + 2 * i;
+        ga.s_w = state->s_w[i];
+        ga.rshift = g.rshift;
+        ga.l2norm = L.l2norm_out ? 1 : 0;
+        ga.pass_sign = FF_PASS_POS;
+        ga.theta = theta;
+        ga.B = B;
+        ga.goodness = goodness + (int64_t)i * 2 * B;
+        ga.coeff = c + (int64_t)i * 2 * B;
+        ga.loss_mean = loss + 2 * i;
+        ga.next_amax_bits = (i + 1 < k) ? act_amax + 2 * (i + 1) : nullptr;
+        ga.nb = 2;
+        ga.st_b = B;
+        ga.st_scalar = 1;
+        HIPCHK(launch_goodness_loss(ga, s));
+    }
+
+    // ---- look-ahead coefficients of every layer (Eq. (3)/(4)) and the absmax of every local gradient
+    {
+        LookaheadArgs la;
+        memset(&la, 0, sizeof(la));
+        la.coeff = c;
+        la.coeff_total = ct;
+        la.k = k;
+        la.np = 2;
+        la.B = B;
+        la.st_layer = 2 * B;
+        la.st_pass = B;
+        la.lambda = lambda;
+        la.vmax = vmax;
+        la.s_a = s_a;
+        la.s_w = state->s_w;
+        la.g_amax_bits = g_amax;
+        HIPCHK(launch_lookahead(la, s));
+    }
+
+    // ---- per layer: int8 local gradient, int8 weight gradient, update (Algorithm 1, inner loop) ----
+    for (int i = 0; i < k; ++i) {
+        const Dims& d = w.d[i];
+        const ff_layer_desc& L = net->layers[i];
+        QuantArgs a;
+        memset(&a, 0, sizeof(a));
+        a.acc = (const int32_t*)(base + w.off_acc[i]);
+        a.st_acc = (int64_t)(w.st_acc[i] / sizeof(int32_t));
+        a.ldacc = pitch32(d.N);
+        a.s_a = s_a + 2 * i;
+        a.st_s_a = 1;
+        a.s_w = state->s_w[i];
+        a.per_sample = ct + (int64_t)i * 2 * B;
+        a.st_per_sample = B;
+        a.rows_per_sample = (int32_t)d.rps;
+        a.relu = L.relu ? 1 : 0;
+        a.amax_bits = g_amax + 2 * i;
+        a.st_amax = 1;
+        a.round_mode = FF_ROUND_STOCHASTIC;
+        a.key = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 0, FF_KIND_GRAD));
+        a.key2 = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 1, FF_KIND_GRAD));
+        a.rows = d.M;
+        a.cols = d.N;
+        a.q_t = (int8_t*)(base + w.off_gy);
+        a.st_qt = (int64_t)w.st_gy;
+        a.ldqt = pitch8(d.M);
+        a.scale = s_g + 2 * i;
+        a.st_scale = 1;
+        a.nb = 2;
+        HIPCHK(launch_quantize(QSRC_GRAD, a, s));
+
+        GemmArgs g;
+        memset(&g, 0, sizeof(g));
+        g.P = (const int8_t*)(base + w.off_gy);
+        g.st_p = (int64_t)w.st_gy;
+        g.Q = (const int8_t*)(base + w.off_aqt[i]);
+        g.st_q = (int64_t)w.st_aqt[i];
+        g.C = (int32_t*)(base + w.off_dw);
+        g.st_c = (int64_t)(w.st_dw / sizeof(int32_t));
+        g.I = (int32_t)d.N;
+        g.J = (int32_t)d.K;
+        g.R = (int32_t)d.M;
+        g.ldp = pitch8(d.M);
+        g.ldq = pitch8(d.M);
+        g.ldc = pitch32(d.K);
+        g.rows_per_sample = 1;
+        g.nb = 2;
+        HIPCHK(launch_gemm_nt_i8(g, s));
+
+        UpdateArgs u;
+        memset(&u, 0, sizeof(u));
+        u.w = state->w_master[i];
+        u.N = d.N;
+        u.K = d.K;
+        u.lddw = pitch32(d.K);
+        u.n_terms = 2;
+        for (int p = 0; p < 2; ++p) {
+            u.dw[p] = (const int32_t*)(base + w.off_dw + p * w.st_dw);
+            u.s_g[p] = s_g + 2 * i + p;
+            u.s_a[p] = s_a + 2 * i + p;
+        }
+        u.lr = lr;
+        u.total_samples = (int32_t)(2 * B);
+        u.w_amax_bits = w_amax + i;
+        HIPCHK(launch_update(u, s));
+
+        QuantArgs qa;
+        memset(&qa, 0, sizeof(qa));
+        qa.x = state->w_master[i];
+        qa.amax_bits = w_amax + i;
+        qa.round_mode = FF_ROUND_NEAREST_EVEN;
+        qa.rows = d.N;
+        qa.cols = d.K;
+        qa.q = state->w_q[i];
+        qa.ldq = pitch8(d.K);
+        qa.scale = state->s_w[i];
+        qa.nb = 1;
+        qa.rows_per_sample = 1;
+        HIPCHK(launch_quantize(QSRC_F32, qa, s));
+    }
+    return FF_OK;
+}
+
+}  // extern "C"

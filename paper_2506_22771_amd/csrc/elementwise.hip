@@ -1,0 +1,532 @@
+// HBM-bound kernels of the FF-INT8 layer step for gfx950: absmax, the int8 quantiser in its three
+// source flavours (fp32 tensor, hand-off from accumulators, local gradient from accumulators),
+// goodness / loss, look-ahead, and the weight update.
+//
+// Numerics follow the paper's Section IV (symmetric uniform quantiser), Section IV-B (stochastic
+// rounding of the layer input, int8 local gradient), Eq. (1)/(2) (losses) and Eq. (3)/(4)
+// (look-ahead).  Every fp32 operation that decides an int8 code is a single correctly rounded IEEE
+// operation in a fixed order; this file must be compiled with -ffp-contract=off.
+#include "ff_internal.hpp"
+
+namespace ffi {
+
+// ------------------------------------------------------------------------------------------------
+// wavefront (64 lanes) reductions with DPP row operations + readlane across the four rows
+// ------------------------------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+}
+
+// After this every lane of a 16-lane row holds the row's maximum.
+__device__ __forceinline__ uint32_t row_max_u32(uint32_t v)
+{
+    v = max(v, dpp_u32<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = max(v, dpp_u32<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = max(v, dpp_u32<0x141>(v));  // row_half_mirror
+    v = max(v, dpp_u32<0x140>(v));  // row_mirror
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+    v = row_max_u32(v);
+    uint32_t a = __builtin_amdgcn_readlane((int)v, 0), b = __builtin_amdgcn_readlane((int)v, 16);
+    uint32_t c = __builtin_amdgcn_readlane((int)v, 32), d = __builtin_amdgcn_readlane((int)v, 48);
+    return max(max(a, b), max(c, d));
+}
+
+// Block-wide maximum of non-negative values' bit patterns, then one atomic per block.
+template <int THREADS>
+__device__ __forceinline__ void block_atomic_max_bits(uint32_t bits, uint32_t* slot)
+{
+    __shared__ uint32_t red[THREADS / 64];
+    const uint32_t w = wave_max_u32(bits);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = w;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t m = red[0];
+#pragma unroll
+        for (int i = 1; i < THREADS / 64; ++i) m = max(m, red[i]);
+        if (m != 0) atomicMax(slot, m);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// fill
+// ------------------------------------------------------------------------------------------------
+__global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)blocks), dim3(256), 0, s, p, n, v);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// absmax of an fp32 tensor -> bit pattern in *slot (HBM-bound: 4 bytes read per element)
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_absmax_f32(const float* __restrict__ x, int64_t n,
+                                                    uint32_t* __restrict__ slot)
+{
+    // scalar head until 16-byte alignment, float4 body, scalar tail
+    const uintptr_t addr = (uintptr_t)x;
+    int64_t head = (int64_t)(((16 - (addr & 15)) & 15) >> 2);
+    if (head > n) head = n;
+    const int64_t nvec = (n - head) >> 2;
+    const float4* xv = (const float4*)(x + head);
+    const int64_t gtid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t gstride = (int64_t)gridDim.x * 256;
+    uint32_t m = 0;
+    for (int64_t i = gtid; i < nvec; i += gstride) {
+        const float4 v = xv[i];
+        m = max(m, __float_as_uint(v.x) & 0x7FFFFFFFu);
+        m = max(m, __float_as_uint(v.y) & 0x7FFFFFFFu);
+        m = max(m, __float_as_uint(v.z) & 0x7FFFFFFFu);
+        m = max(m, __float_as_uint(v.w) & 0x7FFFFFFFu);
+    }
+    if (gtid < head) m = max(m, __float_as_uint(x[gtid]) & 0x7FFFFFFFu);
+    const int64_t tail0 = head + (nvec << 2);
+    if (tail0 + gtid < n) m = max(m, __float_as_uint(x[tail0 + gtid]) & 0x7FFFFFFFu);
+    block_atomic_max_bits<256>(m, slot);
+}
+
+hipError_t launch_absmax(const float* x, int64_t n, uint32_t* slot, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 256 * 16 - 1) / (256 * 16);
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(k_absmax_f32, dim3((unsigned)blocks), dim3(256), 0, s, x, n, slot);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// quantiser
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t sr_word(uint64_t idx, SrKey key)
+{
+    const uint32_t hi = (uint32_t)(idx >> 32);
+    uint32_t k = key.k0;
+    if (hi) k += hi * key.k1;
+    uint32_t v = (uint32_t)idx ^ k;
+    v ^= v >> 16;
+    v *= 0x7FEB352Du;
+    v ^= v >> 15;
+    v *= 0x846CA68Bu;
+    v ^= v >> 16;
+    return v;
+}
+
+template <bool STOCH>
+__device__ __forceinline__ int quant_code(float v, float inv, uint64_t idx, SrKey key)
+{
+    const float t = v * inv;
+    int code;
+    if (STOCH) {
+        const float f = floorf(t);
+        const float frac = t - f;
+        const float u = (float)(sr_word(idx, key) >> 8) * 0x1p-24f;
+        code = (int)f + (u < frac ? 1 : 0);
+    } else {
+        code = (int)rintf(t);
+    }
+    return min(max(code, -127), 127);
+}
+
+constexpr int QT_ROWS = 128;  // tile rows
+constexpr int QT_COLS = 64;   // tile cols
+constexpr int QT_THREADS = 256;
+constexpr int QT_LDW = QT_ROWS / 4 + 1;  // words per column in the transposed LDS tile (+1: bank spread)
+
+// Each thread owns two 4x4 element blocks (rows 4*rb+j, cols 4*cb+c).  Codes are packed four columns
+// to a word for q, byte-transposed in registers for q_t and regrouped through LDS so that q_t is
+// written in 16-byte pieces.
+template <int SRC, bool STOCH>
+__global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
+{
+    const int z = blockIdx.z;
+    const float* x = a.x ? a.x + z * a.st_x : nullptr;
+    const int32_t* acc = a.acc ? a.acc + z * a.st_acc : nullptr;
+    const float* per_sample = a.per_sample ? a.per_sample + z * a.st_per_sample : nullptr;
+    int8_t* q = a.q ? a.q + z * a.st_q : nullptr;
+    int8_t* q_t = a.q_t ? a.q_t + z * a.st_qt : nullptr;
+    const SrKey key = z ? a.key2 : a.key;
+
+    const float amax = __uint_as_float(a.amax_bits[z * a.st_amax]);
+    const float inv = amax > 0.0f ? 127.0f / amax : 0.0f;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+        a.scale[z * a.st_scale] = amax > 0.0f ? amax / 127.0f : 1.0f;
+
+    float s_y = 1.0f;
+    if (SRC != QSRC_F32) s_y = a.s_a[z * a.st_s_a] * a.s_w[z * a.st_s_w];
+
+    const int64_t r0 = (int64_t)blockIdx.y * QT_ROWS;
+    const int64_t c0 = (int64_t)blockIdx.x * QT_COLS;
+    const int t = threadIdx.x;
+    const int cb = t & 15;
+    const int64_t col = c0 + 4 * cb;
+    const bool vec_ok = (SRC != QSRC_F32) || (((a.cols & 3) == 0) && ((((uintptr_t)x) & 15) == 0));
+
+    __shared__ uint32_t tileT[QT_COLS * QT_LDW];
+
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int rb = (t >> 4) + 16 * u;
+        uint32_t rowpack[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t row = r0 + 4 * rb + j;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            bool ok[4] = {false, false, false, false};
+            if (row < a.rows && col < a.cols) {
+                float rs = 1.0f;  // per-row factor
+                bool zero_row = false;
+                if (SRC == QSRC_GRAD) rs = 2.0f * per_sample[row / a.rows_per_sample];
+                if (SRC == QSRC_HANDOFF && a.l2norm) {
+                    rs = sqrtf(per_sample[row / a.rows_per_sample]);
+                    zero_row = !(rs > 0.0f);
+                }
+                float raw[4];
+                if (SRC == QSRC_F32) {
+                    const float* px = x + row * a.cols + col;
+                    if (vec_ok) {
+                        const float4 f = *(const float4*)px;
+                        raw[0] = f.x; raw[1] = f.y; raw[2] = f.z; raw[3] = f.w;
+                        ok[0] = ok[1] = ok[2] = ok[3] = true;
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            ok[c] = col + c < a.cols;
+                            raw[c] = ok[c] ? px[c] : 0.0f;
+                        }
+                    }
+                } else {
+                    const int4 iv = *(const int4*)(acc + row * a.ldacc + col);  // pitch is a multiple of 4
+                    raw[0] = (float)iv.x; raw[1] = (float)iv.y; raw[2] = (float)iv.z; raw[3] = (float)iv.w;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) ok[c] = col + c < a.cols;
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    float y = raw[c];
+                    if (SRC != QSRC_F32) {
+                        y = y * s_y;
+                        if (a.relu) y = fmaxf(y, 0.0f);
+                        if (SRC == QSRC_HANDOFF) {
+                            if (a.l2norm) y = zero_row ? 0.0f : y / rs;
+                        } else {
+                            y = rs * y;
+                        }
+                    }
+                    v[c] = y;
+                }
+            }
+            uint32_t pack = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                int code = 0;
+                if (ok[c]) code = quant_code<STOCH>(v[c], inv, (uint64_t)row * (uint64_t)a.cols + (uint64_t)(col + c), key);
+                pack |= ((uint32_t)code & 0xFFu) << (8 * c);
+            }
+            rowpack[j] = pack;
+            if (q && row < a.rows && col < a.ldq) *(uint32_t*)(q + row * a.ldq + col) = pack;
+        }
+        if (q_t) {
+            // 4x4 byte transpose: colpack[c] = byte c of rowpack[0..3]
+            const uint32_t t0 = __builtin_amdgcn_perm(rowpack[1], rowpack[0], 0x05010400u);
+            const uint32_t t1 = __builtin_amdgcn_perm(rowpack[1], rowpack[0], 0x07030602u);
+            const uint32_t t2 = __builtin_amdgcn_perm(rowpack[3], rowpack[2], 0x05010400u);
+            const uint32_t t3 = __builtin_amdgcn_perm(rowpack[3], rowpack[2], 0x07030602u);
+            tileT[(4 * cb + 0) * QT_LDW + rb] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
+            tileT[(4 * cb + 1) * QT_LDW + rb] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+            tileT[(4 * cb + 2) * QT_LDW + rb] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
+            tileT[(4 * cb + 3) * QT_LDW + rb] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
+        }
+    }
+    if (q_t) {
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int e = t + QT_THREADS * u;
+            const int cl = e >> 3, ch = e & 7;
+            const int64_t oc = c0 + cl;
+            const int64_t orow = r0 + 16 * ch;
+            if (oc < a.cols && orow < a.ldqt) {
+                int4 o;
+                o.x = (int)tileT[cl * QT_LDW + 4 * ch + 0];
+                o.y = (int)tileT[cl * QT_LDW + 4 * ch + 1];
+                o.z = (int)tileT[cl * QT_LDW + 4 * ch + 2];
+                o.w = (int)tileT[cl * QT_LDW + 4 * ch + 3];
+                *(int4*)(q_t + oc * a.ldqt + orow) = o;
+            }
+        }
+    }
+}
+
+hipError_t launch_quantize(int src, const QuantArgs& a, hipStream_t s)
+{
+    const dim3 block(QT_THREADS);
+    const dim3 grid((unsigned)((a.cols + QT_COLS - 1) / QT_COLS), (unsigned)((a.rows + QT_ROWS - 1) / QT_ROWS),
+                    (unsigned)a.nb);
+    if (a.rows <= 0 || a.cols <= 0) return hipSuccess;
+    const bool st = a.round_mode == FF_ROUND_STOCHASTIC;
+    switch (src) {
+        case QSRC_F32:
+            if (st) hipLaunchKernelGGL((k_quantize<QSRC_F32, true>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((k_quantize<QSRC_F32, false>), grid, block, 0, s, a);
+            break;
+        case QSRC_HANDOFF:
+            if (st) hipLaunchKernelGGL((k_quantize<QSRC_HANDOFF, true>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((k_quantize<QSRC_HANDOFF, false>), grid, block, 0, s, a);
+            break;
+        default:
+            if (st) hipLaunchKernelGGL((k_quantize<QSRC_GRAD, true>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((k_quantize<QSRC_GRAD, false>), grid, block, 0, s, a);
+            break;
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// goodness, loss, dL/dG, absmax of the hand-off tensor: one workgroup per pass, fixed reduction order
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float exp_nonpos(float z)
+{
+    // exp(z) for z <= 0 with a fixed operation sequence (it feeds the gradient quantiser through the sigmoid)
+    z = fmaxf(z, -87.0f);
+    z = fminf(z, 0.0f);
+    const float kf = rintf(z * 0x1.715476p+0f);
+    float r = __builtin_fmaf(-kf, 0x1.62e4p-1f, z);
+    r = __builtin_fmaf(-kf, 0x1.7f7d1cp-20f, r);
+    float p = 0x1.a01a02p-13f;
+    p = __builtin_fmaf(p, r, 0x1.6c16c2p-10f);
+    p = __builtin_fmaf(p, r, 0x1.111112p-7f);
+    p = __builtin_fmaf(p, r, 0x1.555556p-5f);
+    p = __builtin_fmaf(p, r, 0x1.555556p-3f);
+    p = __builtin_fmaf(p, r, 0.5f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    p = __builtin_fmaf(p, r, 1.0f);
+    return ldexpf(p, (int)kf);
+}
+
+constexpr int GL_THREADS = 1024;
+
+__global__ __launch_bounds__(GL_THREADS) void k_goodness_loss(GoodnessArgs a)
+{
+    const int z = blockIdx.x;
+    const unsigned long long* gsum = a.gsum + z * a.st_b;
+    const int32_t* vmax = a.vmax + z * a.st_b;
+    float* goodness = a.goodness + z * a.st_b;
+    float* coeff = a.coeff + z * a.st_b;
+    const int sign = z ? -a.pass_sign : a.pass_sign;
+    const float s_y = a.s_a[z * a.st_scalar] * a.s_w[0];
+    const double s_yd = (double)s_y;
+    const double pow2r = (double)(1ull << a.rshift);
+
+    double lsum = 0.0;
+    uint32_t amax_bits = 0;
+    for (int64_t b = threadIdx.x; b < a.B; b += GL_THREADS) {
+        double g = (double)gsum[b];
+        g = g * pow2r;
+        g = g * s_yd;
+        g = g * s_yd;
+        const float G = (float)g;
+        goodness[b] = G;
+        const float x = G - a.theta;
+        const float e = exp_nonpos(-fabsf(x));
+        const float den = 1.0f + e;
+        const float sig_big = 1.0f / den;
+        const float sig_small = e / den;
+        float c;
+        double xd;
+        if (sign > 0) {
+            c = -(x >= 0.0f ? sig_small : sig_big);
+            xd = -(double)x;
+        } else {
+            c = (x >= 0.0f ? sig_big : sig_small);
+            xd = (double)x;
+        }
+        coeff[b] = c;
+        lsum += (xd > 0.0 ? xd : 0.0) + log1p(exp(-fabs(xd)));
+        if (a.next_amax_bits) {
+            float ymax = (float)vmax[b] * s_y;
+            if (a.l2norm) {
+                const float nrm = sqrtf(G);
+                ymax = nrm > 0.0f ? ymax / nrm : 0.0f;
+            }
+            amax_bits = max(amax_bits, __float_as_uint(ymax));
+        }
+    }
+    __shared__ double red[GL_THREADS];
+    __shared__ uint32_t redm[GL_THREADS];
+    red[threadIdx.x] = lsum;
+    redm[threadIdx.x] = amax_bits;
+    __syncthreads();
+    for (int s = GL_THREADS / 2; s > 0; s >>= 1) {
+        if (threadIdx.x < s) {
+            red[threadIdx.x] += red[threadIdx.x + s];
+            redm[threadIdx.x] = max(redm[threadIdx.x], redm[threadIdx.x + s]);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        a.loss_mean[z * a.st_scalar] = a.B > 0 ? (float)(red[0] / (double)a.B) : 0.0f;
+        if (a.next_amax_bits) a.next_amax_bits[z * a.st_scalar] = redm[0];
+    }
+}
+
+hipError_t launch_goodness_loss(const GoodnessArgs& a, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_goodness_loss, dim3((unsigned)a.nb), dim3(GL_THREADS), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// look-ahead (Eq. (3)/(4)): per sample, walk the layers from the last to the first
+// ------------------------------------------------------------------------------------------------
+struct LookaheadKArgs {
+    LookaheadArgs a;
+    const float* s_w[32];
+};
+
+__global__ __launch_bounds__(256) void k_lookahead(LookaheadKArgs ka)
+{
+    const LookaheadArgs& a = ka.a;
+    const int p = blockIdx.y;
+    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool live = b < a.B;
+    float S = 0.0f;
+    for (int i = a.k - 1; i >= 0; --i) {
+        const int64_t off = i * a.st_layer + p * a.st_pass + (live ? b : 0);
+        const float c = live ? a.coeff[off] : 0.0f;
+        const float ct = __builtin_fmaf(a.lambda, S, c);
+        S = S + c;
+        if (live) a.coeff_total[off] = ct;
+        if (a.vmax) {
+            uint32_t bits = 0;
+            if (live) {
+                const float s_y = a.s_a[i * a.np + p] * ka.s_w[i][0];
+                const float ymax = (float)a.vmax[off] * s_y;
+                bits = __float_as_uint(fabsf(2.0f * ct) * ymax);
+            }
+            bits = wave_max_u32(bits);
+            if ((threadIdx.x & 63) == 0 && bits) atomicMax(a.g_amax_bits + i * a.np + p, bits);
+        }
+    }
+}
+
+hipError_t launch_lookahead_impl(const LookaheadArgs& a, const float* const* s_w_host, hipStream_t s)
+{
+    LookaheadKArgs ka;
+    ka.a = a;
+    for (int i = 0; i < 32; ++i) ka.s_w[i] = (s_w_host && i < a.k) ? s_w_host[i] : nullptr;
+    hipLaunchKernelGGL(k_lookahead, dim3((unsigned)((a.B + 255) / 256), (unsigned)a.np), dim3(256), 0, s, ka);
+    return hipGetLastError();
+}
+
+hipError_t launch_lookahead(const LookaheadArgs& a, hipStream_t s)
+{
+    // a.s_w is a HOST array of device pointers here; they travel in the kernel argument block
+    return launch_lookahead_impl(a, a.s_w, s);
+}
+
+__global__ __launch_bounds__(1024) void k_grad_amax(const float* __restrict__ ct, const int32_t* __restrict__ vmax,
+                                                    const float* __restrict__ s_a, const float* __restrict__ s_w,
+                                                    int64_t B, uint32_t* __restrict__ slot)
+{
+    const float s_y = s_a[0] * s_w[0];
+    uint32_t bits = 0;
+    for (int64_t b = threadIdx.x; b < B; b += 1024) {
+        const float ymax = (float)vmax[b] * s_y;
+        bits = max(bits, __float_as_uint(fabsf(2.0f * ct[b]) * ymax));
+    }
+    __shared__ uint32_t red[16];
+    bits = wave_max_u32(bits);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = bits;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t m = 0;
+        for (int i = 0; i < 16; ++i) m = max(m, red[i]);
+        *slot = m;
+    }
+}
+
+hipError_t launch_grad_amax(const float* ct, const int32_t* vmax, const float* s_a, const float* s_w, int64_t B,
+                            uint32_t* slot, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_grad_amax, dim3(1), dim3(1024), 0, s, ct, vmax, s_a, s_w, B, slot);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// weight update (HBM-bound: 4 B x (1 + n_terms) read + 4 B written per weight) with fused absmax
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_update(UpdateArgs a)
+{
+    float sc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) sc[j] = j < a.n_terms ? a.s_g[j][0] * a.s_a[j][0] : 0.0f;
+    const float lr_eff = a.lr / (float)a.total_samples;
+    const int64_t kq = (a.K + 3) >> 2;  // groups of four columns per row
+    const int64_t total = a.N * kq;
+    const bool vec = (a.K & 3) == 0 && ((((uintptr_t)a.w) & 15) == 0);
+    uint32_t m = 0;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int64_t n = e / kq, k = (e - n * kq) << 2;
+        float* pw = a.w + n * a.K + k;
+        const int cnt = (int)min((int64_t)4, a.K - k);
+        float w[4] = {0.f, 0.f, 0.f, 0.f};
+        if (vec) {
+            const float4 f = *(const float4*)pw;
+            w[0] = f.x; w[1] = f.y; w[2] = f.z; w[3] = f.w;
+        } else {
+            for (int c = 0; c < cnt; ++c) w[c] = pw[c];
+        }
+        float g[4];
+        {
+            const int4 d = *(const int4*)(a.dw[0] + n * a.lddw + k);
+            g[0] = (float)d.x * sc[0]; g[1] = (float)d.y * sc[0]; g[2] = (float)d.z * sc[0]; g[3] = (float)d.w * sc[0];
+        }
+        for (int j = 1; j < a.n_terms; ++j) {
+            const int4 d = *(const int4*)(a.dw[j] + n * a.lddw + k);
+            g[0] = __builtin_fmaf((float)d.x, sc[j], g[0]);
+            g[1] = __builtin_fmaf((float)d.y, sc[j], g[1]);
+            g[2] = __builtin_fmaf((float)d.z, sc[j], g[2]);
+            g[3] = __builtin_fmaf((float)d.w, sc[j], g[3]);
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) w[c] = __builtin_fmaf(-lr_eff, g[c], w[c]);
+        if (vec) {
+            *(float4*)pw = make_float4(w[0], w[1], w[2], w[3]);
+            for (int c = 0; c < 4; ++c) m = max(m, __float_as_uint(w[c]) & 0x7FFFFFFFu);
+        } else {
+            for (int c = 0; c < cnt; ++c) {
+                pw[c] = w[c];
+                m = max(m, __float_as_uint(w[c]) & 0x7FFFFFFFu);
+            }
+        }
+    }
+    block_atomic_max_bits<256>(m, a.w_amax_bits);
+}
+
+hipError_t launch_update(const UpdateArgs& a, hipStream_t s)
+{
+    const int64_t total = a.N * ((a.K + 3) >> 2);
+    if (total <= 0) return hipSuccess;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_update, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace ffi

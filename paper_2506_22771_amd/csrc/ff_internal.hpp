@@ -1,0 +1,132 @@
+// Internal declarations shared by the HIP translation units of libffint8 (gfx950 only).
+// Host-side launchers are declared here; each is defined next to its kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/ffint8.h"
+
+namespace ffi {
+
+// ---- layout helpers -------------------------------------------------------------------------
+static inline int64_t pitch8(int64_t cols) { return (cols + 15) & ~int64_t(15); }
+static inline int64_t pitch32(int64_t cols) { return (cols + 3) & ~int64_t(3); }
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- stochastic-rounding key (Section IV-B cites stochastic rounding; the generator is ours) --
+struct SrKey {
+    uint32_t k0;  // low word of the 64-bit key
+    uint32_t k1;  // (high word | 1), multiplies the high half of the element index
+};
+SrKey make_sr_key(uint64_t seed, uint64_t tag);
+
+// ---- quantise kernels (elementwise.hip) -----------------------------------------------------
+enum QSource { QSRC_F32 = 0, QSRC_HANDOFF = 1, QSRC_GRAD = 2 };
+
+// One quantisation problem; `nb` problems (1 or 2) are launched together with the strides below.
+struct QuantArgs {
+    // source
+    const float* x;          // QSRC_F32: [rows, cols] contiguous
+    const int32_t* acc;      // QSRC_HANDOFF / QSRC_GRAD: [rows, ldacc]
+    int64_t ldacc;
+    const float* s_a;        // device scalars (HANDOFF / GRAD)
+    const float* s_w;
+    const float* per_sample; // HANDOFF with l2norm: goodness[B]; GRAD: coeff_total[B]
+    int32_t rows_per_sample;
+    int32_t relu, l2norm;
+    // quantiser
+    const uint32_t* amax_bits;  // device: bit pattern of the non-negative fp32 absmax
+    int32_t round_mode;
+    SrKey key;
+    // destination
+    int64_t rows, cols;
+    int8_t* q;    // [rows, ldq] or null
+    int64_t ldq;
+    int8_t* q_t;  // [cols, ldqt] or null
+    int64_t ldqt;
+    float* scale;  // device scalar out
+    // batching (second problem = first + strides, in elements of the respective type)
+    int32_t nb;
+    int64_t st_x, st_acc, st_per_sample, st_q, st_qt;
+    int32_t st_s_a, st_s_w, st_amax, st_scale;
+    SrKey key2;  // key of the second problem
+};
+hipError_t launch_quantize(int src, const QuantArgs& a, hipStream_t s);
+
+// absmax of |x| over n floats into *slot (bit pattern, atomic max; slot must be zeroed first).
+hipError_t launch_absmax(const float* x, int64_t n, uint32_t* slot, hipStream_t s);
+hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s);
+
+// ---- per-sample kernels ----------------------------------------------------------------------
+struct GoodnessArgs {
+    const unsigned long long* gsum;
+    const int32_t* vmax;
+    const float* s_a;
+    const float* s_w;
+    int32_t rshift, l2norm;
+    int32_t pass_sign;  // sign of the first problem; the second problem (nb == 2) uses the opposite
+    float theta;
+    int64_t B;
+    float* goodness;
+    float* coeff;
+    float* loss_mean;
+    uint32_t* next_amax_bits;  // may be null
+    int32_t nb;
+    int64_t st_b;  // stride between problems for the [B] arrays
+    int32_t st_scalar;  // stride for s_a / loss_mean / next_amax (s_w is shared)
+};
+hipError_t launch_goodness_loss(const GoodnessArgs& a, hipStream_t s);
+
+// coeff / coeff_total: [k][np][B] with strides; also (optionally) the absmax of each layer's local gradient.
+struct LookaheadArgs {
+    const float* coeff;
+    float* coeff_total;
+    int32_t k, np;
+    int64_t B;
+    int64_t st_layer, st_pass;
+    float lambda;
+    // optional gradient absmax (null vmax => skipped)
+    const int32_t* vmax;       // same [k][np][B] strides
+    const float* s_a;          // [k][np]
+    const float* const* s_w;   // device array of k pointers to the layers' weight scales (may be null if vmax null)
+    uint32_t* g_amax_bits;     // [k][np], zeroed
+};
+hipError_t launch_lookahead(const LookaheadArgs& a, hipStream_t s);
+
+// absmax of the local gradient for one layer / pass: max_b |2 c[b]| * (float(vmax[b]) * s_y) -> slot bits.
+hipError_t launch_grad_amax(const float* coeff_total, const int32_t* vmax, const float* s_a,
+                            const float* s_w, int64_t B, uint32_t* slot, hipStream_t s);
+
+struct UpdateArgs {
+    float* w;  // [N, K] contiguous
+    int64_t N, K, lddw;
+    int32_t n_terms;  // <= 4
+    const int32_t* dw[4];
+    const float* s_g[4];
+    const float* s_a[4];
+    float lr;
+    int32_t total_samples;
+    uint32_t* w_amax_bits;  // zeroed slot
+};
+hipError_t launch_update(const UpdateArgs& a, hipStream_t s);
+
+// ---- int8 contraction (gemm_i8.hip):  C[i][j] = sum_r P[i][r] * Q[j][r] -----------------------
+struct GemmArgs {
+    const int8_t* P;  // [I, ldp]
+    const int8_t* Q;  // [J, ldq]
+    int32_t* C;       // [I, ldc]
+    int32_t I, J, R;  // R = reduction length in bytes (pad bytes beyond it are zero)
+    int64_t ldp, ldq, ldc;
+    // fused per-sample reductions (forward only; null gsum => plain contraction)
+    unsigned long long* gsum;
+    int32_t* vmax;
+    int32_t rows_per_sample, relu, rshift;
+    // batching over blockIdx.z
+    int32_t nb;
+    int64_t st_p, st_q, st_c, st_g;
+};
+hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s);
+
+}  // namespace ffi

@@ -1,0 +1,92 @@
+"""CPU-side checks of the boundary: the built library loads, exports every symbol the header
+declares, and rejects bad arguments on the host before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def ff():
+    import paper_2506_22771_amd as m
+    try:
+        m.lib()
+    except FileNotFoundError:
+        import __graft_entry__ as g
+        g.build()
+        m.lib()
+    return m
+
+
+def test_every_declared_symbol_is_exported(ff):
+    text = open(os.path.join(ROOT, "include", "ffint8.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(ff_[a-z0-9_]+)\s*\(", text)))
+    assert {"ff_quantize", "ff_layer_forward", "ff_goodness_loss", "ff_layer_backward_local", "ff_layer_update",
+            "ff_train_step"} <= set(names)
+    L = ff.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_pitch_and_tags(ff):
+    assert [ff.ff_pitch(c) for c in (0, 1, 16, 17, 500, 4096)] == [0, 16, 16, 32, 512, 4096]
+    assert [ff.ff_pitch32(c) for c in (0, 1, 4, 5, 500)] == [0, 4, 4, 8, 500]
+    from oracle import ff_oracle as O
+    for args in [(0, 0, 0, 0), (3, 2, 1, 1), (1000, 19, 0, 1)]:
+        assert ff.ff_stream_tag(*args) == O.stream_tag(*args)
+    assert ff.ff_status_string(0) == "ok" and "workspace" in ff.ff_status_string(-4)
+
+
+def test_goodness_shift_matches_big_integer_bound(ff):
+    from workloads import Layer
+    for K, N in [(784, 500), (4096, 4096), (100, 72), (133144, 8)]:
+        d = ff.layer_desc(Layer("dense", in_features=K, out_features=N), 8)
+        r = ff.ff_goodness_shift(d)
+        worst = (16129 * K) ** 2 * N
+        assert (worst >> r) < 2 ** 64 and (r == 0 or (worst >> (r - 1)) >= 2 ** 64)
+
+
+def test_argument_errors_are_host_side(ff):
+    """Null pointers, bad enums, bad shapes, misalignment and a short workspace are reported as status
+    codes before any launch (this runs without a GPU)."""
+    L = ff.lib()
+    from workloads import Layer
+    d = ff.layer_desc(Layer("dense", in_features=32, out_features=16), 8)
+    P = C.c_void_p
+    fake = P(0x1000)        # never dereferenced: validation fails first
+    assert L.ff_quantize(P(0), 4, 4, 1, 0, 0, fake, P(0), P(0), fake, 4096, P(0)) == -1       # scale null
+    assert L.ff_quantize(fake, 4, 4, 7, 0, 0, fake, P(0), fake, fake, 4096, P(0)) == -1       # bad rounding mode
+    assert L.ff_quantize(fake, 4, 4, 1, 0, 0, fake, P(0), fake, fake, 16, P(0)) == -4         # workspace
+    assert L.ff_quantize(fake, 4, 4, 1, 0, 0, P(0x1008), P(0), fake, fake, 4096, P(0)) == -3  # alignment
+    assert L.ff_quantize(fake, -1, 4, 1, 0, 0, fake, P(0), fake, fake, 4096, P(0)) == -1
+    assert L.ff_layer_forward(C.byref(d), P(0), fake, fake, fake, fake, fake, 4096, P(0)) == -1
+    bad = ff.layer_desc(Layer("dense", in_features=0, out_features=16), 8)
+    assert L.ff_layer_forward(C.byref(bad), fake, fake, fake, fake, fake, fake, 4096, P(0)) == -2
+    long = ff.layer_desc(Layer("dense", in_features=133145, out_features=16), 8)
+    assert L.ff_layer_forward(C.byref(long), fake, fake, fake, fake, fake, fake, 4096, P(0)) == -5
+    assert L.ff_goodness_loss(C.byref(d), fake, fake, fake, fake, 0, 2.0, fake, fake, fake, P(0), P(0)) == -1
+    assert L.ff_lookahead(fake, 0, 8, 0.1, fake, P(0)) == -2
+    assert L.ff_lookahead(fake, 33, 8, 0.1, fake, P(0)) == -2
+    assert L.ff_layer_update(C.byref(d), fake, fake, fake, fake, fake, fake, fake, 0.1, 0, fake, fake, fake, 4096,
+                             P(0)) == -1
+    assert L.ff_workspace_bytes(None) == 0
+
+
+def test_workspace_bytes_and_train_step_validation(ff):
+    from workloads import workload
+    import ctypes as C
+    wl = workload("cfg1")
+    descs = (ff.binding.LayerDesc * 2)(*[ff.layer_desc(l, wl.batch) for l in wl.layers])
+    net = ff.binding.NetDesc(2, wl.batch, descs)
+    n = ff.lib().ff_workspace_bytes(C.byref(net))
+    # at least the retained int32 accumulators and transposed int8 inputs of both layers, both passes
+    need = 2 * sum(wl.batch * l.N * 4 + l.K * ff.ff_pitch(wl.batch) for l in wl.layers)
+    scratch = 2 * max(l.N * l.K * 4 + wl.batch * ff.ff_pitch(l.K) + l.N * ff.ff_pitch(wl.batch) for l in wl.layers)
+    assert need + scratch <= n < 2 * (need + scratch) + (1 << 20)
+    mism = (ff.binding.LayerDesc * 2)(ff.layer_desc(wl.layers[0], wl.batch), ff.layer_desc(wl.layers[0], wl.batch))
+    assert ff.lib().ff_workspace_bytes(C.byref(ff.binding.NetDesc(2, wl.batch, mism))) == 0   # 500 != 784
+    assert ff.lib().ff_train_step(C.byref(net), None, None, None, 2.0, 0.0, 0.1, 0, 0, None, None, None, 0, None) == -1

@@ -368,13 +368,20 @@ int ffo_dense_wgrad(const int8_t *gy_q, const int8_t *a_q, int64_t M, int64_t K,
     int bad = 0;
 #pragma omp parallel for schedule(static) reduction(| : bad)
     for (int64_t n = 0; n < N; ++n) {
-        for (int64_t k = 0; k < K; ++k) {
-            int64_t s = 0;
-            for (int64_t m = 0; m < M; ++m) s += (int32_t)gy_q[m * N + n] * (int32_t)a_q[m * K + k];
-            if (s > INT32_MAX || s < INT32_MIN) bad |= 1;
-            dw[n * K + k] = (int32_t)s;
+        /* row n of dw: sum over m of gy_q[m][n] * (row m of a_q), in exact 64-bit integers */
+        int64_t *row = (int64_t *)calloc((size_t)(K > 0 ? K : 1), sizeof(int64_t));
+        if (!row) { bad |= 2; continue; }
+        for (int64_t m = 0; m < M; ++m) {
+            const int32_t g = (int32_t)gy_q[m * N + n];
+            for (int64_t k = 0; k < K; ++k) row[k] += g * (int32_t)a_q[m * K + k];
         }
+        for (int64_t k = 0; k < K; ++k) {
+            if (row[k] > INT32_MAX || row[k] < INT32_MIN) bad |= 1;
+            dw[n * K + k] = (int32_t)row[k];
+        }
+        free(row);
     }
+    if (bad & 2) return FFO_ERR_ARG;
     return bad ? FFO_ERR_OVERFLOW : FFO_OK;
 }
 

@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the FF-INT8 layer-local train step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg2|cfg1] [--no-cpu-baseline]
+
+A "step" is one ff_train_step: one iteration of the paper's Algorithm 1 over one synthetic batch
+(positive + negative set, all layers: quantise, int8 forward, goodness/loss, look-ahead, int8 local
+gradient, int8 weight gradient, update).  Inputs and weights are resident in HBM before the timed
+region starts.  One JSON line is printed.
+
+metric: FF-INT8 train samples/s per layer step = (B_pos + B_neg) * n_layers / step time, i.e. the rate
+at which samples pass through one layer's complete step.  `roofline` scores the dominant kernel (the
+int8 MFMA contraction, forward and weight-gradient launches together) from HIP events recorded on
+the launch stream during the timed steps.  `cpu_baseline` times the CPU oracle on a bounded sample
+(a smaller batch of the same network).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 256 * 2.4e9 * 8192 / 1e12   # 256 CUs x 2.4 GHz x 8192 int8 ops/CU/clk = 5033 TOP/s
+HBM_PEAK_GBS = 8000.0
+
+
+def setup(ff, torch, wl):
+    from workloads import make_inputs, make_weights
+    W = make_weights(wl)
+    xp, xn = make_inputs(wl)
+    B, k = wl.batch, len(wl.layers)
+    d_w = [torch.from_numpy(w.reshape(w.shape[0], -1)).cuda() for w in W]
+    d_wq = [torch.zeros((l.N, ff.ff_pitch(l.K)), dtype=torch.int8, device="cuda") for l in wl.layers]
+    d_sw = [torch.zeros(1, device="cuda") for _ in wl.layers]
+    ws1 = torch.empty(ff.WS_MIN_BYTES, dtype=torch.uint8, device="cuda")
+    for i, l in enumerate(wl.layers):
+        ff.ff_quantize(d_w[i], l.N, l.K, ff.ROUND_NEAREST, 0, 0, d_wq[i], None, d_sw[i], ws1)
+    net = ff.Net(wl.layers, B, d_w, d_wq, d_sw)
+    ws = torch.empty(net.workspace_bytes(), dtype=torch.uint8, device="cuda")
+    loss = torch.empty((k, 2), device="cuda")
+    good = torch.empty((k, 2, B), device="cuda")
+    d_xp = torch.from_numpy(xp.reshape(B, -1)).cuda()
+    d_xn = torch.from_numpy(xn.reshape(B, -1)).cuda()
+    return net, d_xp, d_xn, loss, good, ws
+
+
+def cpu_baseline(wl, sample_batch: int):
+    """The CPU oracle as it stands, timed on this host, on a smaller batch of the same network."""
+    from oracle import ff_oracle as O
+    from workloads import make_inputs, make_weights, scaled
+    small = scaled(wl, sample_batch)
+    W = make_weights(small)
+    xp, xn = make_inputs(small)
+    O.lib()
+    t0 = time.perf_counter()
+    O.train_step(small.layers, W, xp, xn, small.theta, small.lam, small.lr, small.sr_seed, 0, keep=False)
+    dt = time.perf_counter() - t0
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    omp = os.environ.get("OMP_NUM_THREADS")
+    if omp:
+        cores = min(cores, int(omp))
+    k = len(small.layers)
+    return {"value": 2 * sample_batch * k / dt, "unit": "samples/s per layer step", "cores": cores,
+            "kind": "oracle", "seconds": dt,
+            "sample": f"one oracle train step of {wl.name} at batch {sample_batch}+{sample_batch} "
+                      f"(full batch is {wl.batch}+{wl.batch}); rate is per sample, so it carries over"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg5")
+    ap.add_argument("--cpu-sample-batch", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives are part of it); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2506_22771_amd as ff
+    from workloads import workload
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    ff.lib()
+    torch.cuda.set_device(0)
+    wl = workload(args.workload)
+    net, d_xp, d_xn, loss, good, ws = setup(ff, torch, wl)
+    k, B = len(wl.layers), wl.batch
+
+    step_no = 0
+    for _ in range(args.warmup):
+        ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, step_no, loss, good, ws)
+        step_no += 1
+    torch.cuda.synchronize()
+    ff.ff_timing_reset()
+    ff.ff_timing_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, step_no, loss, good, ws)
+        step_no += 1
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ff.ff_timing_enable(False)
+    ms_per_step = dt / args.steps * 1e3
+    samples = 2 * B
+
+    kern = {}
+    for ci, name in enumerate(ff.KERNEL_CLASSES):
+        ms, n = ff.ff_timing_read(ci)
+        kern[name] = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps}
+
+    # dominant kernel: the int8 contraction (forward + weight-gradient launches; each launch covers both passes)
+    gemm_ms = kern["gemm_fwd"]["ms_per_step"] + kern["gemm_dw"]["ms_per_step"]
+    gemm_launches = kern["gemm_fwd"]["launches_per_step"] + kern["gemm_dw"]["launches_per_step"]
+    ops_per_step = sum(2.0 * 2 * B * l.rows_per_sample * l.K * l.N * 2 for l in wl.layers)  # fwd + dW, both passes
+    ops_per_launch = ops_per_step / max(gemm_launches, 1)
+    avg_launch_ms = gemm_ms / max(gemm_launches, 1)
+    achieved = ops_per_launch / (avg_launch_ms * 1e-3) / 1e12 if avg_launch_ms > 0 else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{wl.name}.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("gemm_bytes_per_launch")
+        except Exception:
+            traffic = None
+    roofline = {"bound": "mfma", "kernel": "k_gemm_nt_i8 (forward and weight-gradient launches)",
+                "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": traffic,
+                "ops_per_launch": ops_per_launch, "avg_launch_ms": avg_launch_ms,
+                "fwd_TOPs": (ops_per_step / 2) / (kern["gemm_fwd"]["ms_per_step"] * 1e-3) / 1e12
+                if kern["gemm_fwd"]["ms_per_step"] > 0 else 0.0,
+                "dw_TOPs": (ops_per_step / 2) / (kern["gemm_dw"]["ms_per_step"] * 1e-3) / 1e12
+                if kern["gemm_dw"]["ms_per_step"] > 0 else 0.0}
+
+    out = {
+        "metric": "FF-INT8 train samples/sec per layer step; int8 MFMA TOPS as % of peak",
+        "value": samples * k / (ms_per_step * 1e-3),
+        "unit": "samples/s per layer step",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 (int32 accumulate; fp32 scales, goodness, master weights)", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": [f"{l.K}->{l.N}" for l in wl.layers],
+                   "batch_pos": B, "batch_neg": B, "lambda": wl.lam, "theta": wl.theta, "lr": wl.lr,
+                   "layer_steps_per_step": k, "whole_step_samples_per_s": samples / (ms_per_step * 1e-3),
+                   "int8_TOPs_whole_step": ops_per_step / (ms_per_step * 1e-3) / 1e12},
+        "int8_mfma_pct_of_peak": 100.0 * achieved / INT8_MFMA_PEAK_TOPS,
+        "roofline": roofline,
+        "kernels_ms_per_step": {n: round(v["ms_per_step"], 5) for n, v in kern.items()},
+        "paper_context": "Jetson Orin Nano, whole training runs: 4.6% faster, 8.3% less energy, 27.0% less memory "
+                         "than BP-GDAI8 (Table V); no per-step figure is published",
+    }
+    if not args.no_cpu_baseline:
+        sb = args.cpu_sample_batch or {"cfg5": 2048, "cfg2": 1024, "cfg1": 64}.get(wl.name, min(B, 256))
+        out["cpu_baseline"] = cpu_baseline(wl, min(sb, B))
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -110,7 +110,7 @@ const char* ff_version(void);
  *   q      [rows, ff_pitch(cols)] int8 (out, may be NULL)
  *   q_t    [cols, ff_pitch(rows)] int8, the transposed copy the weight-gradient contraction reads
  *          (out, may be NULL; at least one of q, q_t must be given)
- *   scale  one fp32 (out): absmax/127, or 1 when the tensor is all zero
+ *   scale  one fp32 (out): absmax/127, or 1 when absmax < 2^-100 (all codes are then 0)
  * codes = clamp(round(x * (127/absmax)), -127, 127).  Stochastic rounding draws one uniform per
  * element from a counter-based generator keyed by (seed, stream_tag, row*cols+col).
  * rows*cols == 0 is accepted (scale = 1).  ws: >= FF_WS_MIN_BYTES of scratch.
@@ -222,6 +222,29 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
 
 /* Bytes of workspace ff_train_step needs for `net`; 0 if the descriptor is invalid. [host only] */
 size_t ff_workspace_bytes(const ff_net_desc* net);
+
+/* ---------------------------------------------------------------------------------------------
+ * Instrumentation (not part of the method).  When enabled, every kernel launch of the library is
+ * bracketed by a pair of HIP events recorded on the launch stream; ff_timing_read waits for the
+ * recorded events and returns the summed device time and the launch count of one kernel class.
+ * Events are host-side objects created on first use (at most FF_TIMING_MAX_RECORDS pairs; launches
+ * beyond that are not recorded).  Not thread-safe; meant for benchmarks.
+ * ------------------------------------------------------------------------------------------- */
+enum {
+    FF_K_GEMM_FWD = 0,   /* forward contraction (+ fused goodness reductions) */
+    FF_K_GEMM_DW = 1,    /* weight-gradient contraction                       */
+    FF_K_QUANT_ACT = 2,  /* activation quantise (fp32 input or hand-off)      */
+    FF_K_QUANT_GRAD = 3, /* local-gradient quantise                           */
+    FF_K_QUANT_W = 4,    /* weight requantise                                 */
+    FF_K_UPDATE = 5,     /* weight update                                     */
+    FF_K_ABSMAX = 6,     /* absmax of the fp32 input                          */
+    FF_K_SMALL = 7,      /* fills, goodness/loss, look-ahead                  */
+    FF_K_COUNT = 8
+};
+#define FF_TIMING_MAX_RECORDS 16384
+ff_status ff_timing_enable(int32_t on);
+ff_status ff_timing_reset(void);
+ff_status ff_timing_read(int32_t kernel_class, double* total_ms, int64_t* launches);
 
 #ifdef __cplusplus
 }

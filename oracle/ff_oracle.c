@@ -88,6 +88,7 @@ float ffo_uniform(uint64_t seed, uint64_t tag, uint64_t idx)
  * (Section IV, Section IV-B).  n elements, element i uses random index i
  * (the linear index of the logical row-major tensor).
  * amax_in < 0: scan the tensor for max|x|; otherwise use the given amax.
+ * The paper fixes no behaviour for a vanishing range; see the comment below.
  * ---------------------------------------------------------------------- */
 static int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
@@ -104,7 +105,10 @@ int ffo_quantize(const float *x, int64_t n, int mode, uint64_t seed, uint64_t ta
             if (a > amax) amax = a;
         }
     }
-    if (amax == 0.0f) {
+    /* A vanishing range (absmax below 2^-100, which includes the all-zero tensor) quantises to
+     * all-zero codes with scale 1: 127/absmax must stay a finite fp32 number, and magnitudes this
+     * small cannot move an fp32 weight. */
+    if (amax < 0x1p-100f) {
         *scale_out = 1.0f;
         memset(q, 0, (size_t)n);
         return FFO_OK;

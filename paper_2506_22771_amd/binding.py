@@ -78,6 +78,11 @@ def lib() -> C.CDLL:
                                     sz, P]
         L.ff_workspace_bytes.restype = sz
         L.ff_workspace_bytes.argtypes = [C.POINTER(NetDesc)]
+        L.ff_timing_enable.restype = i32
+        L.ff_timing_enable.argtypes = [i32]
+        L.ff_timing_reset.restype = i32
+        L.ff_timing_read.restype = i32
+        L.ff_timing_read.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         _lib = L
     return _lib
 
@@ -200,3 +205,21 @@ def ff_train_step(net: Net, x_pos, x_neg, theta, lam, lr, seed, step, loss, good
     _chk(lib().ff_train_step(C.byref(net.desc), C.byref(net.state), _ptr(x_pos), _ptr(x_neg), theta, lam, lr, seed,
                              step, _ptr(loss), _ptr(goodness), _ptr(ws),
                              ws.numel() * ws.element_size() if ws is not None else 0, _stream()), "ff_train_step")
+
+
+KERNEL_CLASSES = ("gemm_fwd", "gemm_dw", "quant_act", "quant_grad", "quant_w", "update", "absmax", "small")
+
+
+def ff_timing_enable(on: bool) -> None:
+    _chk(lib().ff_timing_enable(1 if on else 0), "ff_timing_enable")
+
+
+def ff_timing_reset() -> None:
+    _chk(lib().ff_timing_reset(), "ff_timing_reset")
+
+
+def ff_timing_read(kernel_class: int):
+    """(total device milliseconds, launches) of one kernel class since the last reset."""
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    _chk(lib().ff_timing_read(kernel_class, C.byref(ms), C.byref(n)), "ff_timing_read")
+    return ms.value, n.value

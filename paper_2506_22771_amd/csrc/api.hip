@@ -53,6 +53,8 @@ static ff_status layer_dims(const ff_layer_desc* L, Dims* d)
 static bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 static bool aligned4(const void* p) { return (((uintptr_t)p) & 3) == 0; }
 #define HIPCHK(e) do { if ((e) != hipSuccess) return FF_ERR_HIP; } while (0)
+// launch bracketed by timing events of kernel class `cls` on the stream of the launch (last argument `s`)
+#define HIPCHK_T(cls, e) do { hipError_t _err; { Timed _t((cls), s); _err = (e); } if (_err != hipSuccess) return FF_ERR_HIP; } while (0)
 
 static int32_t goodness_shift(int64_t K, int64_t terms)
 {
@@ -142,6 +144,42 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
     return FF_OK;
 }
 
+// ---- instrumentation: HIP events around each launch, recorded on the launch stream -----------------
+struct TimingState {
+    bool on = false;
+    int n = 0;
+    hipEvent_t* ev = nullptr;  // 2 per record
+    int8_t* cls = nullptr;
+    int created = 0;
+};
+static TimingState g_timing;
+
+struct Timed {
+    hipStream_t s;
+    int idx = -1;
+    Timed(int kernel_class, hipStream_t stream) : s(stream)
+    {
+        TimingState& t = g_timing;
+        if (!t.on || t.n >= FF_TIMING_MAX_RECORDS) return;
+        if (!t.ev) {
+            t.ev = new hipEvent_t[2 * FF_TIMING_MAX_RECORDS];
+            t.cls = new int8_t[FF_TIMING_MAX_RECORDS];
+        }
+        while (t.created <= t.n) {
+            if (hipEventCreate(&t.ev[2 * t.created]) != hipSuccess) return;
+            if (hipEventCreate(&t.ev[2 * t.created + 1]) != hipSuccess) return;
+            ++t.created;
+        }
+        idx = t.n++;
+        t.cls[idx] = (int8_t)kernel_class;
+        (void)hipEventRecord(t.ev[2 * idx], s);
+    }
+    ~Timed()
+    {
+        if (idx >= 0) (void)hipEventRecord(g_timing.ev[2 * idx + 1], s);
+    }
+};
+
 }  // namespace ffi
 
 using namespace ffi;
@@ -193,14 +231,14 @@ ff_status ff_quantize(const float* x, int64_t rows, int64_t cols, int32_t round_
         const float one = 1.0f;
         uint32_t bits;
         memcpy(&bits, &one, 4);
-        HIPCHK(launch_fill_u32((uint32_t*)scale, 1, bits, s));
+        HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)scale, 1, bits, s));
         return FF_OK;
     }
     if (!x) return FF_ERR_INVALID_ARG;
     if (!aligned4(x)) return FF_ERR_ALIGN;
     uint32_t* slot = (uint32_t*)ws;
-    HIPCHK(launch_fill_u32(slot, 1, 0u, s));
-    HIPCHK(launch_absmax(x, rows * cols, slot, s));
+    HIPCHK_T(FF_K_SMALL, launch_fill_u32(slot, 1, 0u, s));
+    HIPCHK_T(FF_K_ABSMAX, launch_absmax(x, rows * cols, slot, s));
     QuantArgs a;
     memset(&a, 0, sizeof(a));
     a.x = x;
@@ -216,7 +254,7 @@ ff_status ff_quantize(const float* x, int64_t rows, int64_t cols, int32_t round_
     a.scale = scale;
     a.nb = 1;
     a.rows_per_sample = 1;
-    HIPCHK(launch_quantize(QSRC_F32, a, s));
+    HIPCHK_T(FF_K_QUANT_ACT, launch_quantize(QSRC_F32, a, s));
     return FF_OK;
 }
 
@@ -234,8 +272,8 @@ ff_status ff_layer_forward(const ff_layer_desc* layer, const int8_t* a_q, const 
     if (d.K > INT32_SAFE_LEN) return FF_ERR_OVERFLOW_BOUND;
     hipStream_t s = (hipStream_t)stream;
     if (d.B == 0) return FF_OK;
-    HIPCHK(launch_fill_u32((uint32_t*)gsum_int, 2 * d.B, 0u, s));
-    HIPCHK(launch_fill_u32((uint32_t*)vmax, d.B, 0u, s));
+    HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)gsum_int, 2 * d.B, 0u, s));
+    HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)vmax, d.B, 0u, s));
     GemmArgs g;
     memset(&g, 0, sizeof(g));
     g.P = a_q;
@@ -253,7 +291,7 @@ ff_status ff_layer_forward(const ff_layer_desc* layer, const int8_t* a_q, const 
     g.relu = layer->relu ? 1 : 0;
     g.rshift = goodness_shift(d.K, d.rps * d.N);
     g.nb = 1;
-    HIPCHK(launch_gemm_nt_i8(g, s));
+    HIPCHK_T(FF_K_GEMM_FWD, launch_gemm_nt_i8(g, s));
     return FF_OK;
 }
 
@@ -267,6 +305,7 @@ ff_status ff_goodness_loss(const ff_layer_desc* layer, const uint64_t* gsum_int,
     if (!gsum_int || !vmax || !s_a || !s_w || !goodness || !coeff || !loss_mean) return FF_ERR_INVALID_ARG;
     if (pass_sign != FF_PASS_POS && pass_sign != FF_PASS_NEG) return FF_ERR_INVALID_ARG;
     if ((((uintptr_t)gsum_int) & 7) || !aligned4(vmax) || !aligned4(goodness) || !aligned4(coeff)) return FF_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
     GoodnessArgs a;
     memset(&a, 0, sizeof(a));
     a.gsum = (const unsigned long long*)gsum_int;
@@ -283,7 +322,7 @@ ff_status ff_goodness_loss(const ff_layer_desc* layer, const uint64_t* gsum_int,
     a.loss_mean = loss_mean;
     a.next_amax_bits = (uint32_t*)next_amax;
     a.nb = 1;
-    HIPCHK(launch_goodness_loss(a, (hipStream_t)stream));
+    HIPCHK_T(FF_K_SMALL, launch_goodness_loss(a, s));
     return FF_OK;
 }
 
@@ -298,6 +337,7 @@ ff_status ff_layer_handoff(const ff_layer_desc* layer, const int32_t* acc, const
     if (layer->l2norm_out && !goodness) return FF_ERR_INVALID_ARG;
     if (round_mode != FF_ROUND_NEAREST_EVEN && round_mode != FF_ROUND_STOCHASTIC) return FF_ERR_INVALID_ARG;
     if (!aligned16(acc) || (q && !aligned16(q)) || (q_t && !aligned16(q_t))) return FF_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
     QuantArgs a;
     memset(&a, 0, sizeof(a));
     a.acc = acc;
@@ -319,7 +359,7 @@ ff_status ff_layer_handoff(const ff_layer_desc* layer, const int32_t* acc, const
     a.ldqt = pitch8(d.M);
     a.scale = scale;
     a.nb = 1;
-    HIPCHK(launch_quantize(QSRC_HANDOFF, a, (hipStream_t)stream));
+    HIPCHK_T(FF_K_QUANT_ACT, launch_quantize(QSRC_HANDOFF, a, s));
     return FF_OK;
 }
 
@@ -329,6 +369,7 @@ ff_status ff_lookahead(const float* coeff, int32_t n_layers, int64_t batch, floa
     if (!coeff || !coeff_total || batch < 0) return FF_ERR_INVALID_ARG;
     if (n_layers < 1 || n_layers > MAX_LAYERS) return FF_ERR_SHAPE;
     if (batch == 0) return FF_OK;
+    hipStream_t s = (hipStream_t)stream;
     LookaheadArgs a;
     memset(&a, 0, sizeof(a));
     a.coeff = coeff;
@@ -339,7 +380,7 @@ ff_status ff_lookahead(const float* coeff, int32_t n_layers, int64_t batch, floa
     a.st_layer = batch;
     a.st_pass = 0;
     a.lambda = lambda;
-    HIPCHK(launch_lookahead(a, (hipStream_t)stream));
+    HIPCHK_T(FF_K_SMALL, launch_lookahead(a, s));
     return FF_OK;
 }
 
@@ -360,7 +401,7 @@ ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc
     if (d.M > INT32_SAFE_LEN) return FF_ERR_OVERFLOW_BOUND;
     hipStream_t s = (hipStream_t)stream;
     uint32_t* slot = (uint32_t*)ws;
-    HIPCHK(launch_grad_amax(coeff_total, vmax, s_a, s_w, d.B, slot, s));
+    HIPCHK_T(FF_K_SMALL, launch_grad_amax(coeff_total, vmax, s_a, s_w, d.B, slot, s));
     QuantArgs a;
     memset(&a, 0, sizeof(a));
     a.acc = acc;
@@ -379,7 +420,7 @@ ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc
     a.ldqt = pitch8(d.M);
     a.scale = s_g;
     a.nb = 1;
-    HIPCHK(launch_quantize(QSRC_GRAD, a, s));
+    HIPCHK_T(FF_K_QUANT_GRAD, launch_quantize(QSRC_GRAD, a, s));
     GemmArgs g;
     memset(&g, 0, sizeof(g));
     g.P = gy_q_t;
@@ -393,7 +434,7 @@ ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc
     g.ldc = pitch32(d.K);
     g.nb = 1;
     g.rows_per_sample = 1;
-    HIPCHK(launch_gemm_nt_i8(g, s));
+    HIPCHK_T(FF_K_GEMM_DW, launch_gemm_nt_i8(g, s));
     return FF_OK;
 }
 
@@ -413,7 +454,7 @@ ff_status ff_layer_update(const ff_layer_desc* layer, float* w_master, const int
         return FF_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
     uint32_t* slot = (uint32_t*)ws;
-    HIPCHK(launch_fill_u32(slot, 1, 0u, s));
+    HIPCHK_T(FF_K_SMALL, launch_fill_u32(slot, 1, 0u, s));
     UpdateArgs u;
     memset(&u, 0, sizeof(u));
     u.w = w_master;
@@ -430,7 +471,7 @@ ff_status ff_layer_update(const ff_layer_desc* layer, float* w_master, const int
     u.lr = lr;
     u.total_samples = total_samples;
     u.w_amax_bits = slot;
-    HIPCHK(launch_update(u, s));
+    HIPCHK_T(FF_K_UPDATE, launch_update(u, s));
     QuantArgs a;
     memset(&a, 0, sizeof(a));
     a.x = w_master;
@@ -443,7 +484,7 @@ ff_status ff_layer_update(const ff_layer_desc* layer, float* w_master, const int
     a.scale = s_w;
     a.nb = 1;
     a.rows_per_sample = 1;
-    HIPCHK(launch_quantize(QSRC_F32, a, s));
+    HIPCHK_T(FF_K_QUANT_W, launch_quantize(QSRC_F32, a, s));
     return FF_OK;
 }
 
@@ -484,10 +525,10 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
     float* c = (float*)(base + w.off_c);
     float* ct = (float*)(base + w.off_ct);
 
-    HIPCHK(launch_fill_u32((uint32_t*)base, (int64_t)(w.zero_bytes / 4), 0u, s));
+    HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)base, (int64_t)(w.zero_bytes / 4), 0u, s));
     const int64_t n_in = w.d[0].M * w.d[0].in_cols;
-    HIPCHK(launch_absmax(x_pos, n_in, act_amax + 0, s));
-    HIPCHK(launch_absmax(x_neg, n_in, act_amax + 1, s));
+    HIPCHK_T(FF_K_ABSMAX, launch_absmax(x_pos, n_in, act_amax + 0, s));
+    HIPCHK_T(FF_K_ABSMAX, launch_absmax(x_neg, n_in, act_amax + 1, s));
 
     // ---- forward pass through all layers, both data sets together (Algorithm 1) -----------------
     for (int i = 0; i < k; ++i) {
@@ -534,7 +575,7 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         a.scale = s_a + 2 * i;
         a.st_scale = 1;
         a.nb = 2;
-        HIPCHK(launch_quantize(src, a, s));
+        HIPCHK_T(FF_K_QUANT_ACT, launch_quantize(src, a, s));
 
         GemmArgs g;
         memset(&g, 0, sizeof(g));
@@ -557,7 +598,7 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         g.relu = L.relu ? 1 : 0;
         g.rshift = goodness_shift(d.K, d.rps * d.N);
         g.nb = 2;
-        HIPCHK(launch_gemm_nt_i8(g, s));
+        HIPCHK_T(FF_K_GEMM_FWD, launch_gemm_nt_i8(g, s));
 
         GoodnessArgs ga;
         memset(&ga, 0, sizeof(ga));
@@ -577,7 +618,7 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         ga.nb = 2;
         ga.st_b = B;
         ga.st_scalar = 1;
-        HIPCHK(launch_goodness_loss(ga, s));
+        HIPCHK_T(FF_K_SMALL, launch_goodness_loss(ga, s));
     }
 
     // ---- look-ahead coefficients of every layer (Eq. (3)/(4)) and the absmax of every local gradient
@@ -596,7 +637,7 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         la.s_a = s_a;
         la.s_w = state->s_w;
         la.g_amax_bits = g_amax;
-        HIPCHK(launch_lookahead(la, s));
+        HIPCHK_T(FF_K_SMALL, launch_lookahead(la, s));
     }
 
     // ---- per layer: int8 local gradient, int8 weight gradient, update (Algorithm 1, inner loop) ----
@@ -628,7 +669,7 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         a.scale = s_g + 2 * i;
         a.st_scale = 1;
         a.nb = 2;
-        HIPCHK(launch_quantize(QSRC_GRAD, a, s));
+        HIPCHK_T(FF_K_QUANT_GRAD, launch_quantize(QSRC_GRAD, a, s));
 
         GemmArgs g;
         memset(&g, 0, sizeof(g));
@@ -646,7 +687,7 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         g.ldc = pitch32(d.K);
         g.rows_per_sample = 1;
         g.nb = 2;
-        HIPCHK(launch_gemm_nt_i8(g, s));
+        HIPCHK_T(FF_K_GEMM_DW, launch_gemm_nt_i8(g, s));
 
         UpdateArgs u;
         memset(&u, 0, sizeof(u));
@@ -663,7 +704,7 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         u.lr = lr;
         u.total_samples = (int32_t)(2 * B);
         u.w_amax_bits = w_amax + i;
-        HIPCHK(launch_update(u, s));
+        HIPCHK_T(FF_K_UPDATE, launch_update(u, s));
 
         QuantArgs qa;
         memset(&qa, 0, sizeof(qa));
@@ -677,8 +718,38 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         qa.scale = state->s_w[i];
         qa.nb = 1;
         qa.rows_per_sample = 1;
-        HIPCHK(launch_quantize(QSRC_F32, qa, s));
+        HIPCHK_T(FF_K_QUANT_W, launch_quantize(QSRC_F32, qa, s));
     }
+    return FF_OK;
+}
+
+ff_status ff_timing_enable(int32_t on)
+{
+    g_timing.on = on != 0;
+    return FF_OK;
+}
+
+ff_status ff_timing_reset(void)
+{
+    g_timing.n = 0;
+    return FF_OK;
+}
+
+ff_status ff_timing_read(int32_t kernel_class, double* total_ms, int64_t* launches)
+{
+    if (!total_ms || !launches || kernel_class < 0 || kernel_class >= FF_K_COUNT) return FF_ERR_INVALID_ARG;
+    double tot = 0.0;
+    int64_t cnt = 0;
+    for (int i = 0; i < g_timing.n; ++i) {
+        if (g_timing.cls[i] != kernel_class) continue;
+        if (hipEventSynchronize(g_timing.ev[2 * i + 1]) != hipSuccess) return FF_ERR_HIP;
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, g_timing.ev[2 * i], g_timing.ev[2 * i + 1]) != hipSuccess) return FF_ERR_HIP;
+        tot += (double)ms;
+        ++cnt;
+    }
+    *total_ms = tot;
+    *launches = cnt;
     return FF_OK;
 }
 

@@ -162,10 +162,12 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
     int8_t* q_t = a.q_t ? a.q_t + z * a.st_qt : nullptr;
     const SrKey key = z ? a.key2 : a.key;
 
+    // a vanishing range (absmax < 2^-100, all-zero tensor included) quantises to zero codes with scale 1
     const float amax = __uint_as_float(a.amax_bits[z * a.st_amax]);
-    const float inv = amax > 0.0f ? 127.0f / amax : 0.0f;
+    const bool live = amax >= 0x1p-100f;
+    const float inv = live ? 127.0f / amax : 0.0f;
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
-        a.scale[z * a.st_scale] = amax > 0.0f ? amax / 127.0f : 1.0f;
+        a.scale[z * a.st_scale] = live ? amax / 127.0f : 1.0f;
 
     float s_y = 1.0f;
     if (SRC != QSRC_F32) s_y = a.s_a[z * a.st_s_a] * a.s_w[z * a.st_s_w];
@@ -235,7 +237,7 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 int code = 0;
-                if (ok[c]) code = quant_code<STOCH>(v[c], inv, (uint64_t)row * (uint64_t)a.cols + (uint64_t)(col + c), key);
+                if (ok[c] && live) code = quant_code<STOCH>(v[c], inv, (uint64_t)row * (uint64_t)a.cols + (uint64_t)(col + c), key);
                 pack |= ((uint32_t)code & 0xFFu) << (8 * c);
             }
             rowpack[j] = pack;

@@ -61,6 +61,12 @@ def test_quantize_degenerate(ff):
     ff.ff_quantize(None, 0, 9, 1, 1, 2, q, None, s, workspace())     # empty tensor
     torch.cuda.synchronize()
     assert s.item() == 1.0
+    # vanishing range: below 2^-100 everything quantises to zero with scale 1
+    tiny = dev(np.array([[1e-38, -2.7e-37, 0.0, 5e-31]], np.float32))
+    q, s = empty8(1, 4), scalar()
+    ff.ff_quantize(tiny, 1, 4, 1, 1, 2, q, None, s, workspace())
+    torch.cuda.synchronize()
+    assert s.item() == 1.0 and not q.cpu().numpy().any()
     # unaligned fp32 base (4-byte aligned only) takes the scalar path
     rng = np.random.default_rng(0)
     big = dev(rng.standard_normal(1 + 40 * 12).astype(np.float32))
@@ -242,6 +248,15 @@ def _run_steps(ff, wl, n_steps, lam=None):
 @pytest.mark.parametrize("name,steps", [("tiny", 3), ("tiny_l2", 3), ("cfg1", 3), ("cfg2", 1)])
 def test_train_step(ff, name, steps):
     _run_steps(ff, workload(name), steps)
+
+
+@pytest.mark.slow
+@pytest.mark.timeout(1200)
+def test_train_step_cfg5_full_size(ff):
+    """The large-GEMM configuration at its full size (8192+8192 samples, 4096->4096->4096), in the launch
+    configuration bench.py times, against the complete oracle step: every master weight and int8 weight of
+    both layers bit-exact, goodness and loss within 1e-5.  Takes a minute or two of CPU oracle time."""
+    _run_steps(ff, workload("cfg5"), 1)
 
 
 def test_train_step_lambda_zero_and_reproducible(ff):

@@ -30,6 +30,18 @@ def test_quantize_all_zero():
     assert s == np.float32(1.0) and not q.any()
 
 
+def test_quantize_vanishing_range():
+    """Reading R-Q0: absmax below 2^-100 quantises to zero codes with scale 1; just above it the
+    ordinary rule applies and the reciprocal scale is still finite."""
+    tiny = np.array([1e-38, -2.7e-37, 0.0, 5e-31], np.float32)
+    for mode in (O.ROUND_NEAREST, O.ROUND_STOCHASTIC):
+        q, s = O.quantize(tiny, mode, 1, 1)
+        assert s == np.float32(1.0) and not q.any()
+    ok = np.array([2.0 ** -99, -(2.0 ** -100), 0.0], np.float32)
+    q, s = O.quantize(ok, O.ROUND_NEAREST)
+    assert q.tolist() == [127, -64, 0] and s == np.float32(2.0 ** -99) / np.float32(127)
+
+
 def test_quantize_nearest_matches_numpy_rint():
     """Special case that reduces to a library routine: round-to-nearest-even."""
     rng = np.random.default_rng(0)

@@ -18,7 +18,7 @@ LIB = os.path.join(HERE, "libffint8.so")
 SOURCES = ["elementwise.hip", "gemm_i8.hip", "api.hip"]
 HEADERS = [os.path.join(CSRC, "ff_internal.hpp"), os.path.join(os.path.dirname(HERE), "include", "ffint8.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-ffp-contract=off", "-fno-fast-math",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]
 
 
 def _stale(target: str, deps) -> bool:

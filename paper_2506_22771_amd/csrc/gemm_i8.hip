@@ -8,12 +8,21 @@
 // into the epilogue: sum of squared integer activities (uint64) and their maximum, accumulated
 // with integer atomics, hence independent of workgroup order.
 //
-// Tiling: a workgroup of WM x WN wavefronts computes a BM x BN tile; operand tiles of 64 reduction
-// bytes are staged in LDS (two stages, global loads for step k+1 in flight while step k is
-// multiplied); 16-byte chunks are XOR-swizzled so that both the 16-byte LDS writes and the MFMA
-// fragment reads are bank-conflict free.  The Q tile feeds the MFMA "A" operand and the P tile the
-// "B" operand, so that every lane ends up with one row i of C and four consecutive columns j per
-// accumulator quad: 16-byte stores, and the per-row reductions stay inside a lane.
+// Structure (measured choices, see the design notes):
+//  * A workgroup of WM x WN wavefronts computes a BM x BN tile in steps of BK = 128 reduction bytes,
+//    i.e. whole 128-byte lines of both operands per row (half lines halve the useful L2 bandwidth).
+//  * Operand tiles go from global memory straight into LDS with buffer_load_dwordx4 ... lds (no VGPR
+//    staging; rows and reduction tails beyond the matrix read as zero through the buffer's range
+//    check).  Two LDS stages; the copy of step k+1 is in flight while step k is multiplied.  The copies
+//    are issued from inline assembly and tracked by hand with vmcnt: through the compiler's builtin
+//    every LDS read would wait for all outstanding copies, and __syncthreads() would drain them too.
+//  * 16-byte chunks are XOR-swizzled inside each 128-byte row so that the MFMA fragment reads
+//    (32 rows x 16 bytes per half-wave, ds_read_b128) hit all 64 banks; bank-conflict counter = 0.
+//  * MFMA fragments are double-buffered in registers: the reads for sub-step s+1 are issued before
+//    the MFMAs of sub-step s.
+//  * The Q tile feeds the MFMA "A" operand and the P tile the "B" operand, so that every lane ends up
+//    with one row i of C and four consecutive columns j per accumulator quad: 16-byte stores, and the
+//    per-row reductions stay inside a lane (one cross-half-wave shuffle at the end).
 #include "ff_internal.hpp"
 
 namespace ffi {
@@ -21,67 +30,61 @@ namespace ffi {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 64;  // reduction bytes per stage
+constexpr int BK = 128;  // reduction bytes per LDS stage
 
-__device__ __forceinline__ int swz(int row, int kc) { return row * BK + ((kc ^ ((row >> 2) & 3)) << 4); }
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void lds_dma16(__amdgpu_buffer_rsrc_t rsrc, int voffset, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(voffset), "s"(rsrc) : "memory", "m0");
+}
+__device__ __forceinline__ int swz(int row, int kc) { return row * BK + ((kc ^ ((row >> 1) & 7)) << 4); }
 
 template <int BM, int BN, int WM, int WN, bool EPI>
 __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
 {
     constexpr int T = WM * WN * 64;
-    constexpr int WTM = BM / WM, WTN = BN / WN;  // wave tile
-    constexpr int TI = WTM / 32, TJ = WTN / 32;  // MFMA tiles per wave
-    constexpr int CH_P = BM * 4 / T, CH_Q = BN * 4 / T;
-    static_assert(BM * 4 % T == 0 && BN * 4 % T == 0, "tile/threads mismatch");
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of 32");
-
-    __shared__ __attribute__((aligned(16))) int8_t lds[2][(BM + BN) * BK];
+    constexpr int WTM = BM / WM, WTN = BN / WN;
+    constexpr int TI = WTM / 32, TJ = WTN / 32;
+    constexpr int CH_P = BM * 8 / T, CH_Q = BN * 8 / T;
+    constexpr int STAGE_BYTES = (BM + BN) * BK;
+    static_assert(BM * 8 % T == 0 && BN * 8 % T == 0, "tile/threads mismatch");
+    __shared__ __attribute__((aligned(16))) int8_t lds[2 * STAGE_BYTES];
 
     const int z = blockIdx.z;
     const int8_t* __restrict__ P = a.P + z * a.st_p;
     const int8_t* __restrict__ Q = a.Q + z * a.st_q;
     int32_t* __restrict__ C = a.C + z * a.st_c;
-
-    // tile coordinates: blockIdx.x walks i-tiles fastest inside a group of j-tiles
     const int tiles_i = (a.I + BM - 1) / BM;
     const int bi = blockIdx.x % tiles_i, bj = blockIdx.x / tiles_i;
     const int i0 = bi * BM, j0 = bj * BN;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int Rpad = (a.R + 15) & ~15;
     const int nk = (Rpad + BK - 1) / BK;
 
-    v4i regP[CH_P], regQ[CH_Q];
-    auto gload = [&](int k0) {
+    const int rows_p = min(BM, a.I - i0), rows_q = min(BN, a.J - j0);
+    __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc((void*)(P + (int64_t)i0 * a.ldp), 0, (int)(rows_p * a.ldp), 0x00020000);
+    __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc((void*)(Q + (int64_t)j0 * a.ldq), 0, (int)(rows_q * a.ldq), 0x00020000);
+    int offP[CH_P], offQ[CH_Q];
+    // every chunk of one thread has the same k column: chunk index c = s*T + tid, T multiple of 8
+    const int kcol = (((tid & 7) ^ ((tid >> 4) & 7))) * 16;   // (c & 7) ^ ((row >> 1) & 7), row = c >> 3
 #pragma unroll
-        for (int s = 0; s < CH_P; ++s) {
-            const int c = tid + s * T, row = c >> 2, kc = c & 3;
-            const int gi = i0 + row, kb = k0 + kc * 16;
-            v4i v = {0, 0, 0, 0};
-            if (gi < a.I && kb < Rpad) v = *(const v4i*)(P + (int64_t)gi * a.ldp + kb);
-            regP[s] = v;
-        }
+    for (int s = 0; s < CH_P; ++s) offP[s] = ((s * T + tid) >> 3) * (int)a.ldp + kcol;
 #pragma unroll
-        for (int s = 0; s < CH_Q; ++s) {
-            const int c = tid + s * T, row = c >> 2, kc = c & 3;
-            const int gj = j0 + row, kb = k0 + kc * 16;
-            v4i v = {0, 0, 0, 0};
-            if (gj < a.J && kb < Rpad) v = *(const v4i*)(Q + (int64_t)gj * a.ldq + kb);
-            regQ[s] = v;
-        }
-    };
-    auto lstore = [&](int buf) {
+    for (int s = 0; s < CH_Q; ++s) offQ[s] = ((s * T + tid) >> 3) * (int)a.ldq + kcol;
+    auto issue = [&](int kt, int buf) {
+        const int k0 = kt * BK;
+        const bool ok = k0 + kcol < Rpad;
+        int8_t* base = lds + buf * STAGE_BYTES;
 #pragma unroll
-        for (int s = 0; s < CH_P; ++s) {
-            const int c = tid + s * T, row = c >> 2, kc = c & 3;
-            *(v4i*)(&lds[buf][swz(row, kc)]) = regP[s];
-        }
+        for (int s = 0; s < CH_P; ++s)
+            lds_dma16(rp, ok ? offP[s] + k0 : 0x7FFFFFF0, (unsigned)(uintptr_t)(base + (s * T + wave * 64) * 16));
 #pragma unroll
-        for (int s = 0; s < CH_Q; ++s) {
-            const int c = tid + s * T, row = c >> 2, kc = c & 3;
-            *(v4i*)(&lds[buf][BM * BK + swz(row, kc)]) = regQ[s];
-        }
+        for (int s = 0; s < CH_Q; ++s)
+            lds_dma16(rq, ok ? offQ[s] + k0 : 0x7FFFFFF0, (unsigned)(uintptr_t)(base + BM * BK + (s * T + wave * 64) * 16));
     };
 
     v16i acc[TI][TJ];
@@ -93,34 +96,43 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
             for (int v = 0; v < 16; ++v) acc[ti][tj][v] = 0;
 
     const int lr = lane & 31, lh = lane >> 5;
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    int buf = 0;
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) gload((kt + 1) * BK);
+    v4i fp[2][TI], fq[2][TJ];
+    auto ldfrag = [&](int set, const int8_t* sb, int ks) {
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            v4i fp[TI], fq[TJ];
+        for (int ti = 0; ti < TI; ++ti) fp[set][ti] = *(const v4i*)(sb + swz(wm * WTM + ti * 32 + lr, ks * 2 + lh));
 #pragma unroll
-            for (int ti = 0; ti < TI; ++ti)
-                fp[ti] = *(const v4i*)(&lds[buf][swz(wm * WTM + ti * 32 + lr, ks * 2 + lh)]);
+        for (int tj = 0; tj < TJ; ++tj) fq[set][tj] = *(const v4i*)(sb + BM * BK + swz(wn * WTN + tj * 32 + lr, ks * 2 + lh));
+    };
+    auto mma = [&](int set) {
+#pragma unroll
+        for (int ti = 0; ti < TI; ++ti)
 #pragma unroll
             for (int tj = 0; tj < TJ; ++tj)
-                fq[tj] = *(const v4i*)(&lds[buf][BM * BK + swz(wn * WTN + tj * 32 + lr, ks * 2 + lh)]);
-#pragma unroll
-            for (int ti = 0; ti < TI; ++ti)
-#pragma unroll
-                for (int tj = 0; tj < TJ; ++tj)
-                    acc[ti][tj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fq[tj], fp[ti], acc[ti][tj], 0, 0, 0);
-        }
-        if (kt + 1 < nk) lstore(buf ^ 1);
-        __syncthreads();
-        buf ^= 1;
+                acc[ti][tj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fq[set][tj], fp[set][ti], acc[ti][tj], 0, 0, 0);
+    };
+
+    issue(0, 0);
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    ldfrag(0, lds, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        const int8_t* sb = lds + cur * STAGE_BYTES;
+        const int8_t* sn = lds + (cur ^ 1) * STAGE_BYTES;
+        if (kt + 1 < nk) issue(kt + 1, cur ^ 1);
+        ldfrag(1, sb, 1);
+        mma(0);
+        ldfrag(0, sb, 2);
+        mma(1);
+        ldfrag(1, sb, 3);
+        mma(0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (kt + 1 < nk) ldfrag(0, sn, 0);
+        mma(1);
     }
 
-    // Epilogue.  Lane (lr, lh) of tile (ti, tj) holds C[i][j] for i = i0 + wm*WTM + ti*32 + lr and
-    // j = j0 + wn*WTN + tj*32 + 8*g + 4*lh + e, accumulator register v = 4*g + e.
 #pragma unroll
     for (int ti = 0; ti < TI; ++ti) {
         const int i = i0 + wm * WTM + ti * 32 + lr;
@@ -144,7 +156,6 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
                     }
                 }
                 if (EPI) {
-                    // columns j >= J and rows i >= I hold exact zeros (their operand rows were zero-filled)
                     const int cc[4] = {c0, c1, c2, c3};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -158,7 +169,6 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
             }
         }
         if (EPI) {
-            // the two half-waves hold the two column halves of the same row
             const unsigned lo = (unsigned)sq, hi = (unsigned)(sq >> 32);
             const unsigned lo2 = (unsigned)__shfl_xor((int)lo, 32), hi2 = (unsigned)__shfl_xor((int)hi, 32);
             sq += ((unsigned long long)hi2 << 32) | lo2;
@@ -171,6 +181,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
         }
     }
 }
+
 
 template <int BM, int BN, int WM, int WN>
 static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s)
@@ -185,10 +196,12 @@ static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s)
 hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s)
 {
     if (a.I <= 0 || a.J <= 0) return hipSuccess;
+    // tile-relative byte offsets of the operand copies are 32-bit
+    if (a.ldp >= (int64_t(1) << 22) || a.ldq >= (int64_t(1) << 22)) return hipErrorInvalidValue;
     // pick the largest tile that still yields at least ~2 workgroups per compute unit
     const int64_t want = 512;
     auto tiles = [&](int bm, int bn) { return (int64_t)((a.I + bm - 1) / bm) * ((a.J + bn - 1) / bn) * a.nb; };
-    if (tiles(256, 256) >= want) return launch_cfg<256, 256, 2, 4>(a, s);
+    if (tiles(256, 256) >= want) return launch_cfg<256, 256, 4, 2>(a, s);
     if (tiles(128, 128) >= want) return launch_cfg<128, 128, 2, 2>(a, s);
     return launch_cfg<64, 64, 2, 2>(a, s);
 }

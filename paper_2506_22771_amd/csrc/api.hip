@@ -238,7 +238,7 @@ ff_status ff_quantize(const float* x, int64_t rows, int64_t cols, int32_t round_
     if (!aligned4(x)) return FF_ERR_ALIGN;
     uint32_t* slot = (uint32_t*)ws;
     HIPCHK_T(FF_K_SMALL, launch_fill_u32(slot, 1, 0u, s));
-    HIPCHK_T(FF_K_ABSMAX, launch_absmax(x, rows * cols, slot, s));
+    HIPCHK_T(FF_K_ABSMAX, launch_absmax(x, 0, 1, rows * cols, slot, s));
     QuantArgs a;
     memset(&a, 0, sizeof(a));
     a.x = x;
@@ -527,8 +527,8 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
 
     HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)base, (int64_t)(w.zero_bytes / 4), 0u, s));
     const int64_t n_in = w.d[0].M * w.d[0].in_cols;
-    HIPCHK_T(FF_K_ABSMAX, launch_absmax(x_pos, n_in, act_amax + 0, s));
-    HIPCHK_T(FF_K_ABSMAX, launch_absmax(x_neg, n_in, act_amax + 1, s));
+    HIPCHK_T(FF_K_ABSMAX, launch_absmax(x_pos, ((intptr_t)x_neg - (intptr_t)x_pos) / (intptr_t)sizeof(float), 2, n_in,
+                                        act_amax, s));
 
     // ---- forward pass through all layers, both data sets together (Algorithm 1) -----------------
     for (int i = 0; i < k; ++i) {

@@ -73,52 +73,57 @@ hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s)
 }
 
 // ------------------------------------------------------------------------------------------------
-// absmax of an fp32 tensor -> bit pattern in *slot (HBM-bound: 4 bytes read per element)
+// absmax of fp32 tensors -> bit pattern in slot[z] (HBM-bound: 4 bytes read per element).
+// blockIdx.y selects the tensor (x + z*stride); four independent 16-byte loads per thread per trip.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_absmax_f32(const float* __restrict__ x, int64_t n,
+__device__ __forceinline__ uint32_t absbits4(const float4 v)
+{
+    const uint32_t a = max(__float_as_uint(v.x) & 0x7FFFFFFFu, __float_as_uint(v.y) & 0x7FFFFFFFu);
+    const uint32_t b = max(__float_as_uint(v.z) & 0x7FFFFFFFu, __float_as_uint(v.w) & 0x7FFFFFFFu);
+    return max(a, b);
+}
+
+__global__ __launch_bounds__(256) void k_absmax_f32(const float* __restrict__ x0, int64_t st_x, int64_t n,
                                                     uint32_t* __restrict__ slot)
 {
+    const float* __restrict__ x = x0 + (int64_t)blockIdx.y * st_x;
     // scalar head until 16-byte alignment, float4 body, scalar tail
     const uintptr_t addr = (uintptr_t)x;
     int64_t head = (int64_t)(((16 - (addr & 15)) & 15) >> 2);
     if (head > n) head = n;
     const int64_t nvec = (n - head) >> 2;
-    const float4* xv = (const float4*)(x + head);
+    const float4* __restrict__ xv = (const float4*)(x + head);
     const int64_t gtid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t gstride = (int64_t)gridDim.x * 256;
     uint32_t m = 0;
-    for (int64_t i = gtid; i < nvec; i += gstride) {
-        const float4 v = xv[i];
-        m = max(m, __float_as_uint(v.x) & 0x7FFFFFFFu);
-        m = max(m, __float_as_uint(v.y) & 0x7FFFFFFFu);
-        m = max(m, __float_as_uint(v.z) & 0x7FFFFFFFu);
-        m = max(m, __float_as_uint(v.w) & 0x7FFFFFFFu);
+    int64_t i = gtid;
+    for (; i + 3 * gstride < nvec; i += 4 * gstride) {
+        const float4 v0 = xv[i], v1 = xv[i + gstride], v2 = xv[i + 2 * gstride], v3 = xv[i + 3 * gstride];
+        m = max(m, max(max(absbits4(v0), absbits4(v1)), max(absbits4(v2), absbits4(v3))));
     }
+    for (; i < nvec; i += gstride) m = max(m, absbits4(xv[i]));
     if (gtid < head) m = max(m, __float_as_uint(x[gtid]) & 0x7FFFFFFFu);
     const int64_t tail0 = head + (nvec << 2);
     if (tail0 + gtid < n) m = max(m, __float_as_uint(x[tail0 + gtid]) & 0x7FFFFFFFu);
-    block_atomic_max_bits<256>(m, slot);
+    block_atomic_max_bits<256>(m, slot + blockIdx.y);
 }
 
-hipError_t launch_absmax(const float* x, int64_t n, uint32_t* slot, hipStream_t s)
+hipError_t launch_absmax(const float* x, int64_t st_x, int nb, int64_t n, uint32_t* slot, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
     int64_t blocks = (n + 256 * 16 - 1) / (256 * 16);
-    if (blocks > 4096) blocks = 4096;
+    if (blocks > 2048) blocks = 2048;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(k_absmax_f32, dim3((unsigned)blocks), dim3(256), 0, s, x, n, slot);
+    hipLaunchKernelGGL(k_absmax_f32, dim3((unsigned)blocks, (unsigned)nb), dim3(256), 0, s, x, st_x, n, slot);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
 // quantiser
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t sr_word(uint64_t idx, SrKey key)
+// one random word per element: two multiply / xor-shift stages over (low index word ^ key)
+__device__ __forceinline__ uint32_t sr_mix(uint32_t v)
 {
-    const uint32_t hi = (uint32_t)(idx >> 32);
-    uint32_t k = key.k0;
-    if (hi) k += hi * key.k1;
-    uint32_t v = (uint32_t)idx ^ k;
     v ^= v >> 16;
     v *= 0x7FEB352Du;
     v ^= v >> 15;
@@ -127,15 +132,17 @@ __device__ __forceinline__ uint32_t sr_word(uint64_t idx, SrKey key)
     return v;
 }
 
+// STOCH: floor + Bernoulli(frac) from the counter-based word; else round-to-nearest-even.
+// `word_in` is (low 32 bits of the element index) ^ key, already adjusted for the high index half.
 template <bool STOCH>
-__device__ __forceinline__ int quant_code(float v, float inv, uint64_t idx, SrKey key)
+__device__ __forceinline__ int quant_code(float v, float inv, uint32_t word_in)
 {
     const float t = v * inv;
     int code;
     if (STOCH) {
         const float f = floorf(t);
         const float frac = t - f;
-        const float u = (float)(sr_word(idx, key) >> 8) * 0x1p-24f;
+        const float u = (float)(sr_mix(word_in) >> 8) * 0x1p-24f;
         code = (int)f + (u < frac ? 1 : 0);
     } else {
         code = (int)rintf(t);
@@ -150,16 +157,18 @@ constexpr int QT_LDW = QT_ROWS / 4 + 1;  // words per column in the transposed L
 
 // Each thread owns two 4x4 element blocks (rows 4*rb+j, cols 4*cb+c).  Codes are packed four columns
 // to a word for q, byte-transposed in registers for q_t and regrouped through LDS so that q_t is
-// written in 16-byte pieces.
-template <int SRC, bool STOCH>
+// written in 16-byte pieces.  All eight 16-byte loads of a thread are issued before any arithmetic.
+// VEC: 16-byte loads are legal (always for the int32 sources; for fp32 when cols % 4 == 0 and the base
+// is 16-byte aligned).  BIG: the tensor has 2^32 elements or more (64-bit element index).
+template <int SRC, bool STOCH, bool VEC, bool BIG>
 __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
 {
     const int z = blockIdx.z;
-    const float* x = a.x ? a.x + z * a.st_x : nullptr;
-    const int32_t* acc = a.acc ? a.acc + z * a.st_acc : nullptr;
-    const float* per_sample = a.per_sample ? a.per_sample + z * a.st_per_sample : nullptr;
-    int8_t* q = a.q ? a.q + z * a.st_q : nullptr;
-    int8_t* q_t = a.q_t ? a.q_t + z * a.st_qt : nullptr;
+    const float* __restrict__ x = a.x ? a.x + z * a.st_x : nullptr;
+    const int32_t* __restrict__ acc = a.acc ? a.acc + z * a.st_acc : nullptr;
+    const float* __restrict__ per_sample = a.per_sample ? a.per_sample + z * a.st_per_sample : nullptr;
+    int8_t* __restrict__ q = a.q ? a.q + z * a.st_q : nullptr;
+    int8_t* __restrict__ q_t = a.q_t ? a.q_t + z * a.st_qt : nullptr;
     const SrKey key = z ? a.key2 : a.key;
 
     // a vanishing range (absmax < 2^-100, all-zero tensor included) quantises to zero codes with scale 1
@@ -177,71 +186,103 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
     const int t = threadIdx.x;
     const int cb = t & 15;
     const int64_t col = c0 + 4 * cb;
-    const bool vec_ok = (SRC != QSRC_F32) || (((a.cols & 3) == 0) && ((((uintptr_t)x) & 15) == 0));
+    const bool col_in = col < a.cols;
 
     __shared__ uint32_t tileT[QT_COLS * QT_LDW];
 
+    // ---- loads: 2 blocks x 4 rows x 16 bytes, raw bits.  Row (u, j) of this thread is rowb + 64*u + j:
+    // all per-row offsets are (compile-time constant) x (uniform pitch), i.e. scalar-unit work.
+    const int64_t rowb = r0 + 4 * (t >> 4);
+    const float* __restrict__ px0 = SRC == QSRC_F32 ? x + rowb * a.cols + col : nullptr;
+    const int32_t* __restrict__ pa0 = SRC != QSRC_F32 ? acc + rowb * a.ldacc + col : nullptr;
+    int8_t* __restrict__ pq0 = q ? q + rowb * a.ldq + col : nullptr;
+    uint32_t raw[2][4][4];
+    float rowf[2][4];   // per-row factor (GRAD: 2*coeff; HANDOFF+l2norm: sqrt(goodness))
+    const bool ragged = (a.cols & 3) != 0;   // the int32 sources' pad columns hold junk: mask them at load
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int dr = 64 * u + j;
+            const int64_t row = rowb + dr;
+            const bool in = row < a.rows && col_in;
+            uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
+            if (SRC == QSRC_F32) {
+                const float* px = px0 + (int64_t)dr * a.cols;
+                if (VEC) {
+                    if (in) {
+                        const uint4 f = *(const uint4*)px;
+                        w0 = f.x; w1 = f.y; w2 = f.z; w3 = f.w;
+                    }
+                } else if (in) {
+                    w0 = __float_as_uint(px[0]);
+                    if (col + 1 < a.cols) w1 = __float_as_uint(px[1]);
+                    if (col + 2 < a.cols) w2 = __float_as_uint(px[2]);
+                    if (col + 3 < a.cols) w3 = __float_as_uint(px[3]);
+                }
+            } else if (in) {
+                const uint4 f = *(const uint4*)(pa0 + (int64_t)dr * a.ldacc);  // pitch is a multiple of 4
+                w0 = f.x; w1 = f.y; w2 = f.z; w3 = f.w;
+                if (ragged) {
+                    if (col + 1 >= a.cols) w1 = 0;
+                    if (col + 2 >= a.cols) w2 = 0;
+                    if (col + 3 >= a.cols) w3 = 0;
+                }
+            }
+            raw[u][j][0] = w0; raw[u][j][1] = w1; raw[u][j][2] = w2; raw[u][j][3] = w3;
+            float rf = 1.0f;
+            if (SRC == QSRC_GRAD || (SRC == QSRC_HANDOFF && a.l2norm)) {
+                rf = 0.0f;
+                if (in) {
+                    const int64_t smp = a.rows_per_sample == 1 ? row : row / a.rows_per_sample;
+                    rf = SRC == QSRC_GRAD ? 2.0f * per_sample[smp] : sqrtf(per_sample[smp]);
+                }
+            }
+            rowf[u][j] = rf;
+        }
+    }
+
+    // ---- quantise
+    const uint64_t idx0 = (uint64_t)rowb * (uint64_t)a.cols + (uint64_t)col;   // element index of (row rowb, col)
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
         const int rb = (t >> 4) + 16 * u;
         uint32_t rowpack[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int64_t row = r0 + 4 * rb + j;
-            float v[4] = {0.f, 0.f, 0.f, 0.f};
-            bool ok[4] = {false, false, false, false};
-            if (row < a.rows && col < a.cols) {
-                float rs = 1.0f;  // per-row factor
-                bool zero_row = false;
-                if (SRC == QSRC_GRAD) rs = 2.0f * per_sample[row / a.rows_per_sample];
-                if (SRC == QSRC_HANDOFF && a.l2norm) {
-                    rs = sqrtf(per_sample[row / a.rows_per_sample]);
-                    zero_row = !(rs > 0.0f);
-                }
-                float raw[4];
-                if (SRC == QSRC_F32) {
-                    const float* px = x + row * a.cols + col;
-                    if (vec_ok) {
-                        const float4 f = *(const float4*)px;
-                        raw[0] = f.x; raw[1] = f.y; raw[2] = f.z; raw[3] = f.w;
-                        ok[0] = ok[1] = ok[2] = ok[3] = true;
-                    } else {
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            ok[c] = col + c < a.cols;
-                            raw[c] = ok[c] ? px[c] : 0.0f;
-                        }
-                    }
-                } else {
-                    const int4 iv = *(const int4*)(acc + row * a.ldacc + col);  // pitch is a multiple of 4
-                    raw[0] = (float)iv.x; raw[1] = (float)iv.y; raw[2] = (float)iv.z; raw[3] = (float)iv.w;
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) ok[c] = col + c < a.cols;
-                }
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    float y = raw[c];
-                    if (SRC != QSRC_F32) {
-                        y = y * s_y;
-                        if (a.relu) y = fmaxf(y, 0.0f);
-                        if (SRC == QSRC_HANDOFF) {
-                            if (a.l2norm) y = zero_row ? 0.0f : y / rs;
-                        } else {
-                            y = rs * y;
-                        }
-                    }
-                    v[c] = y;
-                }
+            const int dr = 64 * u + j;
+            const int64_t row = rowb + dr;
+            uint32_t base_lo;
+            uint32_t kk = key.k0;
+            bool straddle = false;
+            if (BIG) {
+                const uint64_t idx = idx0 + (uint64_t)dr * (uint64_t)a.cols;
+                base_lo = (uint32_t)idx;
+                const uint32_t hi = (uint32_t)(idx >> 32);
+                straddle = hi != (uint32_t)((idx + 3) >> 32);   // the four elements cross a 2^32 boundary (rare)
+                kk += hi * key.k1;
+            } else {
+                base_lo = (uint32_t)idx0 + (uint32_t)dr * (uint32_t)a.cols;
             }
             uint32_t pack = 0;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                int code = 0;
-                if (ok[c] && live) code = quant_code<STOCH>(v[c], inv, (uint64_t)row * (uint64_t)a.cols + (uint64_t)(col + c), key);
+                float v = SRC == QSRC_F32 ? __uint_as_float(raw[u][j][c]) : (float)(int)raw[u][j][c];
+                if (SRC != QSRC_F32) {
+                    v = v * s_y;
+                    if (a.relu) v = fmaxf(v, 0.0f);
+                    if (SRC == QSRC_GRAD) v = rowf[u][j] * v;
+                    else if (a.l2norm) v = rowf[u][j] > 0.0f ? v / rowf[u][j] : 0.0f;
+                }
+                uint32_t kc = kk;
+                if (BIG && straddle && base_lo + (uint32_t)c < base_lo) kc += key.k1;   // carried into the high half
+                // elements outside the tensor were loaded as zero and a dead range has inv == 0: in both
+                // cases t == 0, so the code is 0 in either rounding mode without any masking
+                const int code = quant_code<STOCH>(v, inv, (base_lo + (uint32_t)c) ^ kc);
                 pack |= ((uint32_t)code & 0xFFu) << (8 * c);
             }
             rowpack[j] = pack;
-            if (q && row < a.rows && col < a.ldq) *(uint32_t*)(q + row * a.ldq + col) = pack;
+            if (q && row < a.rows && col < a.ldq) *(uint32_t*)(pq0 + (int64_t)dr * a.ldq) = pack;
         }
         if (q_t) {
             // 4x4 byte transpose: colpack[c] = byte c of rowpack[0..3]
@@ -275,6 +316,23 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
     }
 }
 
+template <int SRC, bool STOCH>
+static void launch_quantize_t(const QuantArgs& a, dim3 grid, dim3 block, hipStream_t s)
+{
+    const bool big = (uint64_t)a.rows * (uint64_t)a.cols >= (uint64_t(1) << 32);
+    bool vec = true;
+    if (SRC == QSRC_F32) {
+        vec = (a.cols & 3) == 0 && (((uintptr_t)a.x) & 15) == 0 && ((a.st_x & 3) == 0 || a.nb == 1);
+    }
+    if (big) {
+        if (vec) hipLaunchKernelGGL((k_quantize<SRC, STOCH, true, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_quantize<SRC, STOCH, SRC != QSRC_F32, true>), grid, block, 0, s, a);
+    } else {
+        if (vec) hipLaunchKernelGGL((k_quantize<SRC, STOCH, true, false>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_quantize<SRC, STOCH, SRC != QSRC_F32, false>), grid, block, 0, s, a);
+    }
+}
+
 hipError_t launch_quantize(int src, const QuantArgs& a, hipStream_t s)
 {
     const dim3 block(QT_THREADS);
@@ -284,16 +342,16 @@ hipError_t launch_quantize(int src, const QuantArgs& a, hipStream_t s)
     const bool st = a.round_mode == FF_ROUND_STOCHASTIC;
     switch (src) {
         case QSRC_F32:
-            if (st) hipLaunchKernelGGL((k_quantize<QSRC_F32, true>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((k_quantize<QSRC_F32, false>), grid, block, 0, s, a);
+            if (st) launch_quantize_t<QSRC_F32, true>(a, grid, block, s);
+            else launch_quantize_t<QSRC_F32, false>(a, grid, block, s);
             break;
         case QSRC_HANDOFF:
-            if (st) hipLaunchKernelGGL((k_quantize<QSRC_HANDOFF, true>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((k_quantize<QSRC_HANDOFF, false>), grid, block, 0, s, a);
+            if (st) launch_quantize_t<QSRC_HANDOFF, true>(a, grid, block, s);
+            else launch_quantize_t<QSRC_HANDOFF, false>(a, grid, block, s);
             break;
         default:
-            if (st) hipLaunchKernelGGL((k_quantize<QSRC_GRAD, true>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((k_quantize<QSRC_GRAD, false>), grid, block, 0, s, a);
+            if (st) launch_quantize_t<QSRC_GRAD, true>(a, grid, block, s);
+            else launch_quantize_t<QSRC_GRAD, false>(a, grid, block, s);
             break;
     }
     return hipGetLastError();
@@ -471,51 +529,74 @@ hipError_t launch_grad_amax(const float* ct, const int32_t* vmax, const float* s
 }
 
 // ------------------------------------------------------------------------------------------------
-// weight update (HBM-bound: 4 B x (1 + n_terms) read + 4 B written per weight) with fused absmax
+// weight update (HBM-bound: 4 B x (1 + n_terms) read + 4 B written per weight) with fused absmax.
+// One workgroup per (row, 4096-column segment); a thread owns four groups of four columns, 256 groups
+// apart, and issues all of its loads before the arithmetic.
 // ------------------------------------------------------------------------------------------------
+constexpr int UP_SEG = 4096;
+
+template <bool VEC>
 __global__ __launch_bounds__(256) void k_update(UpdateArgs a)
 {
     float sc[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) sc[j] = j < a.n_terms ? a.s_g[j][0] * a.s_a[j][0] : 0.0f;
     const float lr_eff = a.lr / (float)a.total_samples;
-    const int64_t kq = (a.K + 3) >> 2;  // groups of four columns per row
-    const int64_t total = a.N * kq;
-    const bool vec = (a.K & 3) == 0 && ((((uintptr_t)a.w) & 15) == 0);
-    uint32_t m = 0;
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int64_t n = e / kq, k = (e - n * kq) << 2;
-        float* pw = a.w + n * a.K + k;
-        const int cnt = (int)min((int64_t)4, a.K - k);
-        float w[4] = {0.f, 0.f, 0.f, 0.f};
-        if (vec) {
-            const float4 f = *(const float4*)pw;
-            w[0] = f.x; w[1] = f.y; w[2] = f.z; w[3] = f.w;
+    const int64_t n = blockIdx.y;
+    const int64_t kbase = (int64_t)blockIdx.x * UP_SEG + 4 * threadIdx.x;
+    float* __restrict__ wrow = a.w + n * a.K;
+    float w[4][4];
+    int4 d[4][4];
+    int cnt[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int64_t k = kbase + g * 1024;
+        cnt[g] = (int)max((int64_t)0, min((int64_t)4, a.K - k));
+        if (VEC) {
+            float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (cnt[g]) f = *(const float4*)(wrow + k);
+            w[g][0] = f.x; w[g][1] = f.y; w[g][2] = f.z; w[g][3] = f.w;
         } else {
-            for (int c = 0; c < cnt; ++c) w[c] = pw[c];
-        }
-        float g[4];
-        {
-            const int4 d = *(const int4*)(a.dw[0] + n * a.lddw + k);
-            g[0] = (float)d.x * sc[0]; g[1] = (float)d.y * sc[0]; g[2] = (float)d.z * sc[0]; g[3] = (float)d.w * sc[0];
-        }
-        for (int j = 1; j < a.n_terms; ++j) {
-            const int4 d = *(const int4*)(a.dw[j] + n * a.lddw + k);
-            g[0] = __builtin_fmaf((float)d.x, sc[j], g[0]);
-            g[1] = __builtin_fmaf((float)d.y, sc[j], g[1]);
-            g[2] = __builtin_fmaf((float)d.z, sc[j], g[2]);
-            g[3] = __builtin_fmaf((float)d.w, sc[j], g[3]);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) w[g][c] = c < cnt[g] ? wrow[k + c] : 0.0f;
         }
 #pragma unroll
-        for (int c = 0; c < 4; ++c) w[c] = __builtin_fmaf(-lr_eff, g[c], w[c]);
-        if (vec) {
-            *(float4*)pw = make_float4(w[0], w[1], w[2], w[3]);
-            for (int c = 0; c < 4; ++c) m = max(m, __float_as_uint(w[c]) & 0x7FFFFFFFu);
-        } else {
-            for (int c = 0; c < cnt; ++c) {
-                pw[c] = w[c];
-                m = max(m, __float_as_uint(w[c]) & 0x7FFFFFFFu);
+        for (int j = 0; j < 4; ++j) {
+            d[g][j] = make_int4(0, 0, 0, 0);
+            if (j < a.n_terms && cnt[g]) d[g][j] = *(const int4*)(a.dw[j] + n * a.lddw + k);
+        }
+    }
+    uint32_t m = 0;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const int64_t k = kbase + g * 1024;
+        float gr[4];
+        gr[0] = (float)d[g][0].x * sc[0]; gr[1] = (float)d[g][0].y * sc[0];
+        gr[2] = (float)d[g][0].z * sc[0]; gr[3] = (float)d[g][0].w * sc[0];
+#pragma unroll
+        for (int j = 1; j < 4; ++j) {
+            if (j < a.n_terms) {
+                gr[0] = __builtin_fmaf((float)d[g][j].x, sc[j], gr[0]);
+                gr[1] = __builtin_fmaf((float)d[g][j].y, sc[j], gr[1]);
+                gr[2] = __builtin_fmaf((float)d[g][j].z, sc[j], gr[2]);
+                gr[3] = __builtin_fmaf((float)d[g][j].w, sc[j], gr[3]);
             }
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) w[g][c] = __builtin_fmaf(-lr_eff, gr[c], w[g][c]);
+        if (VEC) {
+            if (cnt[g]) {
+                *(float4*)(wrow + k) = make_float4(w[g][0], w[g][1], w[g][2], w[g][3]);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) m = max(m, __float_as_uint(w[g][c]) & 0x7FFFFFFFu);
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (c < cnt[g]) {
+                    wrow[k + c] = w[g][c];
+                    m = max(m, __float_as_uint(w[g][c]) & 0x7FFFFFFFu);
+                }
         }
     }
     block_atomic_max_bits<256>(m, a.w_amax_bits);
@@ -523,11 +604,11 @@ __global__ __launch_bounds__(256) void k_update(UpdateArgs a)
 
 hipError_t launch_update(const UpdateArgs& a, hipStream_t s)
 {
-    const int64_t total = a.N * ((a.K + 3) >> 2);
-    if (total <= 0) return hipSuccess;
-    int64_t blocks = (total + 255) / 256;
-    if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(k_update, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    if (a.N <= 0 || a.K <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((a.K + UP_SEG - 1) / UP_SEG), (unsigned)a.N);
+    const bool vec = (a.K & 3) == 0 && ((((uintptr_t)a.w) & 15) == 0);
+    if (vec) hipLaunchKernelGGL(k_update<true>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(k_update<false>, grid, dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

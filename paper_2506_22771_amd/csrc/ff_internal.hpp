@@ -55,8 +55,9 @@ struct QuantArgs {
 };
 hipError_t launch_quantize(int src, const QuantArgs& a, hipStream_t s);
 
-// absmax of |x| over n floats into *slot (bit pattern, atomic max; slot must be zeroed first).
-hipError_t launch_absmax(const float* x, int64_t n, uint32_t* slot, hipStream_t s);
+// absmax of |x| over n floats of tensor z (x + z*st_x, z < nb) into slot[z] (bit pattern, atomic max;
+// slots must be zeroed first).
+hipError_t launch_absmax(const float* x, int64_t st_x, int nb, int64_t n, uint32_t* slot, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s);
 
 // ---- per-sample kernels ----------------------------------------------------------------------

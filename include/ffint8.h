@@ -135,6 +135,21 @@ ff_status ff_layer_forward(const ff_layer_desc* layer, const int8_t* a_q, const 
                            int32_t* acc, uint64_t* gsum_int, int32_t* vmax, void* ws,
                            size_t ws_bytes, void* stream);
 
+/* Convolution layers (kind FF_CONV2D) in the single-operation entry points
+ *   - M = batch * H_out * W_out rows (one per output pixel, NHWC order), K = ksize^2 * C_in with the reduction
+ *     index ordered (kh, kw, ci), N = C_out.  a_q is the NHWC int8 input [batch, H, W, ff_pitch(C_in)]
+ *     (what ff_quantize writes for rows = batch*H*W, cols = C_in); w_q is [C_out, ff_pitch(K)].
+ *   - ff_layer_forward runs an implicit GEMM when C_in % 16 == 0; otherwise it first writes the patch matrix
+ *     into ws.  ff_layer_backward_local takes the SAME NHWC a_q in its a_q_t argument and materialises the
+ *     transposed patches of one weight-gradient chunk at a time in ws.  Both need
+ *     ws_bytes >= ff_layer_workspace_bytes(layer).
+ *   - A weight-gradient reduction over more than 133144 rows (M * 127^2 would not fit int32) is split into
+ *     ff_layer_dw_chunks(layer) equal blocks of samples, block size = the largest power of two whose rows still
+ *     fit; dw_acc then holds that many [N, ff_pitch32(K)] accumulators back to back, and ff_layer_update
+ *     combines them in order (positive chunks, then negative chunks).  At most 2 chunks per pass. */
+int32_t ff_layer_dw_chunks(const ff_layer_desc* layer);        /* [host only]; -1 for an invalid descriptor */
+size_t ff_layer_workspace_bytes(const ff_layer_desc* layer);   /* [host only]; 0 for an invalid descriptor  */
+
 /* Right shift applied to each squared integer activity before it is summed into gsum_int:
  * the smallest r >= 0 with (127^2 K)^2 * T / 2^r < 2^64, T = activities per sample.  [host only] */
 int32_t ff_goodness_shift(const ff_layer_desc* layer);
@@ -183,7 +198,8 @@ ff_status ff_lookahead(const float* coeff, int32_t n_layers, int64_t batch, floa
  *   gy_q_t       int8 [N, ff_pitch(M)]: quantised g, transposed, scale s_g               (out)
  *   dw_acc       int32 [N, ff_pitch32(K)]: dw_acc[n][k] = sum_m gy_q[m][n] * a_q[m][k]   (out)
  *   a_q_t        int8 [K, ff_pitch(M)]: the transposed copy ff_quantize / ff_layer_handoff wrote (in)
- * Returns FF_ERR_OVERFLOW_BOUND if M * 127^2 could exceed int32 (split the batch instead).
+ *   dw_acc holds ff_layer_dw_chunks(layer) accumulators (1 unless M > 133144).
+ * ws: >= ff_layer_workspace_bytes(layer).
  * ------------------------------------------------------------------------------------------- */
 ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc, const int32_t* vmax,
                                   const float* s_a, const float* s_w, const float* coeff_total,
@@ -239,7 +255,8 @@ enum {
     FF_K_UPDATE = 5,     /* weight update                                     */
     FF_K_ABSMAX = 6,     /* absmax of the fp32 input                          */
     FF_K_SMALL = 7,      /* fills, goodness/loss, look-ahead                  */
-    FF_K_COUNT = 8
+    FF_K_IM2COL = 8,     /* patch matrices of convolution layers              */
+    FF_K_COUNT = 9
 };
 #define FF_TIMING_MAX_RECORDS 16384
 ff_status ff_timing_enable(int32_t on);

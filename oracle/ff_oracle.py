@@ -222,10 +222,15 @@ def update(w: np.ndarray, dws: Sequence[np.ndarray], s_g: Sequence[float], s_a: 
 
 
 def batch_chunks(B: int, rows_per_sample: int) -> List[tuple]:
-    """Sample ranges whose reduction length (rows) cannot overflow an int32 accumulator."""
+    """Sample ranges whose reduction length (rows) cannot overflow an int32 accumulator: the whole batch
+    if it fits, else equal blocks of `per` samples, per = the largest power of two whose rows still fit."""
     if B * rows_per_sample <= INT32_SAFE_ROWS:
         return [(0, B)]
-    per = max(1, INT32_SAFE_ROWS // rows_per_sample)
+    if rows_per_sample > INT32_SAFE_ROWS:
+        raise OracleError("one sample alone exceeds the int32-safe reduction length")
+    per = 1
+    while per * 2 * rows_per_sample <= INT32_SAFE_ROWS:
+        per *= 2
     return [(b0, min(B, b0 + per)) for b0 in range(0, B, per)]
 
 

@@ -59,6 +59,10 @@ def lib() -> C.CDLL:
         L.ff_version.restype = C.c_char_p
         L.ff_goodness_shift.restype = i32
         L.ff_goodness_shift.argtypes = [LD]
+        L.ff_layer_dw_chunks.restype = i32
+        L.ff_layer_dw_chunks.argtypes = [LD]
+        L.ff_layer_workspace_bytes.restype = sz
+        L.ff_layer_workspace_bytes.argtypes = [LD]
         L.ff_quantize.restype = i32
         L.ff_quantize.argtypes = [P, i64, i64, i32, u64, u64, P, P, P, P, sz, P]
         L.ff_layer_forward.restype = i32
@@ -137,6 +141,14 @@ def ff_goodness_shift(desc: LayerDesc) -> int:
     return int(lib().ff_goodness_shift(C.byref(desc)))
 
 
+def ff_layer_dw_chunks(desc: LayerDesc) -> int:
+    return int(lib().ff_layer_dw_chunks(C.byref(desc)))
+
+
+def ff_layer_workspace_bytes(desc: LayerDesc) -> int:
+    return int(lib().ff_layer_workspace_bytes(C.byref(desc)))
+
+
 def ff_quantize(x, rows, cols, round_mode, seed, stream_tag, q, q_t, scale, ws) -> None:
     _chk(lib().ff_quantize(_ptr(x), rows, cols, round_mode, seed, stream_tag, _ptr(q), _ptr(q_t), _ptr(scale),
                            _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream()), "ff_quantize")
@@ -207,7 +219,7 @@ def ff_train_step(net: Net, x_pos, x_neg, theta, lam, lr, seed, step, loss, good
                              ws.numel() * ws.element_size() if ws is not None else 0, _stream()), "ff_train_step")
 
 
-KERNEL_CLASSES = ("gemm_fwd", "gemm_dw", "quant_act", "quant_grad", "quant_w", "update", "absmax", "small")
+KERNEL_CLASSES = ("gemm_fwd", "gemm_dw", "quant_act", "quant_grad", "quant_w", "update", "absmax", "small", "im2col")
 
 
 def ff_timing_enable(on: bool) -> None:

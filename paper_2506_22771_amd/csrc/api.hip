@@ -27,33 +27,79 @@ SrKey make_sr_key(uint64_t seed, uint64_t tag)
 
 constexpr int64_t INT32_SAFE_LEN = 2147483647ll / (127 * 127);  // longest reduction that cannot overflow int32
 constexpr int MAX_LAYERS = 32;
+constexpr int MAX_CHUNKS = 2;  // weight-gradient accumulators per pass (k_update combines at most 4 terms)
 
+// Shapes of one layer as the kernels see them.
 struct Dims {
-    int64_t B, M, K, N, rps, in_cols;  // M rows per pass, rps rows per sample, in_cols = columns of the 2-D input view
+    int kind;
+    int64_t B, M, K, N, rps;   // M rows per pass (dense: B; conv: B*Ho*Wo), rps rows per sample
+    int64_t in_rows, in_cols;  // 2-D view of the layer input: dense [B, K]; conv [B*H*W, C_in]
+    bool implicit;             // conv whose forward runs as an implicit GEMM (C_in % 16 == 0)
+    ConvGeom g;                // conv only
+    int n_chunks;              // weight-gradient accumulators per pass
+    int64_t chunk_b;           // samples per accumulator
 };
 
 static ff_status layer_dims(const ff_layer_desc* L, Dims* d)
 {
     if (!L) return FF_ERR_INVALID_ARG;
     if (L->batch < 0) return FF_ERR_INVALID_ARG;
+    memset(d, 0, sizeof(*d));
+    d->kind = L->kind;
+    d->B = L->batch;
     if (L->kind == FF_DENSE) {
         if (L->in_features <= 0 || L->out_features <= 0) return FF_ERR_SHAPE;
-        d->B = L->batch;
         d->M = L->batch;
         d->K = L->in_features;
         d->N = L->out_features;
         d->rps = 1;
+        d->in_rows = L->batch;
         d->in_cols = L->in_features;
-        return FF_OK;
+    } else if (L->kind == FF_CONV2D) {
+        if (L->H <= 0 || L->W <= 0 || L->C_in <= 0 || L->C_out <= 0) return FF_ERR_SHAPE;
+        if ((L->ksize != 1 && L->ksize != 3) || (L->stride != 1 && L->stride != 2) || L->pad != L->ksize / 2)
+            return FF_ERR_SHAPE;
+        ConvGeom& g = d->g;
+        g.H = L->H;
+        g.W = L->W;
+        g.Cin = L->C_in;
+        g.cpitch = (int32_t)pitch8(L->C_in);
+        g.ks = L->ksize;
+        g.stride = L->stride;
+        g.pad = L->pad;
+        g.Ho = (L->H + 2 * L->pad - L->ksize) / L->stride + 1;
+        g.Wo = (L->W + 2 * L->pad - L->ksize) / L->stride + 1;
+        d->rps = (int64_t)g.Ho * g.Wo;
+        d->M = d->B * d->rps;
+        d->K = (int64_t)L->ksize * L->ksize * L->C_in;
+        d->N = L->C_out;
+        d->in_rows = d->B * L->H * L->W;
+        d->in_cols = L->C_in;
+        d->implicit = (L->C_in & 15) == 0;
+        if (d->in_rows * g.cpitch >= (int64_t(1) << 31) || d->M >= (int64_t(1) << 31)) return FF_ERR_UNSUPPORTED;
+    } else {
+        return FF_ERR_INVALID_ARG;
     }
-    if (L->kind == FF_CONV2D) return FF_ERR_UNSUPPORTED;
-    return FF_ERR_INVALID_ARG;
+    // Weight-gradient reduction: one accumulator if M * 127^2 fits int32, otherwise equal blocks of `per`
+    // samples, per = the largest power of two with per * rps <= 133144.
+    if (d->M <= INT32_SAFE_LEN) {
+        d->n_chunks = 1;
+        d->chunk_b = d->B;
+    } else {
+        int64_t per = 1;
+        if (d->rps > INT32_SAFE_LEN) return FF_ERR_OVERFLOW_BOUND;
+        while (per * 2 * d->rps <= INT32_SAFE_LEN) per *= 2;
+        d->chunk_b = per;
+        d->n_chunks = (int)((d->B + per - 1) / per);
+        if ((per * d->rps) & 15) return FF_ERR_UNSUPPORTED;  // chunk starts must fall on 16-byte boundaries
+    }
+    return FF_OK;
 }
 
 static bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 static bool aligned4(const void* p) { return (((uintptr_t)p) & 3) == 0; }
 #define HIPCHK(e) do { if ((e) != hipSuccess) return FF_ERR_HIP; } while (0)
-// launch bracketed by timing events of kernel class `cls` on the stream of the launch (last argument `s`)
+// launch bracketed by timing events of kernel class `cls` on the stream `s` of the enclosing function
 #define HIPCHK_T(cls, e) do { hipError_t _err; { Timed _t((cls), s); _err = (e); } if (_err != hipSuccess) return FF_ERR_HIP; } while (0)
 
 static int32_t goodness_shift(int64_t K, int64_t terms)
@@ -63,6 +109,16 @@ static int32_t goodness_shift(int64_t K, int64_t terms)
     int r = 0;
     while ((bound >> r) >> 64) ++r;
     return r;
+}
+
+// Scratch one layer's single-operation calls need beyond FF_WS_MIN_BYTES: the row-major patch matrix of an
+// explicit-im2col forward, or the transposed patch matrix of one weight-gradient chunk.
+static size_t layer_scratch_bytes(const Dims& d)
+{
+    if (d.kind != FF_CONV2D) return 0;
+    const size_t fwd = d.implicit ? 0 : (size_t)(d.M * pitch8(d.K));
+    const size_t bwd = (size_t)(d.K * pitch8(d.chunk_b * d.rps));
+    return align_up(fwd > bwd ? fwd : bwd, 256);
 }
 
 // ---- workspace of ff_train_step ------------------------------------------------------------------
@@ -77,11 +133,12 @@ struct WsLayout {
     size_t zero_bytes;     // the region [0, zero_bytes) is cleared at the start of a step
     size_t off_scales;     // fp32: s_a[k][2], s_g[k][2]
     size_t off_c, off_ct;  // fp32 [k][2][B]
-    size_t off_aq, st_aq;  // int8 scratch [2][st_aq]
-    size_t off_gy, st_gy;  // int8 scratch [2][st_gy]
-    size_t off_dw, st_dw;  // int32 scratch [2][st_dw] (bytes)
-    size_t off_aqt[MAX_LAYERS], st_aqt[MAX_LAYERS];  // int8 [2][st]
-    size_t off_acc[MAX_LAYERS], st_acc[MAX_LAYERS];  // int32 [2][st] (bytes)
+    size_t off_gy, st_gy;  // int8 scratch [2][st_gy]: transposed quantised local gradient
+    size_t off_dw, st_dw, dw_bytes;  // int32 scratch [2][MAX_CHUNKS][dw_bytes]; st_dw = pass stride (bytes)
+    size_t off_col, st_col;          // int8 scratch [2][st_col]: patch matrices of conv layers
+    size_t off_aq[MAX_LAYERS], st_aq[MAX_LAYERS];    // quantised layer input [2][st]: dense layers share one scratch
+    size_t off_aqt[MAX_LAYERS], st_aqt[MAX_LAYERS];  // dense only: transposed quantised input [2][st], retained
+    size_t off_acc[MAX_LAYERS], st_acc[MAX_LAYERS];  // int32 accumulators [2][st] (bytes), retained
     size_t total;
 };
 
@@ -95,9 +152,16 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
     for (int i = 0; i < w->k; ++i) {
         const ff_status st = layer_dims(&net->layers[i], &w->d[i]);
         if (st != FF_OK) return st;
+        const Dims& d = w->d[i];
         if (net->layers[i].batch != net->batch) return FF_ERR_SHAPE;
-        if (i > 0 && w->d[i].K != w->d[i - 1].N) return FF_ERR_SHAPE;
-        if (w->d[i].K > INT32_SAFE_LEN || w->d[i].M > INT32_SAFE_LEN) return FF_ERR_OVERFLOW_BOUND;
+        if (d.K > INT32_SAFE_LEN) return FF_ERR_OVERFLOW_BOUND;
+        if (d.n_chunks > MAX_CHUNKS) return FF_ERR_UNSUPPORTED;
+        if (i > 0) {
+            const Dims& p = w->d[i - 1];
+            if (p.kind != d.kind) return FF_ERR_UNSUPPORTED;  // no dense <-> conv transitions in this build
+            if (d.kind == FF_DENSE && d.K != p.N) return FF_ERR_SHAPE;
+            if (d.kind == FF_CONV2D && (d.g.Cin != p.N || d.g.H != p.g.Ho || d.g.W != p.g.Wo)) return FF_ERR_SHAPE;
+        }
     }
     const size_t A = 256;
     size_t off = 0;
@@ -115,27 +179,42 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
     off = align_up(off + sizeof(float) * k * 2 * B, A);
     w->off_ct = off;
     off = align_up(off + sizeof(float) * k * 2 * B, A);
-    size_t aq = 0, gy = 0, dw = 0;
+    size_t aq_dense = 0, gy = 0, dw = 0, col = 0;
     for (int i = 0; i < w->k; ++i) {
         const Dims& d = w->d[i];
-        aq = max(aq, (size_t)(d.M * pitch8(d.K)));
+        if (d.kind == FF_DENSE) aq_dense = max(aq_dense, (size_t)(d.in_rows * pitch8(d.in_cols)));
         gy = max(gy, (size_t)(d.N * pitch8(d.M)));
         dw = max(dw, (size_t)(d.N * pitch32(d.K)) * sizeof(int32_t));
+        col = max(col, layer_scratch_bytes(d));
     }
-    w->st_aq = align_up(aq, A);
-    w->off_aq = off;
-    off += 2 * w->st_aq;
+    aq_dense = align_up(aq_dense, A);
+    const size_t off_aq_dense = off;
+    off += 2 * aq_dense;
     w->st_gy = align_up(gy, A);
     w->off_gy = off;
     off += 2 * w->st_gy;
-    w->st_dw = align_up(dw, A);
+    w->dw_bytes = align_up(dw, A);
+    w->st_dw = MAX_CHUNKS * w->dw_bytes;
     w->off_dw = off;
     off += 2 * w->st_dw;
+    w->st_col = col;
+    w->off_col = off;
+    off += 2 * w->st_col;
     for (int i = 0; i < w->k; ++i) {
         const Dims& d = w->d[i];
-        w->st_aqt[i] = align_up((size_t)(d.K * pitch8(d.M)), A);
-        w->off_aqt[i] = off;
-        off += 2 * w->st_aqt[i];
+        if (d.kind == FF_DENSE) {
+            w->off_aq[i] = off_aq_dense;
+            w->st_aq[i] = aq_dense;
+            w->st_aqt[i] = align_up((size_t)(d.K * pitch8(d.M)), A);
+            w->off_aqt[i] = off;
+            off += 2 * w->st_aqt[i];
+        } else {
+            w->st_aq[i] = align_up((size_t)(d.in_rows * pitch8(d.in_cols)), A);
+            w->off_aq[i] = off;
+            off += 2 * w->st_aq[i];
+            w->st_aqt[i] = 0;
+            w->off_aqt[i] = 0;
+        }
         w->st_acc[i] = align_up((size_t)(d.M * pitch32(d.N)) * sizeof(int32_t), A);
         w->off_acc[i] = off;
         off += 2 * w->st_acc[i];
@@ -180,6 +259,121 @@ struct Timed {
     }
 };
 
+// ---- the two contractions of a layer, for nb passes at once ------------------------------------------
+// Forward: acc[z] = A_q[z] x W_q^T (+ per-sample sums).  `aq` is the quantised layer input (dense: [M, pitch(K)];
+// conv: NHWC), `col` scratch for an explicit patch matrix (conv with C_in % 16 != 0).
+static ff_status run_forward(const Dims& d, int relu, const int8_t* aq, int64_t st_aq, const int8_t* w_q, int32_t* acc,
+                             int64_t st_acc, unsigned long long* gsum, int32_t* vmax, int64_t st_g, int8_t* col,
+                             int64_t st_col, int nb, hipStream_t s)
+{
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.Q = w_q;
+    g.st_q = 0;
+    g.C = acc;
+    g.st_c = st_acc;
+    g.I = (int32_t)d.M;
+    g.J = (int32_t)d.N;
+    g.R = (int32_t)d.K;
+    g.ldq = pitch8(d.K);
+    g.ldc = pitch32(d.N);
+    g.gsum = gsum;
+    g.vmax = vmax;
+    g.st_g = st_g;
+    g.rows_per_sample = (int32_t)d.rps;
+    g.relu = relu;
+    g.rshift = goodness_shift(d.K, d.rps * d.N);
+    g.nb = nb;
+    g.splits = 1;
+    if (d.kind == FF_DENSE) {
+        g.P = aq;
+        g.st_p = st_aq;
+        g.ldp = pitch8(d.K);
+    } else if (d.implicit) {
+        g.P = aq;
+        g.st_p = st_aq;
+        g.ldp = 16;  // unused by the implicit loader
+        g.conv = 1;
+        g.H = d.g.H; g.W = d.g.W; g.Cin = d.g.Cin; g.cpitch = d.g.cpitch; g.ks = d.g.ks;
+        g.stride = d.g.stride; g.pad = d.g.pad; g.Ho = d.g.Ho; g.Wo = d.g.Wo;
+        g.p_bytes = d.in_rows * d.g.cpitch;
+    } else {
+        Im2colArgs ic;
+        memset(&ic, 0, sizeof(ic));
+        ic.a = aq;
+        ic.st_a = st_aq;
+        ic.out = col;
+        ic.st_out = st_col;
+        ic.g = d.g;
+        ic.K = (int32_t)d.K;
+        ic.b0 = 0;
+        ic.b1 = (int32_t)d.B;
+        ic.ld_out = pitch8(d.K);
+        ic.nb = nb;
+        HIPCHK_T(FF_K_IM2COL, launch_im2col(ic, false, s));
+        g.P = col;
+        g.st_p = st_col;
+        g.ldp = pitch8(d.K);
+    }
+    HIPCHK_T(FF_K_GEMM_FWD, launch_gemm_nt_i8(g, s));
+    return FF_OK;
+}
+
+// Weight gradient: dw[z][c] = gy_q_t[z][:, chunk c] x (patches of chunk c)^T for every chunk c.
+// `aqt` is the transposed quantised input (dense) or the NHWC quantised input (conv; patches are materialised
+// chunk by chunk into `colT`).  dw accumulators of one pass are dw_elems apart.
+static ff_status run_wgrad(const Dims& d, const int8_t* gy_t, int64_t st_gy, const int8_t* aqt, int64_t st_aqt,
+                           int8_t* colT, int64_t st_colT, int32_t* dw, int64_t st_dw, int64_t dw_elems, int nb,
+                           hipStream_t s)
+{
+    for (int c = 0; c < d.n_chunks; ++c) {
+        const int64_t b0 = c * d.chunk_b, b1 = min(d.B, b0 + d.chunk_b);
+        const int64_t m0 = b0 * d.rps, mc = (b1 - b0) * d.rps;
+        GemmArgs g;
+        memset(&g, 0, sizeof(g));
+        g.P = gy_t + m0;
+        g.st_p = st_gy;
+        g.ldp = pitch8(d.M);
+        g.C = dw + c * dw_elems;
+        g.st_c = st_dw;
+        g.I = (int32_t)d.N;
+        g.J = (int32_t)d.K;
+        g.R = (int32_t)mc;
+        g.ldc = pitch32(d.K);
+        g.rows_per_sample = 1;
+        g.nb = nb;
+        if (d.kind == FF_DENSE) {
+            g.Q = aqt + m0;
+            g.st_q = st_aqt;
+            g.ldq = pitch8(d.M);
+        } else {
+            Im2colArgs ic;
+            memset(&ic, 0, sizeof(ic));
+            ic.a = aqt;
+            ic.st_a = st_aqt;
+            ic.out = colT;
+            ic.st_out = st_colT;
+            ic.g = d.g;
+            ic.K = (int32_t)d.K;
+            ic.b0 = (int32_t)b0;
+            ic.b1 = (int32_t)b1;
+            ic.ld_out = pitch8(mc);
+            ic.nb = nb;
+            HIPCHK_T(FF_K_IM2COL, launch_im2col(ic, true, s));
+            g.Q = colT;
+            g.st_q = st_colT;
+            g.ldq = pitch8(mc);
+        }
+        g.splits = gemm_pick_splits(g.I, g.J, g.R, nb);
+        if (g.splits > 1) {
+            for (int z = 0; z < nb; ++z)
+                HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(g.C + z * st_dw), d.N * pitch32(d.K), 0u, s));
+        }
+        HIPCHK_T(FF_K_GEMM_DW, launch_gemm_nt_i8(g, s));
+    }
+    return FF_OK;
+}
+
 }  // namespace ffi
 
 using namespace ffi;
@@ -209,13 +403,27 @@ const char* ff_status_string(ff_status s)
     }
 }
 
-const char* ff_version(void) { return "ffint8 0.1 (gfx950)"; }
+const char* ff_version(void) { return "ffint8 0.2 (gfx950)"; }
 
 int32_t ff_goodness_shift(const ff_layer_desc* layer)
 {
     Dims d;
     if (layer_dims(layer, &d) != FF_OK) return -1;
     return goodness_shift(d.K, d.rps * d.N);
+}
+
+int32_t ff_layer_dw_chunks(const ff_layer_desc* layer)
+{
+    Dims d;
+    if (layer_dims(layer, &d) != FF_OK) return -1;
+    return d.n_chunks;
+}
+
+size_t ff_layer_workspace_bytes(const ff_layer_desc* layer)
+{
+    Dims d;
+    if (layer_dims(layer, &d) != FF_OK) return 0;
+    return FF_WS_MIN_BYTES + layer_scratch_bytes(d);
 }
 
 ff_status ff_quantize(const float* x, int64_t rows, int64_t cols, int32_t round_mode, uint64_t seed,
@@ -261,8 +469,6 @@ ff_status ff_quantize(const float* x, int64_t rows, int64_t cols, int32_t round_
 ff_status ff_layer_forward(const ff_layer_desc* layer, const int8_t* a_q, const int8_t* w_q, int32_t* acc,
                            uint64_t* gsum_int, int32_t* vmax, void* ws, size_t ws_bytes, void* stream)
 {
-    (void)ws;
-    (void)ws_bytes;
     Dims d;
     const ff_status st = layer_dims(layer, &d);
     if (st != FF_OK) return st;
@@ -270,29 +476,18 @@ ff_status ff_layer_forward(const ff_layer_desc* layer, const int8_t* a_q, const 
     if (!aligned16(a_q) || !aligned16(w_q) || !aligned16(acc) || (((uintptr_t)gsum_int) & 7) || !aligned4(vmax))
         return FF_ERR_ALIGN;
     if (d.K > INT32_SAFE_LEN) return FF_ERR_OVERFLOW_BOUND;
+    const bool need_col = d.kind == FF_CONV2D && !d.implicit;
+    if (need_col) {
+        if (!ws) return FF_ERR_INVALID_ARG;
+        if (!aligned16(ws)) return FF_ERR_ALIGN;
+        if (ws_bytes < FF_WS_MIN_BYTES + layer_scratch_bytes(d)) return FF_ERR_WORKSPACE;
+    }
     hipStream_t s = (hipStream_t)stream;
     if (d.B == 0) return FF_OK;
     HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)gsum_int, 2 * d.B, 0u, s));
     HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)vmax, d.B, 0u, s));
-    GemmArgs g;
-    memset(&g, 0, sizeof(g));
-    g.P = a_q;
-    g.Q = w_q;
-    g.C = acc;
-    g.I = (int32_t)d.M;
-    g.J = (int32_t)d.N;
-    g.R = (int32_t)d.K;
-    g.ldp = pitch8(d.K);
-    g.ldq = pitch8(d.K);
-    g.ldc = pitch32(d.N);
-    g.gsum = (unsigned long long*)gsum_int;
-    g.vmax = vmax;
-    g.rows_per_sample = (int32_t)d.rps;
-    g.relu = layer->relu ? 1 : 0;
-    g.rshift = goodness_shift(d.K, d.rps * d.N);
-    g.nb = 1;
-    HIPCHK_T(FF_K_GEMM_FWD, launch_gemm_nt_i8(g, s));
-    return FF_OK;
+    int8_t* col = need_col ? (int8_t*)ws + FF_WS_MIN_BYTES : nullptr;
+    return run_forward(d, layer->relu ? 1 : 0, a_q, 0, w_q, acc, 0, (unsigned long long*)gsum_int, vmax, 0, col, 0, 1, s);
 }
 
 ff_status ff_goodness_loss(const ff_layer_desc* layer, const uint64_t* gsum_int, const int32_t* vmax,
@@ -395,11 +590,11 @@ ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc
     if (!acc || !vmax || !s_a || !s_w || !coeff_total || !a_q_t || !gy_q_t || !s_g || !dw_acc || !ws)
         return FF_ERR_INVALID_ARG;
     if (round_mode != FF_ROUND_NEAREST_EVEN && round_mode != FF_ROUND_STOCHASTIC) return FF_ERR_INVALID_ARG;
-    if (ws_bytes < FF_WS_MIN_BYTES) return FF_ERR_WORKSPACE;
+    if (ws_bytes < FF_WS_MIN_BYTES + layer_scratch_bytes(d)) return FF_ERR_WORKSPACE;
     if (!aligned16(acc) || !aligned16(a_q_t) || !aligned16(gy_q_t) || !aligned16(dw_acc) || !aligned16(ws))
         return FF_ERR_ALIGN;
-    if (d.M > INT32_SAFE_LEN) return FF_ERR_OVERFLOW_BOUND;
     hipStream_t s = (hipStream_t)stream;
+    if (d.B == 0) return FF_OK;
     uint32_t* slot = (uint32_t*)ws;
     HIPCHK_T(FF_K_SMALL, launch_grad_amax(coeff_total, vmax, s_a, s_w, d.B, slot, s));
     QuantArgs a;
@@ -421,21 +616,8 @@ ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc
     a.scale = s_g;
     a.nb = 1;
     HIPCHK_T(FF_K_QUANT_GRAD, launch_quantize(QSRC_GRAD, a, s));
-    GemmArgs g;
-    memset(&g, 0, sizeof(g));
-    g.P = gy_q_t;
-    g.Q = a_q_t;
-    g.C = dw_acc;
-    g.I = (int32_t)d.N;
-    g.J = (int32_t)d.K;
-    g.R = (int32_t)d.M;
-    g.ldp = pitch8(d.M);
-    g.ldq = pitch8(d.M);
-    g.ldc = pitch32(d.K);
-    g.nb = 1;
-    g.rows_per_sample = 1;
-    HIPCHK_T(FF_K_GEMM_DW, launch_gemm_nt_i8(g, s));
-    return FF_OK;
+    const int64_t dw_elems = d.N * pitch32(d.K);
+    return run_wgrad(d, gy_q_t, 0, a_q_t, 0, (int8_t*)ws + FF_WS_MIN_BYTES, 0, dw_acc, 0, dw_elems, 1, s);
 }
 
 ff_status ff_layer_update(const ff_layer_desc* layer, float* w_master, const int32_t* dw_acc_pos,
@@ -452,22 +634,26 @@ ff_status ff_layer_update(const ff_layer_desc* layer, float* w_master, const int
     if (ws_bytes < FF_WS_MIN_BYTES) return FF_ERR_WORKSPACE;
     if (!aligned4(w_master) || !aligned16(dw_acc_pos) || !aligned16(dw_acc_neg) || !aligned16(w_q) || !aligned16(ws))
         return FF_ERR_ALIGN;
+    if (d.n_chunks > MAX_CHUNKS) return FF_ERR_UNSUPPORTED;
     hipStream_t s = (hipStream_t)stream;
     uint32_t* slot = (uint32_t*)ws;
     HIPCHK_T(FF_K_SMALL, launch_fill_u32(slot, 1, 0u, s));
+    const int64_t dw_elems = d.N * pitch32(d.K);
     UpdateArgs u;
     memset(&u, 0, sizeof(u));
     u.w = w_master;
     u.N = d.N;
     u.K = d.K;
     u.lddw = pitch32(d.K);
-    u.n_terms = 2;
-    u.dw[0] = dw_acc_pos;
-    u.s_g[0] = s_g_pos;
-    u.s_a[0] = s_a_pos;
-    u.dw[1] = dw_acc_neg;
-    u.s_g[1] = s_g_neg;
-    u.s_a[1] = s_a_neg;
+    u.n_terms = 2 * d.n_chunks;
+    for (int c = 0; c < d.n_chunks; ++c) {
+        u.dw[c] = dw_acc_pos + c * dw_elems;
+        u.s_g[c] = s_g_pos;
+        u.s_a[c] = s_a_pos;
+        u.dw[d.n_chunks + c] = dw_acc_neg + c * dw_elems;
+        u.s_g[d.n_chunks + c] = s_g_neg;
+        u.s_a[d.n_chunks + c] = s_a_neg;
+    }
     u.lr = lr;
     u.total_samples = total_samples;
     u.w_amax_bits = slot;
@@ -526,21 +712,22 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
     float* ct = (float*)(base + w.off_ct);
 
     HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)base, (int64_t)(w.zero_bytes / 4), 0u, s));
-    const int64_t n_in = w.d[0].M * w.d[0].in_cols;
-    HIPCHK_T(FF_K_ABSMAX, launch_absmax(x_pos, ((intptr_t)x_neg - (intptr_t)x_pos) / (intptr_t)sizeof(float), 2, n_in,
-                                        act_amax, s));
+    const int64_t n_in = w.d[0].in_rows * w.d[0].in_cols;
+    const int64_t st_x = ((intptr_t)x_neg - (intptr_t)x_pos) / (intptr_t)sizeof(float);
+    HIPCHK_T(FF_K_ABSMAX, launch_absmax(x_pos, st_x, 2, n_in, act_amax, s));
 
     // ---- forward pass through all layers, both data sets together (Algorithm 1) -----------------
     for (int i = 0; i < k; ++i) {
         const Dims& d = w.d[i];
         const ff_layer_desc& L = net->layers[i];
+        const bool dense = d.kind == FF_DENSE;
         QuantArgs a;
         memset(&a, 0, sizeof(a));
         int src;
         if (i == 0) {
             src = QSRC_F32;
             a.x = x_pos;
-            a.st_x = ((intptr_t)x_neg - (intptr_t)x_pos) / (intptr_t)sizeof(float);
+            a.st_x = st_x;
             a.rows_per_sample = 1;
         } else {
             const Dims& dp = w.d[i - 1];
@@ -564,41 +751,26 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         a.round_mode = FF_ROUND_STOCHASTIC;
         a.key = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 0, FF_KIND_ACT));
         a.key2 = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 1, FF_KIND_ACT));
-        a.rows = d.M;
+        a.rows = d.in_rows;
         a.cols = d.in_cols;
-        a.q = (int8_t*)(base + w.off_aq);
-        a.st_q = (int64_t)w.st_aq;
-        a.ldq = pitch8(d.K);
-        a.q_t = (int8_t*)(base + w.off_aqt[i]);
-        a.st_qt = (int64_t)w.st_aqt[i];
-        a.ldqt = pitch8(d.M);
+        a.q = (int8_t*)(base + w.off_aq[i]);
+        a.st_q = (int64_t)w.st_aq[i];
+        a.ldq = pitch8(d.in_cols);
+        if (dense) {
+            a.q_t = (int8_t*)(base + w.off_aqt[i]);
+            a.st_qt = (int64_t)w.st_aqt[i];
+            a.ldqt = pitch8(d.M);
+        }
         a.scale = s_a + 2 * i;
         a.st_scale = 1;
         a.nb = 2;
         HIPCHK_T(FF_K_QUANT_ACT, launch_quantize(src, a, s));
 
-        GemmArgs g;
-        memset(&g, 0, sizeof(g));
-        g.P = (const int8_t*)(base + w.off_aq);
-        g.st_p = (int64_t)w.st_aq;
-        g.Q = state->w_q[i];
-        g.st_q = 0;
-        g.C = (int32_t*)(base + w.off_acc[i]);
-        g.st_c = (int64_t)(w.st_acc[i] / sizeof(int32_t));
-        g.I = (int32_t)d.M;
-        g.J = (int32_t)d.N;
-        g.R = (int32_t)d.K;
-        g.ldp = pitch8(d.K);
-        g.ldq = pitch8(d.K);
-        g.ldc = pitch32(d.N);
-        g.gsum = gsum + (int64_t)i * 2 * B;
-        g.vmax = vmax + (int64_t)i * 2 * B;
-        g.st_g = B;
-        g.rows_per_sample = (int32_t)d.rps;
-        g.relu = L.relu ? 1 : 0;
-        g.rshift = goodness_shift(d.K, d.rps * d.N);
-        g.nb = 2;
-        HIPCHK_T(FF_K_GEMM_FWD, launch_gemm_nt_i8(g, s));
+        const ff_status fs = run_forward(d, L.relu ? 1 : 0, (const int8_t*)(base + w.off_aq[i]), (int64_t)w.st_aq[i],
+                                         state->w_q[i], (int32_t*)(base + w.off_acc[i]),
+                                         (int64_t)(w.st_acc[i] / sizeof(int32_t)), gsum + (int64_t)i * 2 * B,
+                                         vmax + (int64_t)i * 2 * B, B, (int8_t*)(base + w.off_col), (int64_t)w.st_col, 2, s);
+        if (fs != FF_OK) return fs;
 
         GoodnessArgs ga;
         memset(&ga, 0, sizeof(ga));
@@ -606,7 +778,7 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         ga.vmax = vmax + (int64_t)i * 2 * B;
         ga.s_a = s_a + 2 * i;
         ga.s_w = state->s_w[i];
-        ga.rshift = g.rshift;
+        ga.rshift = goodness_shift(d.K, d.rps * d.N);
         ga.l2norm = L.l2norm_out ? 1 : 0;
         ga.pass_sign = FF_PASS_POS;
         ga.theta = theta;
@@ -644,6 +816,7 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
     for (int i = 0; i < k; ++i) {
         const Dims& d = w.d[i];
         const ff_layer_desc& L = net->layers[i];
+        const bool dense = d.kind == FF_DENSE;
         QuantArgs a;
         memset(&a, 0, sizeof(a));
         a.acc = (const int32_t*)(base + w.off_acc[i]);
@@ -671,23 +844,13 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         a.nb = 2;
         HIPCHK_T(FF_K_QUANT_GRAD, launch_quantize(QSRC_GRAD, a, s));
 
-        GemmArgs g;
-        memset(&g, 0, sizeof(g));
-        g.P = (const int8_t*)(base + w.off_gy);
-        g.st_p = (int64_t)w.st_gy;
-        g.Q = (const int8_t*)(base + w.off_aqt[i]);
-        g.st_q = (int64_t)w.st_aqt[i];
-        g.C = (int32_t*)(base + w.off_dw);
-        g.st_c = (int64_t)(w.st_dw / sizeof(int32_t));
-        g.I = (int32_t)d.N;
-        g.J = (int32_t)d.K;
-        g.R = (int32_t)d.M;
-        g.ldp = pitch8(d.M);
-        g.ldq = pitch8(d.M);
-        g.ldc = pitch32(d.K);
-        g.rows_per_sample = 1;
-        g.nb = 2;
-        HIPCHK_T(FF_K_GEMM_DW, launch_gemm_nt_i8(g, s));
+        const int64_t dw_elems = (int64_t)(w.dw_bytes / sizeof(int32_t));
+        const ff_status ws_ = run_wgrad(d, (const int8_t*)(base + w.off_gy), (int64_t)w.st_gy,
+                                        dense ? (const int8_t*)(base + w.off_aqt[i]) : (const int8_t*)(base + w.off_aq[i]),
+                                        dense ? (int64_t)w.st_aqt[i] : (int64_t)w.st_aq[i], (int8_t*)(base + w.off_col),
+                                        (int64_t)w.st_col, (int32_t*)(base + w.off_dw),
+                                        (int64_t)(w.st_dw / sizeof(int32_t)), dw_elems, 2, s);
+        if (ws_ != FF_OK) return ws_;
 
         UpdateArgs u;
         memset(&u, 0, sizeof(u));
@@ -695,12 +858,14 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         u.N = d.N;
         u.K = d.K;
         u.lddw = pitch32(d.K);
-        u.n_terms = 2;
-        for (int p = 0; p < 2; ++p) {
-            u.dw[p] = (const int32_t*)(base + w.off_dw + p * w.st_dw);
-            u.s_g[p] = s_g + 2 * i + p;
-            u.s_a[p] = s_a + 2 * i + p;
-        }
+        u.n_terms = 2 * d.n_chunks;
+        for (int p = 0; p < 2; ++p)
+            for (int cc = 0; cc < d.n_chunks; ++cc) {
+                const int t = p * d.n_chunks + cc;
+                u.dw[t] = (const int32_t*)(base + w.off_dw + p * w.st_dw + cc * w.dw_bytes);
+                u.s_g[t] = s_g + 2 * i + p;
+                u.s_a[t] = s_a + 2 * i + p;
+            }
         u.lr = lr;
         u.total_samples = (int32_t)(2 * B);
         u.w_amax_bits = w_amax + i;

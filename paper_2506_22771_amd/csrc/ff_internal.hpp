@@ -127,7 +127,30 @@ struct GemmArgs {
     // batching over blockIdx.z
     int32_t nb;
     int64_t st_p, st_q, st_c, st_g;
+    // split reduction (blockIdx.y): each split adds its partial sums into a pre-zeroed C with integer atomics
+    // (exact and order-free).  1 = plain stores.  Not combined with the fused reductions.
+    int32_t splits;
+    // implicit-GEMM convolution (conv != 0): P is an NHWC int8 tensor [B, H, W, cpitch] and row i of the
+    // contraction is output pixel (b, ho, wo); reduction index r = (kh*ks + kw)*Cin + ci.  Cin % 16 == 0.
+    int32_t conv, H, W, Cin, cpitch, ks, stride, pad, Ho, Wo;
+    int64_t p_bytes;  // bytes of one P tensor (conv only; must be < 2^31)
 };
 hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s);
+int gemm_pick_splits(int64_t I, int64_t J, int64_t R, int nb);
+
+// ---- explicit im2col (conv.hip) ----------------------------------------------------------------------
+struct ConvGeom {
+    int32_t H, W, Cin, cpitch, ks, stride, pad, Ho, Wo;
+};
+struct Im2colArgs {
+    const int8_t* a;  // NHWC int8 [B, H, W, cpitch]
+    int8_t* out;      // transposed: [K, ld_out] over samples [b0, b1); row-major: [(b1-b0)*Ho*Wo, ld_out]
+    ConvGeom g;
+    int32_t K, b0, b1;
+    int64_t ld_out;
+    int32_t nb;
+    int64_t st_a, st_out;
+};
+hipError_t launch_im2col(const Im2colArgs& p, bool transposed, hipStream_t s);
 
 }  // namespace ffi

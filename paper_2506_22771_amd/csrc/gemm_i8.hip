@@ -36,14 +36,26 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt range");
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
-__device__ __forceinline__ void lds_dma16(__amdgpu_buffer_rsrc_t rsrc, int voffset, unsigned lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(voffset), "s"(rsrc) : "memory", "m0");
+// 16 bytes per lane from a buffer (byte offset voffset + soffset) straight into LDS at lds_base + lane*16.
+// The compiler is not told about the LDS write, so it adds no waits of its own: completion is tracked by
+// hand with vmcnt.  Out-of-range offsets read as zero (buffer range check).
+__device__ __forceinline__ void lds_dma16(__amdgpu_buffer_rsrc_t rsrc, int voffset, int soffset, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset) : "memory", "m0");
+}
+constexpr int OOB = 0x7FFFFFF0;  // a byte offset beyond any buffer
+__device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int d)
+{
+    const unsigned lo = (unsigned)__shfl_xor((int)(unsigned)v, d), hi = (unsigned)__shfl_xor((int)(unsigned)(v >> 32), d);
+    return ((unsigned long long)hi << 32) | lo;
 }
 __device__ __forceinline__ int swz(int row, int kc) { return row * BK + ((kc ^ ((row >> 1) & 7)) << 4); }
 
-template <int BM, int BN, int WM, int WN, bool EPI>
+// MODE 0: store C; 1: store C and accumulate the per-sample goodness sums / maxima; 2: add into C atomically
+// (split reduction).
+template <int BM, int BN, int WM, int WN, int MODE, bool CONV>
 __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
 {
+    constexpr bool EPI = MODE == 1;
     constexpr int T = WM * WN * 64;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int TI = WTM / 32, TJ = WTN / 32;
@@ -63,28 +75,60 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int Rpad = (a.R + 15) & ~15;
-    const int nk = (Rpad + BK - 1) / BK;
+    const int nk_all = (Rpad + BK - 1) / BK;
+    // this workgroup's share of the reduction steps
+    const int nk_per = (nk_all + a.splits - 1) / a.splits;
+    const int kt0 = MODE == 2 ? (int)blockIdx.y * nk_per : 0;
+    const int nk = MODE == 2 ? min(nk_all, kt0 + nk_per) : nk_all;
+    if (MODE == 2 && kt0 >= nk) return;
 
     const int rows_p = min(BM, a.I - i0), rows_q = min(BN, a.J - j0);
-    __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc((void*)(P + (int64_t)i0 * a.ldp), 0, (int)(rows_p * a.ldp), 0x00020000);
+    __amdgpu_buffer_rsrc_t rp = CONV ? __builtin_amdgcn_make_buffer_rsrc((void*)P, 0, (int)a.p_bytes, 0x00020000)
+                                     : __builtin_amdgcn_make_buffer_rsrc((void*)(P + (int64_t)i0 * a.ldp), 0, (int)(rows_p * a.ldp), 0x00020000);
     __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc((void*)(Q + (int64_t)j0 * a.ldq), 0, (int)(rows_q * a.ldq), 0x00020000);
+    // Every chunk of one thread has the same k column: chunk index c = s*T + tid, T a multiple of 8,
+    // LDS slot (row = c >> 3, c & 7) holds reduction chunk (c & 7) ^ ((row >> 1) & 7) of that row.
+    const int kcol = (((tid & 7) ^ ((tid >> 4) & 7))) * 16;
     int offP[CH_P], offQ[CH_Q];
-    // every chunk of one thread has the same k column: chunk index c = s*T + tid, T multiple of 8
-    const int kcol = (((tid & 7) ^ ((tid >> 4) & 7))) * 16;   // (c & 7) ^ ((row >> 1) & 7), row = c >> 3
+    int hi0[CONV ? CH_P : 1], wi0[CONV ? CH_P : 1];   // conv: input pixel of tap (0,0) for the chunk's output pixel
 #pragma unroll
-    for (int s = 0; s < CH_P; ++s) offP[s] = ((s * T + tid) >> 3) * (int)a.ldp + kcol;
+    for (int s = 0; s < CH_P; ++s) {
+        const int row = (s * T + tid) >> 3;
+        if (CONV) {
+            const int m = i0 + row;
+            const int b = m / (a.Ho * a.Wo), rem = m - b * (a.Ho * a.Wo);
+            const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
+            hi0[s] = m < a.I ? ho * a.stride - a.pad : -(1 << 20);   // rows beyond the matrix never pass the bounds test
+            wi0[s] = wo * a.stride - a.pad;
+            offP[s] = ((b * a.H + hi0[s]) * a.W + wi0[s]) * a.cpitch;
+        } else {
+            offP[s] = row * (int)a.ldp + kcol;
+        }
+    }
 #pragma unroll
     for (int s = 0; s < CH_Q; ++s) offQ[s] = ((s * T + tid) >> 3) * (int)a.ldq + kcol;
     auto issue = [&](int kt, int buf) {
         const int k0 = kt * BK;
-        const bool ok = k0 + kcol < Rpad;
+        const bool ok = k0 + kcol < Rpad;   // only the last step can have chunks beyond the reduction length
         int8_t* base = lds + buf * STAGE_BYTES;
+        if (CONV) {
+            const int k = k0 + kcol;
+            const int tap = k / a.Cin, ci0 = k - tap * a.Cin;
+            const int kh = tap / a.ks, kw = tap - kh * a.ks;
+            const int dk = (kh * a.W + kw) * a.cpitch + ci0;
 #pragma unroll
-        for (int s = 0; s < CH_P; ++s)
-            lds_dma16(rp, ok ? offP[s] + k0 : 0x7FFFFFF0, (unsigned)(uintptr_t)(base + (s * T + wave * 64) * 16));
+            for (int s = 0; s < CH_P; ++s) {
+                const bool in = ok && (unsigned)(hi0[s] + kh) < (unsigned)a.H && (unsigned)(wi0[s] + kw) < (unsigned)a.W;
+                lds_dma16(rp, in ? offP[s] + dk : OOB, 0, (unsigned)(uintptr_t)(base + (s * T + wave * 64) * 16));
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < CH_P; ++s)
+                lds_dma16(rp, ok ? offP[s] : OOB - k0, k0, (unsigned)(uintptr_t)(base + (s * T + wave * 64) * 16));
+        }
 #pragma unroll
         for (int s = 0; s < CH_Q; ++s)
-            lds_dma16(rq, ok ? offQ[s] + k0 : 0x7FFFFFF0, (unsigned)(uintptr_t)(base + BM * BK + (s * T + wave * 64) * 16));
+            lds_dma16(rq, ok ? offQ[s] : OOB - k0, k0, (unsigned)(uintptr_t)(base + BM * BK + (s * T + wave * 64) * 16));
     };
 
     v16i acc[TI][TJ];
@@ -111,12 +155,12 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
                 acc[ti][tj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fq[set][tj], fp[set][ti], acc[ti][tj], 0, 0, 0);
     };
 
-    issue(0, 0);
+    issue(kt0, 0);
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     ldfrag(0, lds, 0);
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
+    for (int kt = kt0; kt < nk; ++kt) {
+        const int cur = (kt - kt0) & 1;
         const int8_t* sb = lds + cur * STAGE_BYTES;
         const int8_t* sn = lds + (cur ^ 1) * STAGE_BYTES;
         if (kt + 1 < nk) issue(kt + 1, cur ^ 1);
@@ -147,7 +191,12 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
                 const int c2 = acc[ti][tj][4 * g + 2], c3 = acc[ti][tj][4 * g + 3];
                 if (i < a.I) {
                     int32_t* dst = C + (int64_t)i * a.ldc + j;
-                    if (j + 3 < a.J) {
+                    if (MODE == 2) {
+                        if (j + 0 < a.J) atomicAdd(dst + 0, c0);
+                        if (j + 1 < a.J) atomicAdd(dst + 1, c1);
+                        if (j + 2 < a.J) atomicAdd(dst + 2, c2);
+                        if (j + 3 < a.J) atomicAdd(dst + 3, c3);
+                    } else if (j + 3 < a.J) {
                         *(v4i*)dst = (v4i){c0, c1, c2, c3};
                     } else {
                         if (j + 0 < a.J) dst[0] = c0;
@@ -169,11 +218,24 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
             }
         }
         if (EPI) {
-            const unsigned lo = (unsigned)sq, hi = (unsigned)(sq >> 32);
-            const unsigned lo2 = (unsigned)__shfl_xor((int)lo, 32), hi2 = (unsigned)__shfl_xor((int)hi, 32);
-            sq += ((unsigned long long)hi2 << 32) | lo2;
+            // the two half-waves hold the two column halves of the same row
+            sq += shfl_xor_u64(sq, 32);
             vm = max(vm, __shfl_xor(vm, 32));
-            if (lh == 0 && i < a.I) {
+            if ((a.rows_per_sample & 31) == 0) {
+                // all 32 rows of this MFMA tile belong to one sample (convolution): one atomic per wave.
+                // Rows beyond the matrix hold exact zeros and add nothing.
+#pragma unroll
+                for (int d = 1; d < 32; d <<= 1) {
+                    sq += shfl_xor_u64(sq, d);
+                    vm = max(vm, __shfl_xor(vm, d));
+                }
+                const int i_first = i0 + wm * WTM + ti * 32;
+                if (lane == 0 && i_first < a.I) {
+                    const int smp = i_first / a.rows_per_sample;
+                    atomicAdd(a.gsum + z * a.st_g + smp, sq);
+                    atomicMax(a.vmax + z * a.st_g + smp, vm);
+                }
+            } else if (lh == 0 && i < a.I) {
                 const int smp = i / a.rows_per_sample;
                 atomicAdd(a.gsum + z * a.st_g + smp, sq);
                 atomicMax(a.vmax + z * a.st_g + smp, vm);
@@ -187,22 +249,58 @@ template <int BM, int BN, int WM, int WN>
 static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s)
 {
     const int tiles_i = (a.I + BM - 1) / BM, tiles_j = (a.J + BN - 1) / BN;
-    const dim3 grid((unsigned)(tiles_i * tiles_j), 1, (unsigned)a.nb), block(WM * WN * 64);
-    if (a.gsum) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, false>), grid, block, 0, s, a);
+    const dim3 grid((unsigned)(tiles_i * tiles_j), (unsigned)a.splits, (unsigned)a.nb), block(WM * WN * 64);
+    const int mode = a.splits > 1 ? 2 : (a.gsum ? 1 : 0);
+    if (a.conv) {
+        if (mode == 1) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 1, true>), grid, block, 0, s, a);
+        else if (mode == 0) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 0, true>), grid, block, 0, s, a);
+        else return hipErrorInvalidValue;
+    } else {
+        if (mode == 1) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 1, false>), grid, block, 0, s, a);
+        else if (mode == 0) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 0, false>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 2, false>), grid, block, 0, s, a);
+    }
     return hipGetLastError();
+}
+
+// Number of reduction splits that fills the chip when the output alone has too few tiles (the
+// weight-gradient contraction of a convolution: few output elements, a very long reduction).
+int gemm_pick_splits(int64_t I, int64_t J, int64_t R, int nb)
+{
+    const int bm = I > 128 ? 256 : (I > 64 ? 128 : 64), bn = J > 128 ? 256 : (J > 64 ? 128 : 64);
+    const int64_t tiles = ((I + bm - 1) / bm) * ((J + bn - 1) / bn) * nb;
+    const int64_t nk = (R + BK - 1) / BK;
+    if (tiles >= 384 || nk < 16) return 1;
+    int64_t sp = (768 + tiles - 1) / tiles;          // aim at ~3 workgroups per compute unit
+    if (sp > nk / 8) sp = nk / 8;                    // at least 8 reduction steps per split
+    if (sp < 1) sp = 1;
+    return (int)sp;
 }
 
 hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s)
 {
     if (a.I <= 0 || a.J <= 0) return hipSuccess;
-    // tile-relative byte offsets of the operand copies are 32-bit
+    // byte offsets of the operand copies are 32-bit (tile-relative for dense operands, tensor-relative for conv)
     if (a.ldp >= (int64_t(1) << 22) || a.ldq >= (int64_t(1) << 22)) return hipErrorInvalidValue;
-    // pick the largest tile that still yields at least ~2 workgroups per compute unit
-    const int64_t want = 512;
-    auto tiles = [&](int bm, int bn) { return (int64_t)((a.I + bm - 1) / bm) * ((a.J + bn - 1) / bn) * a.nb; };
-    if (tiles(256, 256) >= want) return launch_cfg<256, 256, 4, 2>(a, s);
-    if (tiles(128, 128) >= want) return launch_cfg<128, 128, 2, 2>(a, s);
+    if (a.conv && (a.p_bytes >= (int64_t(1) << 31) || (a.Cin & 15) != 0)) return hipErrorInvalidValue;
+    if (a.splits < 1 || (a.splits > 1 && (a.gsum || a.conv))) return hipErrorInvalidValue;
+    // Tile: as wide as the output allows (a 256-wide tile on a 64-column output would waste three quarters
+    // of the MFMA work), and tall only if that still leaves about two workgroups per compute unit.
+    const int bn = a.J > 128 ? 256 : (a.J > 64 ? 128 : 64);
+    auto tiles = [&](int bm) { return (int64_t)((a.I + bm - 1) / bm) * ((a.J + bn - 1) / bn) * a.nb * a.splits; };
+    const int bm = (a.I > 128 && tiles(256) >= 512) ? 256 : ((a.I > 64 && tiles(128) >= 512) ? 128 : 64);
+    if (bn == 256) {
+        if (bm == 256) return launch_cfg<256, 256, 4, 2>(a, s);
+        if (bm == 128) return launch_cfg<128, 256, 2, 2>(a, s);
+        return launch_cfg<64, 256, 1, 4>(a, s);
+    }
+    if (bn == 128) {
+        if (bm == 256) return launch_cfg<256, 128, 4, 2>(a, s);
+        if (bm == 128) return launch_cfg<128, 128, 2, 2>(a, s);
+        return launch_cfg<64, 128, 2, 2>(a, s);
+    }
+    if (bm == 256) return launch_cfg<256, 64, 4, 1>(a, s);
+    if (bm == 128) return launch_cfg<128, 64, 4, 1>(a, s);
     return launch_cfg<64, 64, 2, 2>(a, s);
 }
 

@@ -54,3 +54,11 @@ def rel_close(got, ref, tol=1e-5):
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
     return np.all(np.abs(got - ref) <= tol * np.abs(ref) + 1e-38)
+
+
+def pad_nhwc(a: np.ndarray) -> np.ndarray:
+    """int8 [B, H, W, C] -> [B, H, W, ff_pitch(C)] with zero pad channels."""
+    B, H, W, C = a.shape
+    out = np.zeros((B, H, W, ff.ff_pitch(C)), np.int8)
+    out[..., :C] = a
+    return out

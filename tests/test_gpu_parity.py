@@ -23,7 +23,7 @@ def ff():
     return m
 
 
-from gpu_util import check_q, dev, empty32, empty8, pad32, pad8, rel_close, scalar, workspace  # noqa: E402
+from gpu_util import check_q, dev, empty32, empty8, pad32, pad8, pad_nhwc, rel_close, scalar, workspace  # noqa: E402
 
 TOL = 1e-5
 
@@ -210,13 +210,103 @@ def test_backward_local_and_update(ff, B, K, N):
     check_q(d_wq, wq_new_ref, "w_q")
 
 
+# ------------------------------------------------------------------------------------------- convolution
+CONV_CASES = [  # B, H, W, Cin, Cout, ks, stride
+    (3, 6, 11, 3, 8, 3, 1),      # C_in = 3: explicit patch matrix, 66 rows per sample
+    (2, 8, 8, 16, 32, 3, 1),     # implicit GEMM, 64 rows per sample (one atomic per wave)
+    (5, 9, 12, 32, 24, 3, 2),    # stride 2, odd height
+    (4, 10, 6, 64, 40, 1, 2),    # 1x1 stride 2
+    (6, 7, 5, 48, 16, 1, 1),     # 1x1
+    (9, 16, 16, 128, 72, 3, 1),  # several reduction steps, 256 rows per sample, more than one row tile
+]
+
+
+@pytest.mark.parametrize("B,H,W,Cin,Cout,ks,stride", CONV_CASES)
+def test_conv_forward_and_backward(ff, B, H, W, Cin, Cout, ks, stride):
+    rng = np.random.default_rng(B * 100 + Cin)
+    pad = ks // 2
+    layer = Layer("conv", H=H, W=W, C_in=Cin, C_out=Cout, ksize=ks, stride=stride, pad=pad)
+    desc = ff.layer_desc(layer, B)
+    a_q = rng.integers(-127, 128, (B, H, W, Cin)).astype(np.int8)
+    w = (rng.standard_normal((Cout, ks, ks, Cin)) * 0.05).astype(np.float32)
+    w_q, s_w = O.quantize(w, 0)
+    s_a = np.float32(0.0041)
+    K, M, rps = layer.K, B * layer.rows_per_sample, layer.rows_per_sample
+    acc_ref = O.conv_forward(a_q, w_q, stride, pad)
+    r = O.goodness_shift(K, layer.terms_per_sample)
+    assert ff.ff_goodness_shift(desc) == r
+    g_ref = O.goodness(acc_ref, 1, r, s_a, s_w)
+    ws = workspace(ff.ff_layer_workspace_bytes(desc))
+    d_aq = dev(pad_nhwc(a_q))
+    acc = empty32(M, Cout)
+    gsum = torch.full((B,), 7, dtype=torch.int64, device="cuda")
+    vmax = torch.full((B,), 9, dtype=torch.int32, device="cuda")
+    ff.ff_layer_forward(desc, d_aq, dev(pad8(w_q.reshape(Cout, K))), acc, gsum, vmax, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(acc.cpu().numpy()[:, :Cout], acc_ref.reshape(M, Cout))
+    np.testing.assert_array_equal(gsum.cpu().numpy().view(np.uint64), g_ref["g_int"])
+    np.testing.assert_array_equal(vmax.cpu().numpy(), g_ref["vmax"])
+    # local gradient + weight gradient
+    ct = (rng.standard_normal(B) * 0.3).astype(np.float32)
+    g = O.local_grad(acc_ref, 1, s_a, s_w, ct)
+    gq_ref, sg_ref = O.quantize(g, 1, 4, 55)
+    assert ff.ff_layer_dw_chunks(desc) == 1
+    dw_ref = O.conv_wgrad(gq_ref, a_q, ks, stride, pad, 0, B)
+    gy_t, s_g, dw = empty8(Cout, M), scalar(), empty32(Cout, K)
+    ff.ff_layer_backward_local(desc, dev(pad32(acc_ref.reshape(M, Cout))), dev(g_ref["vmax"]), dev(np.array([s_a])),
+                               dev(np.array([s_w])), dev(ct), 1, 4, 55, d_aq, gy_t, s_g, dw, ws)
+    torch.cuda.synchronize()
+    assert s_g.item() == sg_ref
+    check_q(gy_t, gq_ref.reshape(M, Cout).T, "conv gy_q_t")
+    np.testing.assert_array_equal(dw.cpu().numpy()[:, :K], dw_ref.reshape(Cout, K))
+
+
+def test_conv_weight_gradient_chunks(ff):
+    """A reduction over more than 133144 output pixels is split into sample blocks with separate int32
+    accumulators (here 128 + 12 images of 32x32), combined by ff_layer_update in chunk order."""
+    rng = np.random.default_rng(77)
+    B, H, W, Cin, Cout = 140, 32, 32, 16, 16
+    layer = Layer("conv", H=H, W=W, C_in=Cin, C_out=Cout, ksize=3, stride=1, pad=1)
+    desc = ff.layer_desc(layer, B)
+    K, M = layer.K, B * H * W
+    assert ff.ff_layer_dw_chunks(desc) == 2 and O.batch_chunks(B, H * W) == [(0, 128), (128, 140)]
+    a_q = rng.integers(-127, 128, (B, H, W, Cin)).astype(np.int8)
+    w = (rng.standard_normal((Cout, 3, 3, Cin)) * 0.05).astype(np.float32)
+    w_q, s_w = O.quantize(w, 0)
+    s_a = np.float32(0.0041)
+    acc = O.conv_forward(a_q, w_q, 1, 1)
+    gd = O.goodness(acc, 1, O.goodness_shift(K, layer.terms_per_sample), s_a, s_w)
+    ws = workspace(ff.ff_layer_workspace_bytes(desc))
+    d_aq, d_acc, d_vmax = dev(pad_nhwc(a_q)), dev(pad32(acc.reshape(M, Cout))), dev(gd["vmax"])
+    d_sa, d_sw = dev(np.array([s_a])), dev(np.array([s_w]))
+    out, refs = [], []
+    for p in range(2):
+        ct = (rng.standard_normal(B) * 0.3).astype(np.float32)
+        gq, sg = O.quantize(O.local_grad(acc, 1, s_a, s_w, ct), 1, 4, 60 + p)
+        chunks = [O.conv_wgrad(gq, a_q, 3, 1, 1, b0, b1).reshape(-1) for b0, b1 in O.batch_chunks(B, H * W)]
+        gy_t, s_g = empty8(Cout, M), scalar()
+        dw = torch.full((2, Cout, ff.ff_pitch32(K)), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+        ff.ff_layer_backward_local(desc, d_acc, d_vmax, d_sa, d_sw, dev(ct), 1, 4, 60 + p, d_aq, gy_t, s_g, dw, ws)
+        torch.cuda.synchronize()
+        assert s_g.item() == sg
+        for c in range(2):
+            np.testing.assert_array_equal(dw[c].cpu().numpy()[:, :K].reshape(-1), chunks[c])
+        out.append((dw, s_g))
+        refs.append((chunks, sg))
+    w_ref = O.update(w, refs[0][0] + refs[1][0], [refs[0][1]] * 2 + [refs[1][1]] * 2, [s_a] * 4, 0.05, 2 * B)
+    d_w, d_wq, d_s = dev(w.reshape(Cout, K)), empty8(Cout, K), scalar()
+    ff.ff_layer_update(desc, d_w, out[0][0], out[0][1], d_sa, out[1][0], out[1][1], d_sa, 0.05, 2 * B, d_wq, d_s, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(d_w.cpu().numpy().reshape(-1), w_ref.reshape(-1))
+
+
 # ------------------------------------------------------------------------------------------- whole step
 def _run_steps(ff, wl, n_steps, lam=None):
     lam = wl.lam if lam is None else lam
     W = make_weights(wl)
     xp, xn = make_inputs(wl)
     k, B = len(wl.layers), wl.batch
-    d_w = [dev(w.reshape(w.shape[0], -1)) for w in W]
+    d_w = [dev(w.reshape(w.shape[0], -1)) for w in W]      # conv weights [C_out, k*k*C_in]
     d_wq = [empty8(l.N, l.K) for l in wl.layers]
     d_sw = [scalar() for _ in wl.layers]
     ws1 = workspace()
@@ -228,7 +318,7 @@ def _run_steps(ff, wl, n_steps, lam=None):
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     loss = torch.empty((k, 2), device="cuda")
     good = torch.empty((k, 2, B), device="cuda")
-    d_xp, d_xn = dev(xp.reshape(B, -1)), dev(xn.reshape(B, -1))
+    d_xp, d_xn = dev(xp), dev(xn)
     Wref = W
     for step in range(n_steps):
         ff.ff_train_step(net, d_xp, d_xn, wl.theta, lam, wl.lr, wl.sr_seed, step, loss, good, ws)
@@ -245,9 +335,18 @@ def _run_steps(ff, wl, n_steps, lam=None):
     return [t.cpu().numpy().copy() for t in d_w]
 
 
-@pytest.mark.parametrize("name,steps", [("tiny", 3), ("tiny_l2", 3), ("cfg1", 3), ("cfg2", 1)])
+@pytest.mark.parametrize("name,steps", [("tiny", 3), ("tiny_l2", 3), ("cfg1", 3), ("cfg2", 1), ("tiny_conv", 3),
+                                        ("tiny_conv16", 3), ("tiny_conv_s2", 3)])
 def test_train_step(ff, name, steps):
     _run_steps(ff, workload(name), steps)
+
+
+@pytest.mark.slow
+@pytest.mark.timeout(1200)
+def test_train_step_cfg3_full_size(ff):
+    """The small CNN (conv3x3 3->64->128->256 at 32x32, 256+256 images) at its full size: weight gradients in two
+    sample chunks, goodness sums with a 3-bit shift in the last layer."""
+    _run_steps(ff, workload("cfg3"), 1)
 
 
 @pytest.mark.slow

@@ -122,8 +122,16 @@ def workload(name: str) -> Workload:
         return Workload("tiny", mlp([100, 72, 52], False), 24, "uniform_onehot", lam=0.25)
     if name == "tiny_l2":
         return Workload("tiny_l2", mlp([100, 72, 52, 36], True), 24, "uniform_onehot", lam=0.25)
-    if name == "tiny_conv":
+    if name == "tiny_conv":     # C_in = 3 and 8: both layers take the explicit patch-matrix route
         return Workload("tiny_conv", conv_stack([3, 8, 16], 6, 11), 6, "uniform_onehot", lam=0.25)
+    if name == "tiny_conv16":   # second and third layer run as implicit GEMM; 8x8 maps: 64 rows per sample
+        return Workload("tiny_conv16", conv_stack([3, 16, 32, 16], 8, 12), 5, "uniform_onehot", lam=0.25)
+    if name == "tiny_conv_s2":  # stride 2 and 1x1 layers, as a ResNet-shaped stack needs them
+        layers = (Layer("conv", H=9, W=12, C_in=3, C_out=16, ksize=3, stride=1, pad=1),
+                  Layer("conv", H=9, W=12, C_in=16, C_out=32, ksize=3, stride=2, pad=1),
+                  Layer("conv", H=5, W=6, C_in=32, C_out=48, ksize=1, stride=2, pad=0),
+                  Layer("conv", H=3, W=3, C_in=48, C_out=16, ksize=1, stride=1, pad=0))
+        return Workload("tiny_conv_s2", layers, 7, "uniform_onehot", lam=0.25)
     raise KeyError(name)
 
 

@@ -364,7 +364,7 @@ static ff_status run_wgrad(const Dims& d, const int8_t* gy_t, int64_t st_gy, con
             g.st_q = st_colT;
             g.ldq = pitch8(mc);
         }
-        g.splits = gemm_pick_splits(g.I, g.J, g.R, nb);
+        g.splits = gemm_plan(g.I, g.J, g.R, nb, true).splits;
         if (g.splits > 1) {
             for (int z = 0; z < nb; ++z)
                 HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(g.C + z * st_dw), d.N * pitch32(d.K), 0u, s));

@@ -85,11 +85,86 @@ __global__ __launch_bounds__(256) void k_im2col(Im2colArgs p)
     }
 }
 
+// Fast transposed patches for stride 1 (3x3 pad 1 or 1x1) when W_out is a multiple of 16.
+// One workgroup: one sample, FT_RH output rows, FT_CT channels.  The input slab is staged channel-major in
+// LDS ([channel][row][padded column], zero borders), so that the 16 reduction bytes of an output chunk --
+// 16 consecutive output pixels of one row, one tap, one channel -- are 16 consecutive LDS bytes at the tap's
+// column offset: five aligned words and a byte alignment instead of sixteen byte gathers.  Lanes run over
+// the chunks of one colT row first: 16-byte stores, FT_RH * W_out contiguous bytes per (tap, channel).
+constexpr int FT_CT = 32;
+
+__global__ __launch_bounds__(256) void k_im2col_t_s1(Im2colArgs p, int RH)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t slab[];
+    const ConvGeom& g = p.g;
+    const int nbatch = p.b1 - p.b0;
+    const int z = blockIdx.z / nbatch, bl = blockIdx.z - z * nbatch, b = p.b0 + bl;
+    const int8_t* __restrict__ a = p.a + z * p.st_a;
+    int8_t* __restrict__ out = p.out + z * p.st_out;
+    const int ho0 = blockIdx.x * RH, c0 = blockIdx.y * FT_CT;
+    const int NR = RH + g.ks - 1;                    // input rows of the slab
+    const int WP = (g.W + 2 * g.pad + 3 + 4) & ~3;   // padded row length, a spare word for the 5-word read
+    const int t = threadIdx.x;
+    // ---- stage: every slab position (row, padded column, 16-channel group) is written once, zero outside the image
+    const int ngroups = FT_CT / 16;
+    const int npos = NR * WP * ngroups;
+    for (int e = t; e < npos; e += 256) {
+        const int cg = e % ngroups, pos = e / ngroups;
+        const int wp = pos % WP, hl = pos / WP;
+        const int hi = ho0 - g.pad + hl, wi = wp - g.pad;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if ((unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W && c0 + 16 * cg < g.cpitch)
+            v = *(const uint4*)(a + (((int64_t)b * g.H + hi) * g.W + wi) * g.cpitch + c0 + 16 * cg);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int c = 0; c < 16; ++c)
+            slab[((cg * 16 + c) * NR + hl) * WP + wp] = (uint8_t)(w[c >> 2] >> (8 * (c & 3)));
+    }
+    __syncthreads();
+    // ---- emit
+    const int cpr = g.Wo >> 4;              // 16-byte chunks per output row
+    const int nchunk = RH * cpr;            // chunks of one colT row in this workgroup
+    const int ntap = g.ks * g.ks;
+    const int nct = min(FT_CT, g.Cin - c0);
+    const int total = ntap * nct * nchunk;
+    const int64_t mbase = (int64_t)bl * g.Ho * g.Wo + (int64_t)ho0 * g.Wo;
+    for (int e = t; e < total; e += 256) {
+        const int ch = e % nchunk, r = e / nchunk;
+        const int ci = r % nct, tap = r / nct;
+        const int kh = tap / g.ks, kw = tap - kh * g.ks;
+        const int hl = ch / cpr, w16 = ch - hl * cpr;
+        const int off = (ci * NR + hl + kh) * WP + w16 * 16 + kw;
+        const uint32_t* wp = (const uint32_t*)(slab + (off & ~3));
+        const uint32_t w0 = wp[0], w1 = wp[1], w2 = wp[2], w3 = wp[3], w4 = wp[4];
+        const uint32_t sh = (uint32_t)(off & 3);
+        uint4 o;
+        o.x = __builtin_amdgcn_alignbyte(w1, w0, sh);
+        o.y = __builtin_amdgcn_alignbyte(w2, w1, sh);
+        o.z = __builtin_amdgcn_alignbyte(w3, w2, sh);
+        o.w = __builtin_amdgcn_alignbyte(w4, w3, sh);
+        *(uint4*)(out + (int64_t)(tap * g.Cin + c0 + ci) * p.ld_out + mbase + hl * g.Wo + w16 * 16) = o;
+    }
+}
+
 hipError_t launch_im2col(const Im2colArgs& p, bool transposed, hipStream_t s)
 {
     const int64_t rows = transposed ? p.K : (int64_t)(p.b1 - p.b0) * p.g.Ho * p.g.Wo;
     const int64_t total = rows * (p.ld_out >> 4);
     if (total <= 0) return hipSuccess;
+    const ConvGeom& g = p.g;
+    if (transposed && g.stride == 1 && (g.Wo & 15) == 0 && (int64_t)p.nb * (p.b1 - p.b0) <= 65535) {
+        int RH = 256 / g.Wo;   // aim at 256 contiguous bytes per colT row and workgroup
+        if (RH < 1) RH = 1;
+        if (RH > g.Ho) RH = g.Ho;
+        while (g.Ho % RH) --RH;
+        const int NR = RH + g.ks - 1, WP = (g.W + 2 * g.pad + 3 + 4) & ~3;
+        const size_t lds = (size_t)FT_CT * NR * WP + 16;
+        if (lds <= 64 * 1024) {
+            const dim3 grid((unsigned)(g.Ho / RH), (unsigned)((g.Cin + FT_CT - 1) / FT_CT), (unsigned)(p.nb * (p.b1 - p.b0)));
+            hipLaunchKernelGGL(k_im2col_t_s1, grid, dim3(256), lds, s, p, RH);
+            return hipGetLastError();
+        }
+    }
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65535) blocks = 65535;
     const dim3 grid((unsigned)blocks, 1, (unsigned)p.nb);

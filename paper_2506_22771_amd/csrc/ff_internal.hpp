@@ -136,7 +136,10 @@ struct GemmArgs {
     int64_t p_bytes;  // bytes of one P tensor (conv only; must be < 2^31)
 };
 hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s);
-int gemm_pick_splits(int64_t I, int64_t J, int64_t R, int nb);
+struct GemmPlan {
+    int bm, bn, splits;
+};
+GemmPlan gemm_plan(int64_t I, int64_t J, int64_t R, int nb, bool allow_split);
 
 // ---- explicit im2col (conv.hip) ----------------------------------------------------------------------
 struct ConvGeom {

@@ -263,18 +263,28 @@ static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s)
     return hipGetLastError();
 }
 
-// Number of reduction splits that fills the chip when the output alone has too few tiles (the
-// weight-gradient contraction of a convolution: few output elements, a very long reduction).
-int gemm_pick_splits(int64_t I, int64_t J, int64_t R, int nb)
+// Tile shape and number of reduction splits for one launch.
+//  * The tile is as wide as the output allows (a 256-wide tile on a 64-column output would waste three
+//    quarters of the MFMA work) and tall only if that still leaves about two workgroups per compute unit.
+//  * allow_split (weight gradients): when the output alone has too few tiles -- a convolution's weight
+//    gradient has few output elements and a very long reduction -- smaller tiles and a split reduction
+//    fill the chip; each split keeps at least 32 reduction steps so that its atomic epilogue stays small.
+GemmPlan gemm_plan(int64_t I, int64_t J, int64_t R, int nb, bool allow_split)
 {
-    const int bm = I > 128 ? 256 : (I > 64 ? 128 : 64), bn = J > 128 ? 256 : (J > 64 ? 128 : 64);
-    const int64_t tiles = ((I + bm - 1) / bm) * ((J + bn - 1) / bn) * nb;
+    GemmPlan p;
+    p.splits = 1;
+    p.bn = J > 128 ? 256 : (J > 64 ? 128 : 64);
+    auto tiles = [&](int bm, int bn) { return ((I + bm - 1) / bm) * ((J + bn - 1) / bn) * nb; };
+    p.bm = (I > 128 && tiles(256, p.bn) >= 512) ? 256 : ((I > 64 && tiles(128, p.bn) >= 512) ? 128 : 64);
     const int64_t nk = (R + BK - 1) / BK;
-    if (tiles >= 384 || nk < 16) return 1;
-    int64_t sp = (768 + tiles - 1) / tiles;          // aim at ~3 workgroups per compute unit
-    if (sp > nk / 8) sp = nk / 8;                    // at least 8 reduction steps per split
-    if (sp < 1) sp = 1;
-    return (int)sp;
+    if (allow_split && tiles(p.bm, p.bn) < 384 && nk >= 64) {
+        p.bm = I > 64 ? 128 : 64;
+        p.bn = J > 64 ? 128 : 64;
+        int64_t sp = (640 + tiles(p.bm, p.bn) - 1) / tiles(p.bm, p.bn);
+        if (sp > nk / 32) sp = nk / 32;
+        p.splits = (int)(sp < 1 ? 1 : sp);
+    }
+    return p;
 }
 
 hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s)
@@ -284,11 +294,9 @@ hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s)
     if (a.ldp >= (int64_t(1) << 22) || a.ldq >= (int64_t(1) << 22)) return hipErrorInvalidValue;
     if (a.conv && (a.p_bytes >= (int64_t(1) << 31) || (a.Cin & 15) != 0)) return hipErrorInvalidValue;
     if (a.splits < 1 || (a.splits > 1 && (a.gsum || a.conv))) return hipErrorInvalidValue;
-    // Tile: as wide as the output allows (a 256-wide tile on a 64-column output would waste three quarters
-    // of the MFMA work), and tall only if that still leaves about two workgroups per compute unit.
-    const int bn = a.J > 128 ? 256 : (a.J > 64 ? 128 : 64);
-    auto tiles = [&](int bm) { return (int64_t)((a.I + bm - 1) / bm) * ((a.J + bn - 1) / bn) * a.nb * a.splits; };
-    const int bm = (a.I > 128 && tiles(256) >= 512) ? 256 : ((a.I > 64 && tiles(128) >= 512) ? 128 : 64);
+    GemmPlan p = gemm_plan(a.I, a.J, a.R, a.nb, a.splits > 1);
+    if (a.splits > 1 && p.splits != a.splits) return hipErrorInvalidValue;  // the caller zeroed C for its own plan
+    const int bm = p.bm, bn = p.bn;
     if (bn == 256) {
         if (bm == 256) return launch_cfg<256, 256, 4, 2>(a, s);
         if (bm == 128) return launch_cfg<128, 256, 2, 2>(a, s);

@@ -218,6 +218,8 @@ CONV_CASES = [  # B, H, W, Cin, Cout, ks, stride
     (4, 10, 6, 64, 40, 1, 2),    # 1x1 stride 2
     (6, 7, 5, 48, 16, 1, 1),     # 1x1
     (9, 16, 16, 128, 72, 3, 1),  # several reduction steps, 256 rows per sample, more than one row tile
+    (3, 16, 32, 40, 24, 1, 1),   # 1x1 with W_out a multiple of 16 (fast transposed-patch kernel), C_in not a multiple of 32
+    (2, 12, 16, 16, 16, 3, 1),   # 3x3 fast transposed-patch kernel with 12 output rows
 ]
 
 

@@ -111,15 +111,23 @@ static int32_t goodness_shift(int64_t K, int64_t terms)
     return r;
 }
 
-// Scratch one layer's single-operation calls need beyond FF_WS_MIN_BYTES: the row-major patch matrix of an
-// explicit-im2col forward, or the transposed patch matrix of one weight-gradient chunk.
-static size_t layer_scratch_bytes(const Dims& d)
+// Scratch one layer needs per pass beyond FF_WS_MIN_BYTES.
+// `col`: the row-major patch matrix of an explicit-im2col forward or the transposed patch matrix of one
+// weight-gradient chunk (conv only).  `part`: partial accumulators of a split weight-gradient reduction.
+static size_t layer_col_bytes(const Dims& d)
 {
     if (d.kind != FF_CONV2D) return 0;
     const size_t fwd = d.implicit ? 0 : (size_t)(d.M * pitch8(d.K));
     const size_t bwd = (size_t)(d.K * pitch8(d.chunk_b * d.rps));
     return align_up(fwd > bwd ? fwd : bwd, 256);
 }
+static size_t layer_part_bytes(const Dims& d, int nb)
+{
+    const GemmPlan p = gemm_plan(d.N, d.K, min(d.M, d.chunk_b * d.rps), nb, true);
+    if (p.splits <= 1) return 0;
+    return align_up((size_t)p.splits * (size_t)(d.N * pitch32(d.K)) * sizeof(int32_t), 256);
+}
+static size_t layer_scratch_bytes(const Dims& d) { return layer_col_bytes(d) + layer_part_bytes(d, 1); }
 
 // ---- workspace of ff_train_step ------------------------------------------------------------------
 struct WsLayout {
@@ -136,6 +144,7 @@ struct WsLayout {
     size_t off_gy, st_gy;  // int8 scratch [2][st_gy]: transposed quantised local gradient
     size_t off_dw, st_dw, dw_bytes;  // int32 scratch [2][MAX_CHUNKS][dw_bytes]; st_dw = pass stride (bytes)
     size_t off_col, st_col;          // int8 scratch [2][st_col]: patch matrices of conv layers
+    size_t off_part, st_part;        // int32 scratch [2][st_part] (bytes): partial sums of split weight gradients
     size_t off_aq[MAX_LAYERS], st_aq[MAX_LAYERS];    // quantised layer input [2][st]: dense layers share one scratch
     size_t off_aqt[MAX_LAYERS], st_aqt[MAX_LAYERS];  // dense only: transposed quantised input [2][st], retained
     size_t off_acc[MAX_LAYERS], st_acc[MAX_LAYERS];  // int32 accumulators [2][st] (bytes), retained
@@ -179,13 +188,14 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
     off = align_up(off + sizeof(float) * k * 2 * B, A);
     w->off_ct = off;
     off = align_up(off + sizeof(float) * k * 2 * B, A);
-    size_t aq_dense = 0, gy = 0, dw = 0, col = 0;
+    size_t aq_dense = 0, gy = 0, dw = 0, col = 0, part = 0;
     for (int i = 0; i < w->k; ++i) {
         const Dims& d = w->d[i];
         if (d.kind == FF_DENSE) aq_dense = max(aq_dense, (size_t)(d.in_rows * pitch8(d.in_cols)));
         gy = max(gy, (size_t)(d.N * pitch8(d.M)));
         dw = max(dw, (size_t)(d.N * pitch32(d.K)) * sizeof(int32_t));
-        col = max(col, layer_scratch_bytes(d));
+        col = max(col, layer_col_bytes(d));
+        part = max(part, layer_part_bytes(d, 2));
     }
     aq_dense = align_up(aq_dense, A);
     const size_t off_aq_dense = off;
@@ -200,6 +210,9 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
     w->st_col = col;
     w->off_col = off;
     off += 2 * w->st_col;
+    w->st_part = part;
+    w->off_part = off;
+    off += 2 * w->st_part;
     for (int i = 0; i < w->k; ++i) {
         const Dims& d = w->d[i];
         if (d.kind == FF_DENSE) {
@@ -323,8 +336,8 @@ static ff_status run_forward(const Dims& d, int relu, const int8_t* aq, int64_t 
 // `aqt` is the transposed quantised input (dense) or the NHWC quantised input (conv; patches are materialised
 // chunk by chunk into `colT`).  dw accumulators of one pass are dw_elems apart.
 static ff_status run_wgrad(const Dims& d, const int8_t* gy_t, int64_t st_gy, const int8_t* aqt, int64_t st_aqt,
-                           int8_t* colT, int64_t st_colT, int32_t* dw, int64_t st_dw, int64_t dw_elems, int nb,
-                           hipStream_t s)
+                           int8_t* colT, int64_t st_colT, int32_t* part, int64_t st_part, int32_t* dw, int64_t st_dw,
+                           int64_t dw_elems, int nb, hipStream_t s)
 {
     for (int c = 0; c < d.n_chunks; ++c) {
         const int64_t b0 = c * d.chunk_b, b1 = min(d.B, b0 + d.chunk_b);
@@ -366,10 +379,15 @@ static ff_status run_wgrad(const Dims& d, const int8_t* gy_t, int64_t st_gy, con
         }
         g.splits = gemm_plan(g.I, g.J, g.R, nb, true).splits;
         if (g.splits > 1) {
-            for (int z = 0; z < nb; ++z)
-                HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(g.C + z * st_dw), d.N * pitch32(d.K), 0u, s));
+            int32_t* out = g.C;
+            g.C = part;
+            g.st_c = st_part;
+            g.st_split = d.N * pitch32(d.K);
+            HIPCHK_T(FF_K_GEMM_DW, launch_gemm_nt_i8(g, s));
+            HIPCHK_T(FF_K_GEMM_DW, launch_reduce_splits(part, g.splits, g.st_split, st_part, out, st_dw, g.st_split, nb, s));
+        } else {
+            HIPCHK_T(FF_K_GEMM_DW, launch_gemm_nt_i8(g, s));
         }
-        HIPCHK_T(FF_K_GEMM_DW, launch_gemm_nt_i8(g, s));
     }
     return FF_OK;
 }
@@ -617,7 +635,8 @@ ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc
     a.nb = 1;
     HIPCHK_T(FF_K_QUANT_GRAD, launch_quantize(QSRC_GRAD, a, s));
     const int64_t dw_elems = d.N * pitch32(d.K);
-    return run_wgrad(d, gy_q_t, 0, a_q_t, 0, (int8_t*)ws + FF_WS_MIN_BYTES, 0, dw_acc, 0, dw_elems, 1, s);
+    int8_t* colT = (int8_t*)ws + FF_WS_MIN_BYTES;
+    return run_wgrad(d, gy_q_t, 0, a_q_t, 0, colT, 0, (int32_t*)(colT + layer_col_bytes(d)), 0, dw_acc, 0, dw_elems, 1, s);
 }
 
 ff_status ff_layer_update(const ff_layer_desc* layer, float* w_master, const int32_t* dw_acc_pos,
@@ -848,7 +867,8 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         const ff_status ws_ = run_wgrad(d, (const int8_t*)(base + w.off_gy), (int64_t)w.st_gy,
                                         dense ? (const int8_t*)(base + w.off_aqt[i]) : (const int8_t*)(base + w.off_aq[i]),
                                         dense ? (int64_t)w.st_aqt[i] : (int64_t)w.st_aq[i], (int8_t*)(base + w.off_col),
-                                        (int64_t)w.st_col, (int32_t*)(base + w.off_dw),
+                                        (int64_t)w.st_col, (int32_t*)(base + w.off_part),
+                                        (int64_t)(w.st_part / sizeof(int32_t)), (int32_t*)(base + w.off_dw),
                                         (int64_t)(w.st_dw / sizeof(int32_t)), dw_elems, 2, s);
         if (ws_ != FF_OK) return ws_;
 

@@ -49,7 +49,9 @@ __device__ __forceinline__ void block_atomic_max_bits(uint32_t bits, uint32_t* s
         uint32_t m = red[0];
 #pragma unroll
         for (int i = 1; i < THREADS / 64; ++i) m = max(m, red[i]);
-        if (m != 0) atomicMax(slot, m);
+        // thousands of workgroups target one word: skip the atomic when the slot already holds a larger value
+        // (the slot only grows, so a stale read can only cause a harmless extra atomic)
+        if (m != 0 && m > __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(slot, m);
     }
 }
 

@@ -127,9 +127,10 @@ struct GemmArgs {
     // batching over blockIdx.z
     int32_t nb;
     int64_t st_p, st_q, st_c, st_g;
-    // split reduction (blockIdx.y): each split adds its partial sums into a pre-zeroed C with integer atomics
-    // (exact and order-free).  1 = plain stores.  Not combined with the fused reductions.
+    // split reduction (blockIdx.y): split s stores its partial sums at C + s*st_split; launch_reduce_splits
+    // adds them up (integer sums: exact and order-free).  1 = no split.  Not combined with the fused reductions.
     int32_t splits;
+    int64_t st_split;
     // implicit-GEMM convolution (conv != 0): P is an NHWC int8 tensor [B, H, W, cpitch] and row i of the
     // contraction is output pixel (b, ho, wo); reduction index r = (kh*ks + kw)*Cin + ci.  Cin % 16 == 0.
     int32_t conv, H, W, Cin, cpitch, ks, stride, pad, Ho, Wo;
@@ -140,6 +141,9 @@ struct GemmPlan {
     int bm, bn, splits;
 };
 GemmPlan gemm_plan(int64_t I, int64_t J, int64_t R, int nb, bool allow_split);
+// out[z][e] = sum over s < splits of part[z][s][e], e < n (n a multiple of 4); strides in elements
+hipError_t launch_reduce_splits(const int32_t* part, int splits, int64_t st_split, int64_t st_part_z, int32_t* out,
+                                int64_t st_out_z, int64_t n, int nb, hipStream_t s);
 
 // ---- explicit im2col (conv.hip) ----------------------------------------------------------------------
 struct ConvGeom {

@@ -50,8 +50,8 @@ __device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v,
 }
 __device__ __forceinline__ int swz(int row, int kc) { return row * BK + ((kc ^ ((row >> 1) & 7)) << 4); }
 
-// MODE 0: store C; 1: store C and accumulate the per-sample goodness sums / maxima; 2: add into C atomically
-// (split reduction).
+// MODE 0: store C; 1: store C and accumulate the per-sample goodness sums / maxima; 2: split reduction, this
+// workgroup stores the partial sums of its share of the reduction steps at C + blockIdx.y * st_split.
 template <int BM, int BN, int WM, int WN, int MODE, bool CONV>
 __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
 {
@@ -79,8 +79,8 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     // this workgroup's share of the reduction steps
     const int nk_per = (nk_all + a.splits - 1) / a.splits;
     const int kt0 = MODE == 2 ? (int)blockIdx.y * nk_per : 0;
-    const int nk = MODE == 2 ? min(nk_all, kt0 + nk_per) : nk_all;
-    if (MODE == 2 && kt0 >= nk) return;
+    const int nk = MODE == 2 ? min(nk_all, kt0 + nk_per) : nk_all;   // the plan leaves no split empty
+    if (MODE == 2) C += (int64_t)blockIdx.y * a.st_split;
 
     const int rows_p = min(BM, a.I - i0), rows_q = min(BN, a.J - j0);
     __amdgpu_buffer_rsrc_t rp = CONV ? __builtin_amdgcn_make_buffer_rsrc((void*)P, 0, (int)a.p_bytes, 0x00020000)
@@ -191,12 +191,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
                 const int c2 = acc[ti][tj][4 * g + 2], c3 = acc[ti][tj][4 * g + 3];
                 if (i < a.I) {
                     int32_t* dst = C + (int64_t)i * a.ldc + j;
-                    if (MODE == 2) {
-                        if (j + 0 < a.J) atomicAdd(dst + 0, c0);
-                        if (j + 1 < a.J) atomicAdd(dst + 1, c1);
-                        if (j + 2 < a.J) atomicAdd(dst + 2, c2);
-                        if (j + 3 < a.J) atomicAdd(dst + 3, c3);
-                    } else if (j + 3 < a.J) {
+                    if (j + 3 < a.J) {
                         *(v4i*)dst = (v4i){c0, c1, c2, c3};
                     } else {
                         if (j + 0 < a.J) dst[0] = c0;
@@ -267,24 +262,72 @@ static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s)
 //  * The tile is as wide as the output allows (a 256-wide tile on a 64-column output would waste three
 //    quarters of the MFMA work) and tall only if that still leaves about two workgroups per compute unit.
 //  * allow_split (weight gradients): when the output alone has too few tiles -- a convolution's weight
-//    gradient has few output elements and a very long reduction -- smaller tiles and a split reduction
-//    fill the chip; each split keeps at least 32 reduction steps so that its atomic epilogue stays small.
+//    gradient has few output elements and a very long reduction -- a split reduction fills the chip.
 GemmPlan gemm_plan(int64_t I, int64_t J, int64_t R, int nb, bool allow_split)
 {
     GemmPlan p;
     p.splits = 1;
-    p.bn = J > 128 ? 256 : (J > 64 ? 128 : 64);
+    // edge of the tile along one dimension: weigh the padding it leaves against the lower efficiency of narrow
+    // tiles (relative MFMA rates measured on this kernel: 256 -> 1, 128 -> 0.85, 64 -> 0.65)
+    auto edge = [](int64_t n) {
+        const int e[3] = {256, 128, 64};
+        const double eff[3] = {1.0, 0.85, 0.65};
+        int best = 64;
+        double score = -1.0;
+        for (int i = 0; i < 3; ++i) {
+            const double sc = eff[i] * (double)n / (double)((n + e[i] - 1) / e[i] * e[i]);
+            if (sc > score + 1e-9) { score = sc; best = e[i]; }
+        }
+        return best;
+    };
+    p.bn = edge(J);
     auto tiles = [&](int bm, int bn) { return ((I + bm - 1) / bm) * ((J + bn - 1) / bn) * nb; };
-    p.bm = (I > 128 && tiles(256, p.bn) >= 512) ? 256 : ((I > 64 && tiles(128, p.bn) >= 512) ? 128 : 64);
     const int64_t nk = (R + BK - 1) / BK;
-    if (allow_split && tiles(p.bm, p.bn) < 384 && nk >= 64) {
-        p.bm = I > 64 ? 128 : 64;
-        p.bn = J > 64 ? 128 : 64;
-        int64_t sp = (640 + tiles(p.bm, p.bn) - 1) / tiles(p.bm, p.bn);
-        if (sp > nk / 32) sp = nk / 32;
-        p.splits = (int)(sp < 1 ? 1 : sp);
+    if (allow_split && tiles(edge(I), p.bn) < 384 && nk >= 32) {
+        // Weight gradient of a convolution: few output elements, a very long reduction.  Keep the tile as large as
+        // the output allows (operand traffic falls with the tile edge) and create the missing parallelism by
+        // splitting the reduction: about two workgroups per compute unit, never more (a third partial round
+        // would idle most of the chip), at least 16 reduction steps per split.
+        p.bm = edge(I);
+        int64_t sp = 512 / tiles(p.bm, p.bn);
+        if (sp > nk / 16) sp = nk / 16;
+        if (sp < 1) sp = 1;
+        const int64_t per = (nk + sp - 1) / sp;
+        p.splits = (int)((nk + per - 1) / per);   // no split without reduction steps
+        return p;
     }
+    // tall tiles only if that still leaves about two workgroups per compute unit
+    p.bm = (I > 128 && tiles(256, p.bn) >= 512) ? 256 : ((I > 64 && tiles(128, p.bn) >= 512) ? 128 : 64);
     return p;
+}
+
+__global__ __launch_bounds__(256) void k_reduce_splits(const int32_t* __restrict__ part, int splits, int64_t st_split,
+                                                       int64_t st_part_z, int32_t* __restrict__ out, int64_t st_out_z,
+                                                       int64_t n4)
+{
+    const int4* __restrict__ p = (const int4*)(part + blockIdx.y * st_part_z);
+    int4* __restrict__ o = (int4*)(out + blockIdx.y * st_out_z);
+    const int64_t s4 = st_split >> 2;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < n4; e += (int64_t)gridDim.x * 256) {
+        int4 acc = p[e];
+        for (int s = 1; s < splits; ++s) {
+            const int4 v = p[e + s * s4];
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        o[e] = acc;
+    }
+}
+
+hipError_t launch_reduce_splits(const int32_t* part, int splits, int64_t st_split, int64_t st_part_z, int32_t* out,
+                                int64_t st_out_z, int64_t n, int nb, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    const int64_t n4 = n >> 2;
+    int64_t blocks = (n4 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_reduce_splits, dim3((unsigned)blocks, (unsigned)nb), dim3(256), 0, s, part, splits, st_split,
+                       st_part_z, out, st_out_z, n4);
+    return hipGetLastError();
 }
 
 hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s)
@@ -295,7 +338,7 @@ hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s)
     if (a.conv && (a.p_bytes >= (int64_t(1) << 31) || (a.Cin & 15) != 0)) return hipErrorInvalidValue;
     if (a.splits < 1 || (a.splits > 1 && (a.gsum || a.conv))) return hipErrorInvalidValue;
     GemmPlan p = gemm_plan(a.I, a.J, a.R, a.nb, a.splits > 1);
-    if (a.splits > 1 && p.splits != a.splits) return hipErrorInvalidValue;  // the caller zeroed C for its own plan
+    if (a.splits > 1 && p.splits != a.splits) return hipErrorInvalidValue;  // the caller sized the partial buffers for its own plan
     const int bm = p.bm, bn = p.bn;
     if (bn == 256) {
         if (bm == 256) return launch_cfg<256, 256, 4, 2>(a, s);

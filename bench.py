@@ -83,6 +83,9 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg5")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB-read / 1 GiB-write elementwise kernel (torch.add) so that a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives are part of it); use --gpus 1",
@@ -101,6 +104,13 @@ def main() -> int:
     wl = workload(args.workload)
     net, d_xp, d_xn, loss, good, ws = setup(ff, torch, wl)
     k, B = len(wl.layers), wl.batch
+
+    if args.pmc_calibration:
+        cal_in = torch.ones(1 << 28, device="cuda")          # 2^28 fp32 = 1 GiB
+        cal_out = torch.empty_like(cal_in)
+        torch.add(cal_in, 1.0, out=cal_out)
+        torch.cuda.synchronize()
+        del cal_in, cal_out
 
     step_no = 0
     for _ in range(args.warmup):

@@ -32,6 +32,10 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 128;  // reduction bytes per LDS stage
 
+#ifndef FF_STAGED_EPI
+#define FF_STAGED_EPI 1   // 1: interior tiles leave through LDS as whole rows (see the epilogue)
+#endif
+
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt range");
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -62,7 +66,11 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     constexpr int CH_P = BM * 8 / T, CH_Q = BN * 8 / T;
     constexpr int STAGE_BYTES = (BM + BN) * BK;
     static_assert(BM * 8 % T == 0 && BN * 8 % T == 0, "tile/threads mismatch");
-    __shared__ __attribute__((aligned(16))) int8_t lds[2 * STAGE_BYTES];
+    // epilogue staging: one 32-row slice of a wave's tile, rows padded by 16 bytes to spread the banks
+    constexpr int EROW = WTN * 4 + 16;
+    constexpr int ESLICE = 32 * EROW;
+    constexpr int LDS_BYTES = 2 * STAGE_BYTES > WM * WN * ESLICE ? 2 * STAGE_BYTES : WM * WN * ESLICE;
+    __shared__ __attribute__((aligned(16))) int8_t lds[LDS_BYTES];
 
     const int z = blockIdx.z;
     const int8_t* __restrict__ P = a.P + z * a.st_p;
@@ -177,6 +185,12 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
         mma(1);
     }
 
+    // Epilogue.  A lane holds, per accumulator quad, four consecutive columns of ONE row, so a direct store
+    // instruction writes 32-byte pieces of 32 different rows.  Interior tiles therefore go through LDS (free
+    // after the main loop; each wave uses a private slice, no barrier needed): 16-byte writes row by row,
+    // then reads that give every store instruction whole contiguous row segments of WTN*4 bytes.
+    const bool staged = FF_STAGED_EPI && i0 + BM <= a.I && j0 + BN <= a.J;
+    int8_t* const ebase = lds + wave * ESLICE;
 #pragma unroll
     for (int ti = 0; ti < TI; ++ti) {
         const int i = i0 + wm * WTM + ti * 32 + lr;
@@ -189,7 +203,9 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
                 const int j = j0 + wn * WTN + tj * 32 + 8 * g + 4 * lh;
                 const int c0 = acc[ti][tj][4 * g + 0], c1 = acc[ti][tj][4 * g + 1];
                 const int c2 = acc[ti][tj][4 * g + 2], c3 = acc[ti][tj][4 * g + 3];
-                if (i < a.I) {
+                if (staged) {
+                    *(v4i*)(ebase + lr * EROW + (tj * 32 + 8 * g + 4 * lh) * 4) = (v4i){c0, c1, c2, c3};
+                } else if (i < a.I) {
                     int32_t* dst = C + (int64_t)i * a.ldc + j;
                     if (j + 3 < a.J) {
                         *(v4i*)dst = (v4i){c0, c1, c2, c3};
@@ -210,6 +226,18 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
                         vm = max(vm, v < 0 ? -v : v);
                     }
                 }
+            }
+        }
+        if (staged) {
+            constexpr int LPR = WTN / 4;          // lanes (16 bytes each) per staged row
+            constexpr int RPI = 64 / LPR;         // rows per store instruction
+            const int rl = lane / LPR, cc = lane - rl * LPR;
+            int32_t* const ctile = C + (int64_t)(i0 + wm * WTM + ti * 32) * a.ldc + j0 + wn * WTN + cc * 4;
+#pragma unroll
+            for (int r = 0; r < 32 / RPI; ++r) {
+                const int row = r * RPI + rl;
+                const v4i v = *(const v4i*)(ebase + row * EROW + cc * 16);
+                *(v4i*)(ctile + (int64_t)row * a.ldc) = v;
             }
         }
         if (EPI) {

@@ -85,15 +85,19 @@ __global__ __launch_bounds__(256) void k_im2col(Im2colArgs p)
     }
 }
 
-// Fast transposed patches for stride 1 (3x3 pad 1 or 1x1) when W_out is a multiple of 16.
-// One workgroup: one sample, FT_RH output rows, FT_CT channels.  The input slab is staged channel-major in
-// LDS ([channel][row][padded column], zero borders), so that the 16 reduction bytes of an output chunk --
-// 16 consecutive output pixels of one row, one tap, one channel -- are 16 consecutive LDS bytes at the tap's
-// column offset: five aligned words and a byte alignment instead of sixteen byte gathers.  Lanes run over
-// the chunks of one colT row first: 16-byte stores, FT_RH * W_out contiguous bytes per (tap, channel).
+// Transposed patches through an LDS slab.
+// One workgroup: one sample, RH output rows, FT_CT channels.  The input rows those outputs touch are staged
+// channel-major in LDS ([channel][row][padded column], zero borders), so that the global gathers become one
+// pass of 16-byte loads, and every colT row receives RH * W_out contiguous bytes per workgroup in 16-byte
+// stores (lanes run over the chunks of one colT row first).
+// FAST (stride 1, W_out % 16 == 0): the 16 reduction bytes of an output chunk -- 16 consecutive output pixels
+// of one row, one tap, one channel -- are 16 consecutive LDS bytes at the tap's column offset: five aligned
+// words and a byte alignment.  Otherwise (stride 2, or maps narrower than 16) each byte is gathered from LDS.
+// Requires H_out * W_out % 16 == 0 (chunks do not straddle samples) and RH * W_out % 16 == 0.
 constexpr int FT_CT = 32;
 
-__global__ __launch_bounds__(256) void k_im2col_t_s1(Im2colArgs p, int RH)
+template <bool FAST>
+__global__ __launch_bounds__(256) void k_im2col_t_slab(Im2colArgs p, int RH)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t slab[];
     const ConvGeom& g = p.g;
@@ -102,7 +106,7 @@ __global__ __launch_bounds__(256) void k_im2col_t_s1(Im2colArgs p, int RH)
     const int8_t* __restrict__ a = p.a + z * p.st_a;
     int8_t* __restrict__ out = p.out + z * p.st_out;
     const int ho0 = blockIdx.x * RH, c0 = blockIdx.y * FT_CT;
-    const int NR = RH + g.ks - 1;                    // input rows of the slab
+    const int NR = (RH - 1) * g.stride + g.ks;       // input rows of the slab
     const int WP = (g.W + 2 * g.pad + 3 + 4) & ~3;   // padded row length, a spare word for the 5-word read
     const int t = threadIdx.x;
     // ---- stage: every slab position (row, padded column, 16-channel group) is written once, zero outside the image
@@ -111,7 +115,7 @@ __global__ __launch_bounds__(256) void k_im2col_t_s1(Im2colArgs p, int RH)
     for (int e = t; e < npos; e += 256) {
         const int cg = e % ngroups, pos = e / ngroups;
         const int wp = pos % WP, hl = pos / WP;
-        const int hi = ho0 - g.pad + hl, wi = wp - g.pad;
+        const int hi = ho0 * g.stride - g.pad + hl, wi = wp - g.pad;
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
         if ((unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W && c0 + 16 * cg < g.cpitch)
             v = *(const uint4*)(a + (((int64_t)b * g.H + hi) * g.W + wi) * g.cpitch + c0 + 16 * cg);
@@ -122,8 +126,7 @@ __global__ __launch_bounds__(256) void k_im2col_t_s1(Im2colArgs p, int RH)
     }
     __syncthreads();
     // ---- emit
-    const int cpr = g.Wo >> 4;              // 16-byte chunks per output row
-    const int nchunk = RH * cpr;            // chunks of one colT row in this workgroup
+    const int nchunk = (RH * g.Wo) >> 4;    // 16-byte chunks of one colT row in this workgroup
     const int ntap = g.ks * g.ks;
     const int nct = min(FT_CT, g.Cin - c0);
     const int total = ntap * nct * nchunk;
@@ -132,17 +135,31 @@ __global__ __launch_bounds__(256) void k_im2col_t_s1(Im2colArgs p, int RH)
         const int ch = e % nchunk, r = e / nchunk;
         const int ci = r % nct, tap = r / nct;
         const int kh = tap / g.ks, kw = tap - kh * g.ks;
-        const int hl = ch / cpr, w16 = ch - hl * cpr;
-        const int off = (ci * NR + hl + kh) * WP + w16 * 16 + kw;
-        const uint32_t* wp = (const uint32_t*)(slab + (off & ~3));
-        const uint32_t w0 = wp[0], w1 = wp[1], w2 = wp[2], w3 = wp[3], w4 = wp[4];
-        const uint32_t sh = (uint32_t)(off & 3);
         uint4 o;
-        o.x = __builtin_amdgcn_alignbyte(w1, w0, sh);
-        o.y = __builtin_amdgcn_alignbyte(w2, w1, sh);
-        o.z = __builtin_amdgcn_alignbyte(w3, w2, sh);
-        o.w = __builtin_amdgcn_alignbyte(w4, w3, sh);
-        *(uint4*)(out + (int64_t)(tap * g.Cin + c0 + ci) * p.ld_out + mbase + hl * g.Wo + w16 * 16) = o;
+        if (FAST) {
+            const int cpr = g.Wo >> 4;              // chunks per output row
+            const int hl = ch / cpr, w16 = ch - hl * cpr;
+            const int off = (ci * NR + hl + kh) * WP + w16 * 16 + kw;
+            const uint32_t* wp = (const uint32_t*)(slab + (off & ~3));
+            const uint32_t w0 = wp[0], w1 = wp[1], w2 = wp[2], w3 = wp[3], w4 = wp[4];
+            const uint32_t sh = (uint32_t)(off & 3);
+            o.x = __builtin_amdgcn_alignbyte(w1, w0, sh);
+            o.y = __builtin_amdgcn_alignbyte(w2, w1, sh);
+            o.z = __builtin_amdgcn_alignbyte(w3, w2, sh);
+            o.w = __builtin_amdgcn_alignbyte(w4, w3, sh);
+        } else {
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+            int ml = ch * 16;
+            int hl = ml / g.Wo, wo = ml - hl * g.Wo;
+            const uint8_t* base = slab + (ci * NR + kh) * WP + kw;
+#pragma unroll
+            for (int tt = 0; tt < 16; ++tt) {
+                w[tt >> 2] |= (uint32_t)base[hl * g.stride * WP + wo * g.stride] << (8 * (tt & 3));
+                if (++wo == g.Wo) { wo = 0; ++hl; }
+            }
+            o = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        *(uint4*)(out + (int64_t)(tap * g.Cin + c0 + ci) * p.ld_out + mbase + ch * 16) = o;
     }
 }
 
@@ -152,16 +169,19 @@ hipError_t launch_im2col(const Im2colArgs& p, bool transposed, hipStream_t s)
     const int64_t total = rows * (p.ld_out >> 4);
     if (total <= 0) return hipSuccess;
     const ConvGeom& g = p.g;
-    if (transposed && g.stride == 1 && (g.Wo & 15) == 0 && (int64_t)p.nb * (p.b1 - p.b0) <= 65535) {
-        int RH = 256 / g.Wo;   // aim at 256 contiguous bytes per colT row and workgroup
+    if (transposed && ((g.Ho * g.Wo) & 15) == 0 && (int64_t)p.nb * (p.b1 - p.b0) <= 65535) {
+        // rows per workgroup: about 256 contiguous bytes per colT row, a divisor of H_out, RH * W_out % 16 == 0
+        int RH = 256 / g.Wo;
         if (RH < 1) RH = 1;
         if (RH > g.Ho) RH = g.Ho;
-        while (g.Ho % RH) --RH;
-        const int NR = RH + g.ks - 1, WP = (g.W + 2 * g.pad + 3 + 4) & ~3;
+        while (RH > 1 && (g.Ho % RH || ((RH * g.Wo) & 15))) --RH;
+        if (g.Ho % RH || ((RH * g.Wo) & 15)) RH = g.Ho;
+        const int NR = (RH - 1) * g.stride + g.ks, WP = (g.W + 2 * g.pad + 3 + 4) & ~3;
         const size_t lds = (size_t)FT_CT * NR * WP + 16;
         if (lds <= 64 * 1024) {
             const dim3 grid((unsigned)(g.Ho / RH), (unsigned)((g.Cin + FT_CT - 1) / FT_CT), (unsigned)(p.nb * (p.b1 - p.b0)));
-            hipLaunchKernelGGL(k_im2col_t_s1, grid, dim3(256), lds, s, p, RH);
+            if (g.stride == 1 && (g.Wo & 15) == 0) hipLaunchKernelGGL(k_im2col_t_slab<true>, grid, dim3(256), lds, s, p, RH);
+            else hipLaunchKernelGGL(k_im2col_t_slab<false>, grid, dim3(256), lds, s, p, RH);
             return hipGetLastError();
         }
     }

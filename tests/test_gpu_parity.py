@@ -220,6 +220,10 @@ CONV_CASES = [  # B, H, W, Cin, Cout, ks, stride
     (9, 16, 16, 128, 72, 3, 1),  # several reduction steps, 256 rows per sample, more than one row tile
     (3, 16, 32, 40, 24, 1, 1),   # 1x1 with W_out a multiple of 16 (fast transposed-patch kernel), C_in not a multiple of 32
     (2, 12, 16, 16, 16, 3, 1),   # 3x3 fast transposed-patch kernel with 12 output rows
+    (5, 16, 16, 32, 16, 3, 2),   # stride 2 -> 8x8 output: LDS-slab patches with byte gathers
+    (6, 8, 8, 48, 32, 3, 1),     # 8x8 map: a 16-byte chunk spans two output rows
+    (7, 4, 4, 64, 32, 3, 1),     # 4x4 map: one chunk per image
+    (3, 16, 8, 16, 16, 1, 2),    # 1x1 stride 2 -> 8x4 output
 ]
 
 
@@ -349,6 +353,14 @@ def test_train_step_cfg3_full_size(ff):
     """The small CNN (conv3x3 3->64->128->256 at 32x32, 256+256 images) at its full size: weight gradients in two
     sample chunks, goodness sums with a 3-bit shift in the last layer."""
     _run_steps(ff, workload("cfg3"), 1)
+
+
+@pytest.mark.slow
+@pytest.mark.timeout(1500)
+def test_train_step_cfg4_plain_full_size(ff):
+    """The seventeen 3x3 convolutions of a ResNet-18-shaped stack (stride-2 layers, 8x8 and 4x4 maps, up to 4608
+    reduction bytes, look-ahead over 17 layers) at 256+256 images, as a plain sequence without the residual adds."""
+    _run_steps(ff, workload("cfg4_plain"), 1)
 
 
 @pytest.mark.slow

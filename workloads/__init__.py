@@ -116,6 +116,16 @@ def workload(name: str) -> Workload:
         return Workload("cfg2", mlp([784, 2000, 2000, 2000, 2000], True), 1024, "uniform_onehot", lam=0.05)
     if name == "cfg3":   # small CNN, conv3x3 3->64->128->256 at 32x32
         return Workload("cfg3", conv_stack([3, 64, 128, 256], 32, 32), 256, "uniform_onehot", lam=0.0)
+    if name == "cfg4_plain":
+        # The 3x3 convolutions of a ResNet-18-shaped stack on 32x32x3 images (stem + 4 stages of 64/128/256/512
+        # channels, two basic blocks each, stride 2 at the start of stages 2-4), run as a plain sequence: the
+        # residual additions and the three 1x1 projection branches are left out (not built).
+        layers, c_in, hw = [], 3, 32
+        plan = [(64, 1)] + [(64, 1)] * 4 + [(128, 2)] + [(128, 1)] * 3 + [(256, 2)] + [(256, 1)] * 3 + [(512, 2)] + [(512, 1)] * 3
+        for c_out, stride in plan:
+            layers.append(Layer("conv", H=hw, W=hw, C_in=c_in, C_out=c_out, ksize=3, stride=stride, pad=1))
+            c_in, hw = c_out, (hw + 2 - 3) // stride + 1
+        return Workload("cfg4_plain", tuple(layers), 256, "uniform_onehot", lam=0.05)
     if name == "cfg5":   # large-GEMM stress
         return Workload("cfg5", mlp([4096, 4096, 4096], False), 8192, "normal", lam=0.05)
     if name == "tiny":   # ragged shapes spanning tile tails, for quick parity tests

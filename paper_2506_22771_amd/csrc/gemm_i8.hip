@@ -52,6 +52,15 @@ __device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v,
     const unsigned lo = (unsigned)__shfl_xor((int)(unsigned)v, d), hi = (unsigned)__shfl_xor((int)(unsigned)(v >> 32), d);
     return ((unsigned long long)hi << 32) | lo;
 }
+// Lanes of one wavefront exchange data through LDS in the epilogues: the hardware executes a wave's LDS
+// instructions in order, but the compiler reasons per thread and, without a fence, may keep a value it loaded
+// earlier instead of re-reading a location another lane has written since.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 __device__ __forceinline__ int swz(int row, int kc) { return row * BK + ((kc ^ ((row >> 1) & 7)) << 4); }
 
 // MODE 0: store C; 1: store C and accumulate the per-sample goodness sums / maxima; 2: split reduction, this
@@ -116,7 +125,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
 #pragma unroll
     for (int s = 0; s < CH_Q; ++s) offQ[s] = ((s * T + tid) >> 3) * (int)a.ldq + kcol;
     auto issue = [&](int kt, int buf) {
-        const int k0 = kt * BK;
+        const int k0 = __builtin_amdgcn_readfirstlane(kt * BK);   // wave-uniform: it travels in a scalar register
         const bool ok = k0 + kcol < Rpad;   // only the last step can have chunks beyond the reduction length
         int8_t* base = lds + buf * STAGE_BYTES;
         if (CONV) {
@@ -163,15 +172,19 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
                 acc[ti][tj] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fq[set][tj], fp[set][ti], acc[ti][tj], 0, 0, 0);
     };
 
+    // Pipeline: stage kt is multiplied while the copy of stage kt+1 is in flight.  The last fragment reads of
+    // stage kt are issued before the barrier of step kt, so its buffer is free right after that barrier and
+    // the copy of stage kt+2 is issued there: one copy is in flight at every moment, each with a whole step
+    // of time to land.
     issue(kt0, 0);
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     ldfrag(0, lds, 0);
+    if (kt0 + 1 < nk) issue(kt0 + 1, 1);
     for (int kt = kt0; kt < nk; ++kt) {
         const int cur = (kt - kt0) & 1;
         const int8_t* sb = lds + cur * STAGE_BYTES;
         const int8_t* sn = lds + (cur ^ 1) * STAGE_BYTES;
-        if (kt + 1 < nk) issue(kt + 1, cur ^ 1);
         ldfrag(1, sb, 1);
         mma(0);
         ldfrag(0, sb, 2);
@@ -181,6 +194,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
+        if (kt + 2 < nk) issue(kt + 2, cur);
         if (kt + 1 < nk) ldfrag(0, sn, 0);
         mma(1);
     }
@@ -229,6 +243,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
             }
         }
         if (staged) {
+            wave_lds_fence();
             constexpr int LPR = WTN / 4;          // lanes (16 bytes each) per staged row
             constexpr int RPI = 64 / LPR;         // rows per store instruction
             const int rl = lane / LPR, cc = lane - rl * LPR;
@@ -239,6 +254,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
                 const v4i v = *(const v4i*)(ebase + row * EROW + cc * 16);
                 *(v4i*)(ctile + (int64_t)row * a.ldc) = v;
             }
+            wave_lds_fence();
         }
         if (EPI) {
             // the two half-waves hold the two column halves of the same row
@@ -366,7 +382,6 @@ hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s)
     if (a.conv && (a.p_bytes >= (int64_t(1) << 31) || (a.Cin & 15) != 0)) return hipErrorInvalidValue;
     if (a.splits < 1 || (a.splits > 1 && (a.gsum || a.conv))) return hipErrorInvalidValue;
     GemmPlan p = gemm_plan(a.I, a.J, a.R, a.nb, a.splits > 1);
-    if (a.splits > 1 && p.splits != a.splits) return hipErrorInvalidValue;  // the caller sized the partial buffers for its own plan
     const int bm = p.bm, bn = p.bn;
     if (bn == 256) {
         if (bm == 256) return launch_cfg<256, 256, 4, 2>(a, s);

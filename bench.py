@@ -71,8 +71,53 @@ def cpu_baseline(wl, sample_batch: int):
     k = len(small.layers)
     return {"value": 2 * sample_batch * k / dt, "unit": "samples/s per layer step", "cores": cores,
             "kind": "oracle", "seconds": dt,
-            "sample": f"one oracle train step of {wl.name} at batch {sample_batch}+{sample_batch} "
-                      f"(full batch is {wl.batch}+{wl.batch}); rate is per sample, so it carries over"}
+            "sample": (f"one whole oracle train step of {wl.name} (batch {wl.batch}+{wl.batch})" if sample_batch == wl.batch
+                       else f"one oracle train step of {wl.name} at batch {sample_batch}+{sample_batch} "
+                            f"(full batch is {wl.batch}+{wl.batch}); rate is per sample, so it carries over")}
+
+
+def gemm_data_probe(ff, torch, wl, iters: int = 20):
+    """The forward contraction of the workload's first layer (one pass), timed on operands that differ only in
+    their VALUES: int8 codes of a quantised Gaussian, a constant, zeros.  Same kernel, same instruction stream,
+    same memory traffic; what changes is the switching activity in the MFMA pipe, so the spread shows how far
+    the launch duration is set by the shader clock under power management rather than by the kernel."""
+    l, B = wl.layers[0], wl.batch
+    desc = ff.layer_desc(l, B)
+    M = B * l.rows_per_sample
+    acc = torch.empty((M, ff.ff_pitch32(l.N)), dtype=torch.int32, device="cuda")
+    gsum = torch.zeros(B, dtype=torch.int64, device="cuda")
+    vmax = torch.zeros(B, dtype=torch.int32, device="cuda")
+    ws = torch.empty(max(ff.ff_layer_workspace_bytes(desc), ff.WS_MIN_BYTES), dtype=torch.uint8, device="cuda")
+    a_shape = (B, l.K) if l.kind == "dense" else (B * l.H * l.W, l.C_in)
+    gen = torch.Generator(device="cuda").manual_seed(1)
+
+    def codes(rows, cols, kind):
+        t = torch.zeros((rows, ff.ff_pitch(cols)), dtype=torch.int8, device="cuda")
+        if kind == "gaussian":
+            t[:, :cols] = (torch.randn((rows, cols), device="cuda", generator=gen) * 23.0).round().clamp(-127, 127).to(torch.int8)
+        elif kind == "constant":
+            t[:, :cols] = 1
+        return t
+
+    res = {}
+    gi = ff.KERNEL_CLASSES.index("gemm_fwd")
+    for kind in ("gaussian", "constant", "zeros"):
+        a_q, w_q = codes(a_shape[0], a_shape[1], kind), codes(l.N, l.K, kind)
+        for _ in range(3):
+            ff.ff_layer_forward(desc, a_q, w_q, acc, gsum, vmax, ws)
+        torch.cuda.synchronize()
+        ff.ff_timing_reset()
+        ff.ff_timing_enable(True)
+        for _ in range(iters):
+            ff.ff_layer_forward(desc, a_q, w_q, acc, gsum, vmax, ws)
+        torch.cuda.synchronize()
+        ff.ff_timing_enable(False)
+        ms, n = ff.ff_timing_read(gi)
+        ops = 2.0 * M * l.K * l.N
+        res[kind] = {"avg_launch_ms": ms / n, "TOPs": ops / (ms / n * 1e-3) / 1e12,
+                     "frac_of_peak": ops / (ms / n * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS}
+    return {"probe": "forward contraction vs operand values", "workload": wl.name, "M": M, "K": l.K, "N": l.N,
+            "launches": iters, "results": res}
 
 
 def main() -> int:
@@ -86,6 +131,9 @@ def main() -> int:
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB-read / 1 GiB-write elementwise kernel (torch.add) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against known traffic")
+    ap.add_argument("--gemm-data-probe", action="store_true",
+                    help="instead of the train step, time the forward contraction of the first layer on Gaussian, "
+                         "constant and zero int8 operands (same kernel and traffic; shows the clock/power effect)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives are part of it); use --gpus 1",
@@ -102,6 +150,9 @@ def main() -> int:
     ff.lib()
     torch.cuda.set_device(0)
     wl = workload(args.workload)
+    if args.gemm_data_probe:
+        print(json.dumps(gemm_data_probe(ff, torch, wl)))
+        return 0
     net, d_xp, d_xn, loss, good, ws = setup(ff, torch, wl)
     k, B = len(wl.layers), wl.batch
 
@@ -175,7 +226,7 @@ def main() -> int:
                          "than BP-GDAI8 (Table V); no per-step figure is published",
     }
     if not args.no_cpu_baseline:
-        sb = args.cpu_sample_batch or {"cfg5": 2048, "cfg2": 1024, "cfg1": 64}.get(wl.name, min(B, 256))
+        sb = args.cpu_sample_batch or {"cfg5": 8192, "cfg2": 1024, "cfg1": 64, "cfg3": 64, "cfg4_plain": 32}.get(wl.name, min(B, 256))
         out["cpu_baseline"] = cpu_baseline(wl, min(sb, B))
     print(json.dumps(out))
     return 0

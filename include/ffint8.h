@@ -80,6 +80,10 @@ typedef struct {
     int32_t n_layers;
     int32_t batch;               /* samples per pass; must equal every layer's batch */
     const ff_layer_desc* layers; /* [host] n_layers entries */
+    const int32_t* train_layer;  /* [host] n_layers flags, or NULL = every layer is trained.  A layer whose flag
+                                    is 0 takes part in the forward pass and in the look-ahead sums of the layers
+                                    before it, but its weights are left as they are (the greedy layer-by-layer
+                                    schedule of Section III trains layer i with layers < i frozen). */
 } ff_net_desc;
 
 /* Trainable state. [host] arrays of n_layers DEVICE pointers.

@@ -256,9 +256,12 @@ def forward_layer(layer, a_f32: np.ndarray, w_q: np.ndarray, s_w, pass_sign: int
 
 def train_step(layers, w_master: List[np.ndarray], x_pos: np.ndarray, x_neg: np.ndarray,
                theta: float, lam: float, lr: float, seed: int, step: int,
-               keep: bool = True) -> Dict:
+               keep: bool = True, train_mask=None) -> Dict:
     """One iteration of Algorithm 1 over both data sets.  Returns the new master weights,
-    the new int8 weights and (keep=True) every intermediate, per layer and pass."""
+    the new int8 weights and (keep=True) every intermediate, per layer and pass.
+    train_mask: optional per-layer flags; a layer whose flag is false is frozen (forward only,
+    its coefficients still enter the look-ahead sums of earlier layers): the greedy
+    layer-by-layer schedule of Section III."""
     k = len(layers)
     wq = [quantize(w, ROUND_NEAREST) for w in w_master]
     B = x_pos.shape[0]
@@ -273,6 +276,12 @@ def train_step(layers, w_master: List[np.ndarray], x_pos: np.ndarray, x_neg: np.
     ctil = [lookahead(np.stack([fwd[i][p]["c"] for i in range(k)]), lam) for p in range(2)]
     new_w, new_wq, new_sw, grads = [], [], [], []
     for i, layer in enumerate(layers):
+        if train_mask is not None and not train_mask[i]:
+            new_w.append(w_master[i])
+            new_wq.append(wq[i][0])
+            new_sw.append(wq[i][1])
+            grads.append(None)
+            continue
         dws, sgs, sas = [], [], []
         per_pass = []
         for p in range(2):

@@ -32,7 +32,8 @@ class LayerDesc(C.Structure):
 
 
 class NetDesc(C.Structure):
-    _fields_ = [("n_layers", C.c_int32), ("batch", C.c_int32), ("layers", C.POINTER(LayerDesc))]
+    _fields_ = [("n_layers", C.c_int32), ("batch", C.c_int32), ("layers", C.POINTER(LayerDesc)),
+                ("train_layer", C.POINTER(C.c_int32))]
 
 
 class NetState(C.Structure):
@@ -194,11 +195,12 @@ class Net:
     Holds references to the tensors so that the pointer arrays stay valid."""
 
     def __init__(self, layers: Sequence, batch: int, w_master: List[torch.Tensor], w_q: List[torch.Tensor],
-                 s_w: List[torch.Tensor]):
+                 s_w: List[torch.Tensor], train_layer: Optional[Sequence[int]] = None):
         self.k = len(layers)
         self.batch = batch
         self._descs = (LayerDesc * self.k)(*[layer_desc(l, batch) for l in layers])
-        self.desc = NetDesc(self.k, batch, self._descs)
+        self._mask = (C.c_int32 * self.k)(*[int(bool(f)) for f in train_layer]) if train_layer is not None else None
+        self.desc = NetDesc(self.k, batch, self._descs, self._mask)
         self.w_master, self.w_q, self.s_w = list(w_master), list(w_q), list(s_w)
         self._pm = (C.c_void_p * self.k)(*[t.data_ptr() for t in self.w_master])
         self._pq = (C.c_void_p * self.k)(*[t.data_ptr() for t in self.w_q])

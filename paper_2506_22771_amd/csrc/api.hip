@@ -833,6 +833,7 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
 
     // ---- per layer: int8 local gradient, int8 weight gradient, update (Algorithm 1, inner loop) ----
     for (int i = 0; i < k; ++i) {
+        if (net->train_layer && !net->train_layer[i]) continue;   // frozen layer: forward only
         const Dims& d = w.d[i];
         const ff_layer_desc& L = net->layers[i];
         const bool dense = d.kind == FF_DENSE;

@@ -131,6 +131,7 @@ def main() -> int:
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB-read / 1 GiB-write elementwise kernel (torch.add) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against known traffic")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph-replay timing")
     ap.add_argument("--gemm-data-probe", action="store_true",
                     help="instead of the train step, time the forward contraction of the first layer on Gaussian, "
                          "constant and zero int8 operands (same kernel and traffic; shows the clock/power effect)")
@@ -163,27 +164,59 @@ def main() -> int:
         torch.cuda.synchronize()
         del cal_in, cal_out
 
-    step_no = 0
-    for _ in range(args.warmup):
-        ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, step_no, loss, good, ws)
-        step_no += 1
+    def run_steps(n, start):
+        for i in range(n):
+            ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, start + i, loss, good, ws)
+        return start + n
+
+    def read_classes(steps):
+        out = {}
+        for ci, name in enumerate(ff.KERNEL_CLASSES):
+            ms, n = ff.ff_timing_read(ci)
+            out[name] = {"ms_per_step": ms / steps, "launches_per_step": n / steps}
+        return out
+
+    step_no = run_steps(args.warmup, 0)
     torch.cuda.synchronize()
+    # ---- the timed region: K steps; HIP events bracket only the launches of the dominant kernel (the two
+    # contractions), because an event record after every one of the ~30 launches of a step would itself
+    # lengthen the step by 5-10 % (it keeps consecutive launches from overlapping)
     ff.ff_timing_reset()
-    ff.ff_timing_enable(True)
+    ff.ff_timing_enable(True, ("gemm_fwd", "gemm_dw"))
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, step_no, loss, good, ws)
-        step_no += 1
+    step_no = run_steps(args.steps, step_no)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ff.ff_timing_enable(False)
     ms_per_step = dt / args.steps * 1e3
     samples = 2 * B
+    kern = read_classes(args.steps)
 
-    kern = {}
-    for ci, name in enumerate(ff.KERNEL_CLASSES):
-        ms, n = ff.ff_timing_read(ci)
-        kern[name] = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps}
+    # ---- outside the timed region: the same K steps with every kernel class timed (the per-class breakdown),
+    # and as K replays of one captured HIP graph (ff_train_step_at keeps the step number in device memory)
+    ff.ff_timing_reset()
+    ff.ff_timing_enable(True)
+    t0 = time.perf_counter()
+    step_no = run_steps(args.steps, step_no)
+    torch.cuda.synchronize()
+    extra = {"all_classes_timed_ms_per_step": (time.perf_counter() - t0) / args.steps * 1e3}
+    ff.ff_timing_enable(False)
+    breakdown = read_classes(args.steps)
+    if not args.no_graph:
+        step_dev = torch.tensor([step_no], dtype=torch.int64, device="cuda")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            ff.ff_train_step_at(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, step_dev, 1, loss, good, ws)
+        for _ in range(2):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) / args.steps * 1e3
+        extra["graph_replay_ms_per_step"] = g_ms
+        extra["graph_replay_samples_per_s_per_layer_step"] = 2 * B * k / (g_ms * 1e-3)
 
     # dominant kernel: the int8 contraction (forward + weight-gradient launches; each launch covers both passes)
     gemm_ms = kern["gemm_fwd"]["ms_per_step"] + kern["gemm_dw"]["ms_per_step"]
@@ -221,7 +254,8 @@ def main() -> int:
                    "int8_TOPs_whole_step": ops_per_step / (ms_per_step * 1e-3) / 1e12},
         "int8_mfma_pct_of_peak": 100.0 * achieved / INT8_MFMA_PEAK_TOPS,
         "roofline": roofline,
-        "kernels_ms_per_step": {n: round(v["ms_per_step"], 5) for n, v in kern.items()},
+        "kernels_ms_per_step": {n: round(v["ms_per_step"], 5) for n, v in breakdown.items()},
+        "other_launch_modes": extra,
         "paper_context": "Jetson Orin Nano, whole training runs: 4.6% faster, 8.3% less energy, 27.0% less memory "
                          "than BP-GDAI8 (Table V); no per-step figure is published",
     }

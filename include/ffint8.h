@@ -240,15 +240,36 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
                         uint64_t step, float* loss, float* goodness, void* ws, size_t ws_bytes,
                         void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * ff_train_step_at — ff_train_step with the step number in DEVICE memory: the kernels read
+ * *step_dev when they run, not when the call is made, so a HIP graph captured from one call can
+ * be replayed for every later iteration of Algorithm 1 (a launch-bound small network spends most
+ * of an eagerly launched step on launch latency).  advance != 0: the last kernel of the call adds
+ * one to *step_dev.  Same results, bit for bit, as ff_train_step(step = *step_dev).
+ *   step_dev  one uint64 (in/out, 8-byte aligned); must stay allocated while a graph holding the
+ *             call is alive.
+ * The call neither allocates nor synchronises and enqueues kernels only, so it may be made on a
+ * stream under capture (kernel timing, if enabled, is skipped for captured launches).  All other
+ * arguments, outputs and errors as ff_train_step.
+ * ------------------------------------------------------------------------------------------- */
+ff_status ff_train_step_at(const ff_net_desc* net, const ff_net_state* state, const float* x_pos,
+                           const float* x_neg, float theta, float lambda, float lr, uint64_t seed,
+                           uint64_t* step_dev, int32_t advance, float* loss, float* goodness,
+                           void* ws, size_t ws_bytes, void* stream);
+
 /* Bytes of workspace ff_train_step needs for `net`; 0 if the descriptor is invalid. [host only] */
 size_t ff_workspace_bytes(const ff_net_desc* net);
 
 /* ---------------------------------------------------------------------------------------------
- * Instrumentation (not part of the method).  When enabled, every kernel launch of the library is
+ * Instrumentation (not part of the method).  ff_timing_enable(class_mask): bit c of the mask
+ * selects kernel class c (-1 = every class, 0 = off).  Every launch of a selected class is
  * bracketed by a pair of HIP events recorded on the launch stream; ff_timing_read waits for the
  * recorded events and returns the summed device time and the launch count of one kernel class.
+ * An event record keeps the next launch from overlapping the previous kernel's tail, so timing
+ * every class costs several per cent of a step; timing only the contractions costs under one.
  * Events are host-side objects created on first use (at most FF_TIMING_MAX_RECORDS pairs; launches
- * beyond that are not recorded).  Not thread-safe; meant for benchmarks.
+ * beyond that are not recorded; launches on a stream under capture are never recorded).
+ * Not thread-safe; meant for benchmarks.
  * ------------------------------------------------------------------------------------------- */
 enum {
     FF_K_GEMM_FWD = 0,   /* forward contraction (+ fused goodness reductions) */
@@ -263,7 +284,7 @@ enum {
     FF_K_COUNT = 9
 };
 #define FF_TIMING_MAX_RECORDS 16384
-ff_status ff_timing_enable(int32_t on);
+ff_status ff_timing_enable(int32_t class_mask);
 ff_status ff_timing_reset(void);
 ff_status ff_timing_read(int32_t kernel_class, double* total_ms, int64_t* launches);
 

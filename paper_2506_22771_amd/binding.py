@@ -81,6 +81,9 @@ def lib() -> C.CDLL:
         L.ff_train_step.restype = i32
         L.ff_train_step.argtypes = [C.POINTER(NetDesc), C.POINTER(NetState), P, P, f32, f32, f32, u64, u64, P, P, P,
                                     sz, P]
+        L.ff_train_step_at.restype = i32
+        L.ff_train_step_at.argtypes = [C.POINTER(NetDesc), C.POINTER(NetState), P, P, f32, f32, f32, u64, P, i32, P, P,
+                                       P, sz, P]
         L.ff_workspace_bytes.restype = sz
         L.ff_workspace_bytes.argtypes = [C.POINTER(NetDesc)]
         L.ff_timing_enable.restype = i32
@@ -221,11 +224,21 @@ def ff_train_step(net: Net, x_pos, x_neg, theta, lam, lr, seed, step, loss, good
                              ws.numel() * ws.element_size() if ws is not None else 0, _stream()), "ff_train_step")
 
 
+def ff_train_step_at(net: Net, x_pos, x_neg, theta, lam, lr, seed, step_dev, advance, loss, goodness, ws) -> None:
+    _chk(lib().ff_train_step_at(C.byref(net.desc), C.byref(net.state), _ptr(x_pos), _ptr(x_neg), theta, lam, lr, seed,
+                                _ptr(step_dev), int(advance), _ptr(loss), _ptr(goodness), _ptr(ws),
+                                ws.numel() * ws.element_size() if ws is not None else 0, _stream()), "ff_train_step_at")
+
+
 KERNEL_CLASSES = ("gemm_fwd", "gemm_dw", "quant_act", "quant_grad", "quant_w", "update", "absmax", "small", "im2col")
 
 
-def ff_timing_enable(on: bool) -> None:
-    _chk(lib().ff_timing_enable(1 if on else 0), "ff_timing_enable")
+def ff_timing_enable(on, classes: Optional[Sequence[str]] = None) -> None:
+    """on: False = off, True = every kernel class, or restrict to the named `classes` (see KERNEL_CLASSES)."""
+    mask = 0
+    if on:
+        mask = -1 if classes is None else sum(1 << KERNEL_CLASSES.index(c) for c in classes)
+    _chk(lib().ff_timing_enable(mask), "ff_timing_enable")
 
 
 def ff_timing_reset() -> None:

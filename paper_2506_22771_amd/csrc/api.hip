@@ -6,25 +6,6 @@
 
 namespace ffi {
 
-static uint64_t fin64(uint64_t z)
-{
-    z ^= z >> 30;
-    z *= 0xBF58476D1CE4E5B9ull;
-    z ^= z >> 27;
-    z *= 0x94D049BB133111EBull;
-    z ^= z >> 31;
-    return z;
-}
-
-SrKey make_sr_key(uint64_t seed, uint64_t tag)
-{
-    const uint64_t key = fin64(seed + 0x9E3779B97F4A7C15ull * (tag + 1ull));
-    SrKey k;
-    k.k0 = (uint32_t)key;
-    k.k1 = (uint32_t)(key >> 32) | 1u;
-    return k;
-}
-
 constexpr int64_t INT32_SAFE_LEN = 2147483647ll / (127 * 127);  // longest reduction that cannot overflow int32
 constexpr int MAX_LAYERS = 32;
 constexpr int MAX_CHUNKS = 2;  // weight-gradient accumulators per pass (k_update combines at most 4 terms)
@@ -238,7 +219,7 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
 
 // ---- instrumentation: HIP events around each launch, recorded on the launch stream -----------------
 struct TimingState {
-    bool on = false;
+    uint32_t mask = 0;   // bit c set: launches of kernel class c are timed
     int n = 0;
     hipEvent_t* ev = nullptr;  // 2 per record
     int8_t* cls = nullptr;
@@ -252,7 +233,9 @@ struct Timed {
     Timed(int kernel_class, hipStream_t stream) : s(stream)
     {
         TimingState& t = g_timing;
-        if (!t.on || t.n >= FF_TIMING_MAX_RECORDS) return;
+        if (!((t.mask >> kernel_class) & 1u) || t.n >= FF_TIMING_MAX_RECORDS) return;
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;   // no event records into a graph under capture
+        if (hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return;
         if (!t.ev) {
             t.ev = new hipEvent_t[2 * FF_TIMING_MAX_RECORDS];
             t.cls = new int8_t[FF_TIMING_MAX_RECORDS];
@@ -403,7 +386,7 @@ int64_t ff_pitch32(int64_t cols) { return pitch32(cols); }
 
 uint64_t ff_stream_tag(uint64_t step, uint32_t layer, uint32_t pass_idx, uint32_t kind)
 {
-    return (step << 20) | ((uint64_t)layer << 4) | ((uint64_t)pass_idx << 2) | (uint64_t)kind;
+    return stream_tag_of(step, layer, pass_idx, kind);
 }
 
 const char* ff_status_string(ff_status s)
@@ -700,9 +683,14 @@ size_t ff_workspace_bytes(const ff_net_desc* net)
     return w.total;
 }
 
-ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const float* x_pos, const float* x_neg,
-                        float theta, float lambda, float lr, uint64_t seed, uint64_t step, float* loss,
-                        float* goodness, void* ws, size_t ws_bytes, void* stream)
+}  // extern "C"
+
+// One iteration of Algorithm 1.  step_dev == null: the step number is `step`; otherwise it is read from device
+// memory by the kernels (and advanced by one at the end when `advance` is set).
+static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* state, const float* x_pos,
+                                 const float* x_neg, float theta, float lambda, float lr, uint64_t seed, uint64_t step,
+                                 uint64_t* step_dev, int32_t advance, float* loss, float* goodness, void* ws,
+                                 size_t ws_bytes, void* stream)
 {
     WsLayout w;
     const ff_status st = make_layout(net, &w);
@@ -770,6 +758,10 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         a.round_mode = FF_ROUND_STOCHASTIC;
         a.key = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 0, FF_KIND_ACT));
         a.key2 = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 1, FF_KIND_ACT));
+        a.step_dev = step_dev;
+        a.seed = seed;
+        a.tag_layer = (uint32_t)i;
+        a.tag_kind = FF_KIND_ACT;
         a.rows = d.in_rows;
         a.cols = d.in_cols;
         a.q = (int8_t*)(base + w.off_aq[i]);
@@ -854,6 +846,10 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         a.round_mode = FF_ROUND_STOCHASTIC;
         a.key = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 0, FF_KIND_GRAD));
         a.key2 = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 1, FF_KIND_GRAD));
+        a.step_dev = step_dev;
+        a.seed = seed;
+        a.tag_layer = (uint32_t)i;
+        a.tag_kind = FF_KIND_GRAD;
         a.rows = d.M;
         a.cols = d.N;
         a.q_t = (int8_t*)(base + w.off_gy);
@@ -906,12 +902,32 @@ ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const
         qa.rows_per_sample = 1;
         HIPCHK_T(FF_K_QUANT_W, launch_quantize(QSRC_F32, qa, s));
     }
+    if (step_dev && advance) HIPCHK_T(FF_K_SMALL, launch_advance_u64(step_dev, s));
     return FF_OK;
 }
 
-ff_status ff_timing_enable(int32_t on)
+extern "C" {
+
+ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const float* x_pos, const float* x_neg,
+                        float theta, float lambda, float lr, uint64_t seed, uint64_t step, float* loss,
+                        float* goodness, void* ws, size_t ws_bytes, void* stream)
 {
-    g_timing.on = on != 0;
+    return train_step_impl(net, state, x_pos, x_neg, theta, lambda, lr, seed, step, nullptr, 0, loss, goodness, ws,
+                           ws_bytes, stream);
+}
+
+ff_status ff_train_step_at(const ff_net_desc* net, const ff_net_state* state, const float* x_pos, const float* x_neg,
+                           float theta, float lambda, float lr, uint64_t seed, uint64_t* step_dev, int32_t advance,
+                           float* loss, float* goodness, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!step_dev || ((uintptr_t)step_dev & 7)) return step_dev ? FF_ERR_ALIGN : FF_ERR_INVALID_ARG;
+    return train_step_impl(net, state, x_pos, x_neg, theta, lambda, lr, seed, 0, step_dev, advance, loss, goodness, ws,
+                           ws_bytes, stream);
+}
+
+ff_status ff_timing_enable(int32_t class_mask)
+{
+    g_timing.mask = (uint32_t)class_mask & ((1u << FF_K_COUNT) - 1u);
     return FF_OK;
 }
 

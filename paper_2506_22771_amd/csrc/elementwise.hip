@@ -74,6 +74,17 @@ hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s)
     return hipGetLastError();
 }
 
+__global__ void k_advance_u64(uint64_t* counter)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) counter[0] += 1;
+}
+
+hipError_t launch_advance_u64(uint64_t* counter, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_advance_u64, dim3(1), dim3(64), 0, s, counter);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------------
 // absmax of fp32 tensors -> bit pattern in slot[z] (HBM-bound: 4 bytes read per element).
 // blockIdx.y selects the tensor (x + z*stride); four independent 16-byte loads per thread per trip.
@@ -171,7 +182,8 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
     const float* __restrict__ per_sample = a.per_sample ? a.per_sample + z * a.st_per_sample : nullptr;
     int8_t* __restrict__ q = a.q ? a.q + z * a.st_q : nullptr;
     int8_t* __restrict__ q_t = a.q_t ? a.q_t + z * a.st_qt : nullptr;
-    const SrKey key = z ? a.key2 : a.key;
+    SrKey key = z ? a.key2 : a.key;
+    if (a.step_dev) key = make_sr_key(a.seed, stream_tag_of(a.step_dev[0], a.tag_layer, (uint32_t)z, a.tag_kind));
 
     // a vanishing range (absmax < 2^-100, all-zero tensor included) quantises to zero codes with scale 1
     const float amax = __uint_as_float(a.amax_bits[z * a.st_amax]);

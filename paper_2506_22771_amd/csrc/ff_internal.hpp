@@ -20,7 +20,26 @@ struct SrKey {
     uint32_t k0;  // low word of the 64-bit key
     uint32_t k1;  // (high word | 1), multiplies the high half of the element index
 };
-SrKey make_sr_key(uint64_t seed, uint64_t tag);
+// key = finaliser of splitmix64 over (seed, stream tag); the same code runs on the host and, when the step
+// number lives in device memory, at the head of the quantise kernels
+__host__ __device__ inline SrKey make_sr_key(uint64_t seed, uint64_t tag)
+{
+    uint64_t z = seed + 0x9E3779B97F4A7C15ull * (tag + 1ull);
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    SrKey k;
+    k.k0 = (uint32_t)z;
+    k.k1 = (uint32_t)(z >> 32) | 1u;
+    return k;
+}
+// stream tag of (step, layer, pass, kind): step << 20 | layer << 4 | pass << 2 | kind
+__host__ __device__ inline uint64_t stream_tag_of(uint64_t step, uint32_t layer, uint32_t pass_idx, uint32_t kind)
+{
+    return (step << 20) | ((uint64_t)layer << 4) | ((uint64_t)pass_idx << 2) | (uint64_t)kind;
+}
 
 // ---- quantise kernels (elementwise.hip) -----------------------------------------------------
 enum QSource { QSRC_F32 = 0, QSRC_HANDOFF = 1, QSRC_GRAD = 2 };
@@ -52,6 +71,11 @@ struct QuantArgs {
     int64_t st_x, st_acc, st_per_sample, st_q, st_qt;
     int32_t st_s_a, st_s_w, st_amax, st_scale;
     SrKey key2;  // key of the second problem
+    // step number in device memory (null: the keys above are used).  The kernel then derives its key from
+    // (seed, stream tag of (*step_dev, tag_layer, problem index, tag_kind)).
+    const uint64_t* step_dev;
+    uint64_t seed;
+    uint32_t tag_layer, tag_kind;
 };
 hipError_t launch_quantize(int src, const QuantArgs& a, hipStream_t s);
 
@@ -59,6 +83,7 @@ hipError_t launch_quantize(int src, const QuantArgs& a, hipStream_t s);
 // slots must be zeroed first).
 hipError_t launch_absmax(const float* x, int64_t st_x, int nb, int64_t n, uint32_t* slot, hipStream_t s);
 hipError_t launch_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s);
+hipError_t launch_advance_u64(uint64_t* counter, hipStream_t s);   // *counter += 1, in stream order
 
 // ---- per-sample kernels ----------------------------------------------------------------------
 struct GoodnessArgs {

@@ -24,7 +24,10 @@
  * bounds and unbiasedness of stochastic rounding, brute-force integer dot
  * products, 1x1 convolution == dense, padded constant image, direct convolution
  * == explicit im2col + library matmul, finite differences of the un-quantised
- * loss for the local gradient, and a hand-computed look-ahead example.
+ * loss for the local gradient, a hand-computed look-ahead example, and for
+ * the residual-block functions: zero skip == plain layer, zero weights ==
+ * dequantised input, exact goodness of power-of-two activities, order
+ * independence and agreement with the fp64 sum of squares.
  * The look-ahead *semantics* (which reading of Eq. (4) is meant) has no pin in
  * the paper: parity unpinned for that choice; its arithmetic is pinned.
  */
@@ -357,6 +360,90 @@ int ffo_local_grad(const int32_t *acc, int64_t B, int64_t terms, int relu, float
             if (relu && y < 0.0f) y = 0.0f;
             g[b * terms + t] = d * y;
         }
+    }
+    return FFO_OK;
+}
+
+/* ------------------------------------------------------------------------
+ * Residual blocks (Section IV-C names ResNet-style blocks; it gives no
+ * mechanics, so this is a reading).  The second convolution of a basic block
+ * is the FF layer whose activity is the BLOCK OUTPUT
+ *     y = act( fp32(acc) * (s_a * s_w)  +  u ),
+ * u = the skip value: the dequantised int8 block input fp32(x_q) * s_x
+ * (identity), or the output of the 1x1 projection fp32(acc_p) * (s_a_p * s_w_p)
+ * (down-sampling blocks).  One rounding per written operation.
+ * ---------------------------------------------------------------------- */
+int ffo_skip_identity(const int8_t *x_q, int64_t n, float s_x, float *u)
+{
+    if (!x_q || !u) return FFO_ERR_ARG;
+    for (int64_t i = 0; i < n; ++i) u[i] = (float)x_q[i] * s_x;
+    return FFO_OK;
+}
+
+int ffo_skip_projection(const int32_t *acc_p, int64_t n, float s_a, float s_w, float *u)
+{
+    if (!acc_p || !u) return FFO_ERR_ARG;
+    const float s_y = s_a * s_w;
+    for (int64_t i = 0; i < n; ++i) u[i] = (float)acc_p[i] * s_y;
+    return FFO_OK;
+}
+
+int ffo_residual_act(const int32_t *acc, const float *u, int64_t n, int relu, float s_a, float s_w,
+                     float *y)
+{
+    if (!acc || !u || !y) return FFO_ERR_ARG;
+    const float s_y = s_a * s_w;
+    for (int64_t i = 0; i < n; ++i) {
+        const float t = (float)acc[i] * s_y;
+        float v = t + u[i];
+        if (relu && v < 0.0f) v = 0.0f;
+        y[i] = v;
+    }
+    return FFO_OK;
+}
+
+/* Goodness of an fp32 activity tensor, made order-free: with amax = max |y| over
+ * the whole tensor of the pass, each term enters as the integer
+ *     floor( r * r * 2^40 ),  r = y * (1 / amax)   (r, 1/amax in fp32; r*r*2^40 exact in fp64)
+ * and G = fp32( fp64(sum) * 2^-40 * amax * amax ).  amax < 2^-100: G = 0.
+ * Also returns max |y| per sample and the plain fp64 sum of squares. */
+int ffo_goodness_fx(const float *y, int64_t B, int64_t terms, float amax, uint64_t *g_int,
+                    float *ymax, float *G, double *G_plain)
+{
+    if (!y || !g_int || !ymax || !G || !G_plain || terms > ((int64_t)1 << 22)) return FFO_ERR_ARG;
+    const int live = amax >= 0x1p-100f;
+    const float inv = live ? 1.0f / amax : 0.0f;
+    for (int64_t b = 0; b < B; ++b) {
+        uint64_t gi = 0;
+        float vm = 0.0f;
+        double plain = 0.0;
+        for (int64_t t = 0; t < terms; ++t) {
+            const float v = y[b * terms + t];
+            const float av = fabsf(v);
+            if (av > vm) vm = av;
+            const float r = v * inv;
+            gi += (uint64_t)((double)r * (double)r * 0x1p40);
+            plain += (double)v * (double)v;
+        }
+        g_int[b] = gi;
+        ymax[b] = vm;
+        G_plain[b] = plain;
+        double g = (double)gi;
+        g = g * 0x1p-40;
+        g = g * (double)amax;
+        g = g * (double)amax;
+        G[b] = live ? (float)g : 0.0f;
+    }
+    return FFO_OK;
+}
+
+/* Local gradient from fp32 activities: g = (2 * ctil[b]) * y. */
+int ffo_local_grad_f32(const float *y, int64_t B, int64_t terms, const float *ctil, float *g)
+{
+    if (!y || !ctil || !g) return FFO_ERR_ARG;
+    for (int64_t b = 0; b < B; ++b) {
+        const float d = 2.0f * ctil[b];
+        for (int64_t t = 0; t < terms; ++t) g[b * terms + t] = d * y[b * terms + t];
     }
     return FFO_OK;
 }

@@ -55,6 +55,11 @@ def lib() -> C.CDLL:
         L.ffo_lookahead.argtypes = [P, i32, i64, f32, P]
         L.ffo_local_grad.argtypes = [P, i64, i64, i32, f32, f32, P, P]
         L.ffo_dense_wgrad.argtypes = [P, P, i64, i64, i64, P]
+        L.ffo_skip_identity.argtypes = [P, i64, f32, P]
+        L.ffo_skip_projection.argtypes = [P, i64, f32, f32, P]
+        L.ffo_residual_act.argtypes = [P, P, i64, i32, f32, f32, P]
+        L.ffo_goodness_fx.argtypes = [P, i64, i64, f32, P, P, P, P]
+        L.ffo_local_grad_f32.argtypes = [P, i64, i64, P, P]
         L.ffo_conv_wgrad.argtypes = [P, P, i64, i64, i64, i64, i64, i64, i64, i64, i64, P]
         L.ffo_update.argtypes = [P, i64, P, P, P, i32, f32, i32]
         _lib = L
@@ -187,6 +192,54 @@ def local_grad(acc: np.ndarray, relu: int, s_a, s_w, ctil: np.ndarray) -> np.nda
     return g
 
 
+# ---- residual blocks (a reading: the paper names ResNet-style blocks in Section IV-C without mechanics) ----
+def skip_identity(x_q: np.ndarray, s_x) -> np.ndarray:
+    x_q = np.ascontiguousarray(x_q, dtype=np.int8)
+    u = np.empty(x_q.shape, dtype=np.float32)
+    _chk(lib().ffo_skip_identity(_p(x_q), x_q.size, np.float32(s_x), _p(u)), "skip_identity")
+    return u
+
+
+def skip_projection(acc_p: np.ndarray, s_a, s_w) -> np.ndarray:
+    acc_p = np.ascontiguousarray(acc_p, dtype=np.int32)
+    u = np.empty(acc_p.shape, dtype=np.float32)
+    _chk(lib().ffo_skip_projection(_p(acc_p), acc_p.size, np.float32(s_a), np.float32(s_w), _p(u)), "skip_projection")
+    return u
+
+
+def residual_act(acc: np.ndarray, u: np.ndarray, relu: int, s_a, s_w) -> np.ndarray:
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    u = np.ascontiguousarray(u, dtype=np.float32)
+    assert acc.shape == u.shape
+    y = np.empty(acc.shape, dtype=np.float32)
+    _chk(lib().ffo_residual_act(_p(acc), _p(u), acc.size, relu, np.float32(s_a), np.float32(s_w), _p(y)), "residual_act")
+    return y
+
+
+def goodness_fx(y: np.ndarray) -> Dict[str, np.ndarray]:
+    """Order-free goodness of an fp32 activity tensor [B, ...] (one pass): see ffo_goodness_fx."""
+    y = np.ascontiguousarray(y, dtype=np.float32)
+    B = y.shape[0]
+    terms = y.size // B if B else 0
+    amax = np.float32(np.max(np.abs(y))) if y.size else np.float32(0)
+    g_int = np.empty(B, dtype=np.uint64)
+    ymax = np.empty(B, dtype=np.float32)
+    G = np.empty(B, dtype=np.float32)
+    G_plain = np.empty(B, dtype=np.float64)
+    _chk(lib().ffo_goodness_fx(_p(y), B, terms, amax, _p(g_int), _p(ymax), _p(G), _p(G_plain)), "goodness_fx")
+    return dict(g_int=g_int, ymax=ymax, G=G, G_plain=G_plain, amax=amax)
+
+
+def local_grad_f32(y: np.ndarray, ctil: np.ndarray) -> np.ndarray:
+    y = np.ascontiguousarray(y, dtype=np.float32)
+    B = y.shape[0]
+    terms = y.size // B if B else 0
+    ctil = np.ascontiguousarray(ctil, dtype=np.float32)
+    g = np.empty(y.shape, dtype=np.float32)
+    _chk(lib().ffo_local_grad_f32(_p(y), B, terms, _p(ctil), _p(g)), "local_grad_f32")
+    return g
+
+
 def dense_wgrad(gy_q: np.ndarray, a_q: np.ndarray) -> np.ndarray:
     M, N = gy_q.shape
     M2, K = a_q.shape
@@ -254,6 +307,10 @@ def forward_layer(layer, a_f32: np.ndarray, w_q: np.ndarray, s_w, pass_sign: int
                 a_next=a_next, **gd)
 
 
+def _layer_attr(layer, name, default):
+    return getattr(layer, name, default)
+
+
 def train_step(layers, w_master: List[np.ndarray], x_pos: np.ndarray, x_neg: np.ndarray,
                theta: float, lam: float, lr: float, seed: int, step: int,
                keep: bool = True, train_mask=None) -> Dict:
@@ -261,32 +318,77 @@ def train_step(layers, w_master: List[np.ndarray], x_pos: np.ndarray, x_neg: np.
     the new int8 weights and (keep=True) every intermediate, per layer and pass.
     train_mask: optional per-layer flags; a layer whose flag is false is frozen (forward only,
     its coefficients still enter the look-ahead sums of earlier layers): the greedy
-    layer-by-layer schedule of Section III."""
+    layer-by-layer schedule of Section III.
+
+    Basic residual blocks (a reading, see ffo_residual_act): a layer may carry
+      input_back = n : its input is the output of layer i-1-n (0 = the previous layer),
+      role = 'proj'  : a 1x1 projection branch: contraction only, no activity, goodness or
+                       hand-off of its own; its accumulators are the skip of layer i+2,
+      skip = 'identity'   : block output y = act(s*acc + dequantised input of layer i-1),
+      skip = 'projection' : block output y = act(s*acc + s_p*acc of layer i-2).
+    A projection layer is updated with the quantised local gradient of the block output."""
     k = len(layers)
     wq = [quantize(w, ROUND_NEAREST) for w in w_master]
     B = x_pos.shape[0]
+    role = [_layer_attr(l, "role", "ff") for l in layers]
+    skip = [_layer_attr(l, "skip", "none") for l in layers]
     fwd: List[List[Dict]] = [[None, None] for _ in range(k)]
     for p, (x, sign) in enumerate(((x_pos, PASS_POS), (x_neg, PASS_NEG))):
-        a = np.ascontiguousarray(x, dtype=np.float32)
+        outs: List[np.ndarray] = [None] * k
         for i, layer in enumerate(layers):
-            f = forward_layer(layer, a, wq[i][0], wq[i][1], sign, theta, seed,
-                              stream_tag(step, i, p, KIND_ACT))
-            a = f.pop("a_next")
-            fwd[i][p] = f
+            src = i - 1 - _layer_attr(layer, "input_back", 0)
+            a = np.ascontiguousarray(x if src < 0 else outs[src], dtype=np.float32)
+            tag = stream_tag(step, i, p, KIND_ACT)
+            if role[i] == "proj":
+                a_q, s_a = quantize(a, ROUND_STOCHASTIC, seed, tag)
+                acc = conv_forward(a_q, wq[i][0], layer.stride, layer.pad)
+                fwd[i][p] = dict(a_q=a_q, s_a=s_a, acc=acc, c=np.zeros(B, np.float32), loss_mean=0.0,
+                                 G=np.zeros(B, np.float32))
+            elif skip[i] == "none":
+                f = forward_layer(layer, a, wq[i][0], wq[i][1], sign, theta, seed, tag)
+                outs[i] = f.pop("a_next")
+                fwd[i][p] = f
+            else:
+                a_q, s_a = quantize(a, ROUND_STOCHASTIC, seed, tag)
+                acc = conv_forward(a_q, wq[i][0], layer.stride, layer.pad)
+                if skip[i] == "identity":
+                    u = skip_identity(fwd[i - 1][p]["a_q"], fwd[i - 1][p]["s_a"])
+                else:
+                    u = skip_projection(fwd[i - 2][p]["acc"], fwd[i - 2][p]["s_a"], wq[i - 2][1])
+                y = residual_act(acc, u.reshape(acc.shape), layer.relu, s_a, wq[i][1])
+                gd = goodness_fx(y)
+                c, loss, loss_mean = loss_coeff(gd["G"], sign, theta)
+                outs[i] = y
+                fwd[i][p] = dict(a_q=a_q, s_a=s_a, acc=acc, y=y, c=c, loss=loss, loss_mean=loss_mean, **gd)
     ctil = [lookahead(np.stack([fwd[i][p]["c"] for i in range(k)]), lam) for p in range(2)]
-    new_w, new_wq, new_sw, grads = [], [], [], []
+    new_w = [None] * k
+    new_wq = [None] * k
+    new_sw = [None] * k
+    grads = [None] * k
+
+    def frozen(i):
+        return train_mask is not None and not train_mask[i]
+
+    def finish(i, dws, sgs, sas):
+        if frozen(i):
+            new_w[i], new_wq[i], new_sw[i] = w_master[i], wq[i][0], wq[i][1]
+            return
+        w_new = update(w_master[i], dws, sgs, sas, lr, 2 * B)
+        q_new, s_new = quantize(w_new, ROUND_NEAREST)
+        new_w[i], new_wq[i], new_sw[i] = w_new, q_new, s_new
+
     for i, layer in enumerate(layers):
-        if train_mask is not None and not train_mask[i]:
-            new_w.append(w_master[i])
-            new_wq.append(wq[i][0])
-            new_sw.append(wq[i][1])
-            grads.append(None)
-            continue
+        if role[i] == "proj":
+            continue          # updated together with the block-output layer i+2
         dws, sgs, sas = [], [], []
+        pdws, psas = [], []
         per_pass = []
         for p in range(2):
             f = fwd[i][p]
-            g = local_grad(f["acc"], layer.relu, f["s_a"], wq[i][1], ctil[p][i])
+            if skip[i] == "none":
+                g = local_grad(f["acc"], layer.relu, f["s_a"], wq[i][1], ctil[p][i])
+            else:
+                g = local_grad_f32(f["y"], ctil[p][i])
             gy_q, s_g = quantize(g, ROUND_STOCHASTIC, seed, stream_tag(step, i, p, KIND_GRAD))
             chunks = batch_chunks(B, layer.rows_per_sample)
             dw_chunks = []
@@ -299,13 +401,15 @@ def train_step(layers, w_master: List[np.ndarray], x_pos: np.ndarray, x_neg: np.
                 dws.append(dw.reshape(-1))
                 sgs.append(s_g)
                 sas.append(f["s_a"])
+                if skip[i] == "projection":
+                    lp, fp = layers[i - 2], fwd[i - 2][p]
+                    pdws.append(conv_wgrad(gy_q, fp["a_q"], lp.ksize, lp.stride, lp.pad, b0, b1).reshape(-1))
+                    psas.append(fp["s_a"])
             per_pass.append(dict(gy_q=gy_q, s_g=s_g, dw=dw_chunks, ctil=ctil[p][i]))
-        w_new = update(w_master[i], dws, sgs, sas, lr, 2 * B)
-        q_new, s_new = quantize(w_new, ROUND_NEAREST)
-        new_w.append(w_new)
-        new_wq.append(q_new)
-        new_sw.append(s_new)
-        grads.append(per_pass)
+        finish(i, dws, sgs, sas)
+        if skip[i] == "projection":
+            finish(i - 2, pdws, sgs, psas)
+        grads[i] = per_pass
     out = dict(w_master=new_w, w_q=new_wq, s_w=new_sw,
                loss=np.array([[fwd[i][p]["loss_mean"] for p in range(2)] for i in range(k)]),
                goodness=np.stack([np.stack([fwd[i][p]["G"] for p in range(2)]) for i in range(k)]))

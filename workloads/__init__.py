@@ -38,6 +38,10 @@ class Layer:
     pad: int = 0
     relu: int = 1
     l2norm_out: int = 0
+    # basic residual blocks: see the docstring of `res_stack`
+    input_back: int = 0        # the layer input is the output of layer i-1-input_back
+    role: str = "ff"           # 'ff' | 'proj' (1x1 projection branch of a down-sampling block)
+    skip: str = "none"         # 'none' | 'identity' | 'projection'
 
     @property
     def H_out(self) -> int:
@@ -108,6 +112,28 @@ def conv_stack(channels: List[int], h: int, w: int) -> Tuple[Layer, ...]:
                        ksize=3, stride=1, pad=1) for i in range(len(channels) - 1))
 
 
+def res_stack(stem_out: int, stages: List[Tuple[int, int, int]], h: int, w: int, c_in: int = 3) -> Tuple[Layer, ...]:
+    """Stem conv3x3 + basic residual blocks.  stages: (channels, first stride, blocks).
+    A block is conv1 (3x3, stride s) and conv2 (3x3), the second one producing the block output
+    relu(conv2 + skip); skip is the block input (identity) or, when the shape changes, a 1x1 stride-s
+    projection of it, which is listed first: [proj, conv1 (input_back=1), conv2 (skip='projection')]."""
+    layers = [Layer("conv", H=h, W=w, C_in=c_in, C_out=stem_out, ksize=3, stride=1, pad=1)]
+    c = stem_out
+    for (c_out, stride, blocks) in stages:
+        for b in range(blocks):
+            s = stride if b == 0 else 1
+            ho, wo = (h + 2 - 3) // s + 1, (w + 2 - 3) // s + 1
+            change = s != 1 or c != c_out
+            if change:
+                layers.append(Layer("conv", H=h, W=w, C_in=c, C_out=c_out, ksize=1, stride=s, pad=0, relu=0, role="proj"))
+            layers.append(Layer("conv", H=h, W=w, C_in=c, C_out=c_out, ksize=3, stride=s, pad=1,
+                                input_back=1 if change else 0))
+            layers.append(Layer("conv", H=ho, W=wo, C_in=c_out, C_out=c_out, ksize=3, stride=1, pad=1,
+                                skip="projection" if change else "identity"))
+            c, h, w = c_out, ho, wo
+    return tuple(layers)
+
+
 def workload(name: str) -> Workload:
     """The benchmark configurations (shapes only; all data is synthetic)."""
     if name == "cfg1":   # small MLP, latency-bound
@@ -126,6 +152,13 @@ def workload(name: str) -> Workload:
             layers.append(Layer("conv", H=hw, W=hw, C_in=c_in, C_out=c_out, ksize=3, stride=stride, pad=1))
             c_in, hw = c_out, (hw + 2 - 3) // stride + 1
         return Workload("cfg4_plain", tuple(layers), 256, "uniform_onehot", lam=0.05)
+    if name == "cfg4":
+        # ResNet-18-shaped: stem + 4 stages x 2 basic blocks (64/128/256/512 channels, 32 -> 16 -> 8 -> 4 pixels):
+        # 17 conv3x3 + 3 conv1x1 projections, every convolution an FF layer (the projections share their block's loss)
+        return Workload("cfg4", res_stack(64, [(64, 1, 2), (128, 2, 2), (256, 2, 2), (512, 2, 2)], 32, 32), 256,
+                        "uniform_onehot", lam=0.05)
+    if name == "tiny_res":   # stem 3->16 at 8x16, an identity block, a down-sampling block with projection
+        return Workload("tiny_res", res_stack(16, [(16, 1, 1), (32, 2, 1)], 8, 16), 6, "uniform_onehot", lam=0.05)
     if name == "cfg5":   # large-GEMM stress
         return Workload("cfg5", mlp([4096, 4096, 4096], False), 8192, "normal", lam=0.05)
     if name == "tiny":   # ragged shapes spanning tile tails, for quick parity tests

@@ -73,7 +73,27 @@ typedef struct {
     int32_t kind, batch, in_features, out_features;
     int32_t H, W, C_in, C_out, ksize, stride, pad;
     int32_t relu, l2norm_out;
+    /* Basic residual blocks in ff_train_step (all zero = a plain chain; see "Residual blocks" below). */
+    int32_t input_back; /* the layer input is the output of layer i-1-input_back (0 or 1) */
+    int32_t role;       /* FF_ROLE_LAYER or FF_ROLE_PROJECTION */
+    int32_t skip;       /* FF_SKIP_NONE, FF_SKIP_IDENTITY or FF_SKIP_PROJECTION */
 } ff_layer_desc;
+
+/* Residual blocks (the paper's Section IV-C names ResNet-style blocks and gives no mechanics; this is the
+ * reading built here).  A basic block is conv1, conv2 and, when the shape changes, a 1x1 projection of the
+ * block input, listed as [projection,] conv1, conv2:
+ *   projection  role = FF_ROLE_PROJECTION: contraction only; no activity, goodness, loss or output of its own
+ *               (its rows of `loss` and `goodness` are 0).  relu and l2norm_out must be 0.
+ *   conv1       an ordinary layer; input_back = 1 when a projection precedes it (both read the block input).
+ *   conv2       skip = FF_SKIP_IDENTITY:   y = act(s*acc + s_x * x_q), x_q = int8 input of layer i-1, or
+ *               skip = FF_SKIP_PROJECTION: y = act(s*acc + s_p * acc of layer i-2).
+ *               y is the block output: the goodness, the loss and the local gradient 2*c*y of this layer are
+ *               taken on it, it is the input of the layers that follow, and the projection is updated with
+ *               the same int8 local gradient.  Goodness: with amax = max|y| over the pass,
+ *               G = fp32(sum floor((y/amax)^2 * 2^40) * 2^-40 * amax^2) (an integer sum: order-free).
+ *               C_out % 4 == 0, l2norm_out == 0. */
+enum { FF_ROLE_LAYER = 0, FF_ROLE_PROJECTION = 1 };
+enum { FF_SKIP_NONE = 0, FF_SKIP_IDENTITY = 1, FF_SKIP_PROJECTION = 2 };
 
 /* A stack of layers trained together by ff_train_step. [host] */
 typedef struct {
@@ -281,7 +301,8 @@ enum {
     FF_K_ABSMAX = 6,     /* absmax of the fp32 input                          */
     FF_K_SMALL = 7,      /* fills, goodness/loss, look-ahead                  */
     FF_K_IM2COL = 8,     /* patch matrices of convolution layers              */
-    FF_K_COUNT = 9
+    FF_K_RESIDUAL = 9,   /* block output and its goodness (residual layers)   */
+    FF_K_COUNT = 10
 };
 #define FF_TIMING_MAX_RECORDS 16384
 ff_status ff_timing_enable(int32_t class_mask);

@@ -28,7 +28,7 @@ class FFError(RuntimeError):
 
 class LayerDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("kind", "batch", "in_features", "out_features", "H", "W", "C_in", "C_out",
-                                         "ksize", "stride", "pad", "relu", "l2norm_out")]
+                                         "ksize", "stride", "pad", "relu", "l2norm_out", "input_back", "role", "skip")]
 
 
 class NetDesc(C.Structure):
@@ -118,7 +118,9 @@ def layer_desc(layer, batch: int) -> LayerDesc:
     """From a workloads.Layer (or any object with the same attributes)."""
     kind = 0 if layer.kind == "dense" else 1
     return LayerDesc(kind, batch, layer.in_features, layer.out_features, layer.H, layer.W, layer.C_in, layer.C_out,
-                     layer.ksize, layer.stride, layer.pad, layer.relu, layer.l2norm_out)
+                     layer.ksize, layer.stride, layer.pad, layer.relu, layer.l2norm_out,
+                     getattr(layer, "input_back", 0), {"ff": 0, "proj": 1}[getattr(layer, "role", "ff")],
+                     {"none": 0, "identity": 1, "projection": 2}[getattr(layer, "skip", "none")])
 
 
 def ff_pitch(cols: int) -> int:
@@ -230,7 +232,8 @@ def ff_train_step_at(net: Net, x_pos, x_neg, theta, lam, lr, seed, step_dev, adv
                                 ws.numel() * ws.element_size() if ws is not None else 0, _stream()), "ff_train_step_at")
 
 
-KERNEL_CLASSES = ("gemm_fwd", "gemm_dw", "quant_act", "quant_grad", "quant_w", "update", "absmax", "small", "im2col")
+KERNEL_CLASSES = ("gemm_fwd", "gemm_dw", "quant_act", "quant_grad", "quant_w", "update", "absmax", "small", "im2col",
+                  "residual")
 
 
 def ff_timing_enable(on, classes: Optional[Sequence[str]] = None) -> None:

@@ -19,6 +19,8 @@ struct Dims {
     ConvGeom g;                // conv only
     int n_chunks;              // weight-gradient accumulators per pass
     int64_t chunk_b;           // samples per accumulator
+    int src;                   // ff_train_step: index of the layer whose output is this layer's input (-1: the net input)
+    int role, skip;            // residual-block wiring (ff_layer_desc)
 };
 
 static ff_status layer_dims(const ff_layer_desc* L, Dims* d)
@@ -116,7 +118,8 @@ struct WsLayout {
     int64_t B;
     Dims d[MAX_LAYERS];
     // byte offsets
-    size_t off_slots;      // uint32: act_amax[k][2], g_amax[k][2], w_amax[k]
+    size_t off_slots;      // uint32: out_amax[k+1][2] (slot 0: the net input, slot j+1: output of layer j),
+                           // g_amax[k][2], w_amax[k]
     size_t off_gsum;       // uint64 [k][2][B]
     size_t off_vmax;       // int32  [k][2][B]
     size_t zero_bytes;     // the region [0, zero_bytes) is cleared at the start of a step
@@ -129,6 +132,7 @@ struct WsLayout {
     size_t off_aq[MAX_LAYERS], st_aq[MAX_LAYERS];    // quantised layer input [2][st]: dense layers share one scratch
     size_t off_aqt[MAX_LAYERS], st_aqt[MAX_LAYERS];  // dense only: transposed quantised input [2][st], retained
     size_t off_acc[MAX_LAYERS], st_acc[MAX_LAYERS];  // int32 accumulators [2][st] (bytes), retained
+    size_t off_y[MAX_LAYERS], st_y[MAX_LAYERS];      // residual layers: fp32 block output [2][st] (bytes), retained
     size_t total;
 };
 
@@ -146,18 +150,51 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
         if (net->layers[i].batch != net->batch) return FF_ERR_SHAPE;
         if (d.K > INT32_SAFE_LEN) return FF_ERR_OVERFLOW_BOUND;
         if (d.n_chunks > MAX_CHUNKS) return FF_ERR_UNSUPPORTED;
-        if (i > 0) {
-            const Dims& p = w->d[i - 1];
+        const ff_layer_desc& L = net->layers[i];
+        Dims& dd = w->d[i];
+        dd.role = L.role;
+        dd.skip = L.skip;
+        if (L.input_back < 0 || L.input_back > 1) return FF_ERR_UNSUPPORTED;
+        if (L.role != FF_ROLE_LAYER && L.role != FF_ROLE_PROJECTION) return FF_ERR_INVALID_ARG;
+        if (L.skip != FF_SKIP_NONE && L.skip != FF_SKIP_IDENTITY && L.skip != FF_SKIP_PROJECTION) return FF_ERR_INVALID_ARG;
+        dd.src = i - 1 - L.input_back;
+        if (dd.src < -1) return FF_ERR_SHAPE;
+        if (dd.src >= 0) {
+            const Dims& p = w->d[dd.src];
+            if (p.role == FF_ROLE_PROJECTION) return FF_ERR_SHAPE;   // a projection has no output of its own
             if (p.kind != d.kind) return FF_ERR_UNSUPPORTED;  // no dense <-> conv transitions in this build
             if (d.kind == FF_DENSE && d.K != p.N) return FF_ERR_SHAPE;
             if (d.kind == FF_CONV2D && (d.g.Cin != p.N || d.g.H != p.g.Ho || d.g.W != p.g.Wo)) return FF_ERR_SHAPE;
+        }
+        if (L.role == FF_ROLE_PROJECTION) {
+            // [projection, conv1 (reads the same input), conv2 (adds the projection)]
+            if (d.kind != FF_CONV2D || L.relu || L.l2norm_out || L.skip != FF_SKIP_NONE) return FF_ERR_INVALID_ARG;
+            if (i + 2 >= w->k || net->layers[i + 1].input_back != 1 || net->layers[i + 1].role != FF_ROLE_LAYER ||
+                net->layers[i + 2].skip != FF_SKIP_PROJECTION)
+                return FF_ERR_SHAPE;
+        }
+        if (L.skip != FF_SKIP_NONE) {
+            if (d.kind != FF_CONV2D || L.role != FF_ROLE_LAYER || L.l2norm_out || (d.N & 3) || L.input_back != 0)
+                return FF_ERR_UNSUPPORTED;
+            if (L.skip == FF_SKIP_IDENTITY) {
+                if (i < 1) return FF_ERR_SHAPE;
+                const Dims& c1 = w->d[i - 1];   // the block input is the input of conv1
+                if (c1.role != FF_ROLE_LAYER || c1.kind != FF_CONV2D || c1.g.Cin != d.N || c1.g.H != d.g.Ho ||
+                    c1.g.W != d.g.Wo)
+                    return FF_ERR_SHAPE;
+            } else {
+                if (i < 2) return FF_ERR_SHAPE;
+                const Dims& pr = w->d[i - 2];
+                if (pr.role != FF_ROLE_PROJECTION || pr.N != d.N || pr.g.Ho != d.g.Ho || pr.g.Wo != d.g.Wo)
+                    return FF_ERR_SHAPE;
+            }
         }
     }
     const size_t A = 256;
     size_t off = 0;
     const size_t k = (size_t)w->k, B = (size_t)w->B;
     w->off_slots = off;
-    off = align_up(off + sizeof(uint32_t) * (k * 5), A);
+    off = align_up(off + sizeof(uint32_t) * (k * 5 + 2), A);
     w->off_gsum = off;
     off = align_up(off + sizeof(uint64_t) * k * 2 * B, A);
     w->off_vmax = off;
@@ -212,6 +249,9 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
         w->st_acc[i] = align_up((size_t)(d.M * pitch32(d.N)) * sizeof(int32_t), A);
         w->off_acc[i] = off;
         off += 2 * w->st_acc[i];
+        w->st_y[i] = d.skip != FF_SKIP_NONE ? align_up((size_t)(d.M * d.N) * sizeof(float), A) : 0;
+        w->off_y[i] = off;
+        off += 2 * w->st_y[i];
     }
     w->total = off;
     return FF_OK;
@@ -708,8 +748,8 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
     char* base = (char*)ws;
     const int k = w.k;
     const int64_t B = w.B;
-    uint32_t* act_amax = (uint32_t*)(base + w.off_slots);  // [k][2]
-    uint32_t* g_amax = act_amax + 2 * k;                   // [k][2]
+    uint32_t* out_amax = (uint32_t*)(base + w.off_slots);  // [k+1][2]: slot 0 the net input, slot j+1 the output of layer j
+    uint32_t* g_amax = out_amax + 2 * (k + 1);             // [k][2]
     uint32_t* w_amax = g_amax + 2 * k;                     // [k]
     unsigned long long* gsum = (unsigned long long*)(base + w.off_gsum);
     int32_t* vmax = (int32_t*)(base + w.off_vmax);
@@ -721,7 +761,7 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
     HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)base, (int64_t)(w.zero_bytes / 4), 0u, s));
     const int64_t n_in = w.d[0].in_rows * w.d[0].in_cols;
     const int64_t st_x = ((intptr_t)x_neg - (intptr_t)x_pos) / (intptr_t)sizeof(float);
-    HIPCHK_T(FF_K_ABSMAX, launch_absmax(x_pos, st_x, 2, n_in, act_amax, s));
+    HIPCHK_T(FF_K_ABSMAX, launch_absmax(x_pos, st_x, 2, n_in, out_amax, s));
 
     // ---- forward pass through all layers, both data sets together (Algorithm 1) -----------------
     for (int i = 0; i < k; ++i) {
@@ -731,29 +771,36 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         QuantArgs a;
         memset(&a, 0, sizeof(a));
         int src;
-        if (i == 0) {
+        if (d.src < 0) {
             src = QSRC_F32;
             a.x = x_pos;
             a.st_x = st_x;
             a.rows_per_sample = 1;
+        } else if (w.d[d.src].skip != FF_SKIP_NONE) {
+            // the source is a residual layer: its block output is held as fp32
+            src = QSRC_F32;
+            a.x = (const float*)(base + w.off_y[d.src]);
+            a.st_x = (int64_t)(w.st_y[d.src] / sizeof(float));
+            a.rows_per_sample = 1;
         } else {
-            const Dims& dp = w.d[i - 1];
-            const ff_layer_desc& Lp = net->layers[i - 1];
+            const int j = d.src;
+            const Dims& dp = w.d[j];
+            const ff_layer_desc& Lp = net->layers[j];
             src = QSRC_HANDOFF;
-            a.acc = (const int32_t*)(base + w.off_acc[i - 1]);
-            a.st_acc = (int64_t)(w.st_acc[i - 1] / sizeof(int32_t));
+            a.acc = (const int32_t*)(base + w.off_acc[j]);
+            a.st_acc = (int64_t)(w.st_acc[j] / sizeof(int32_t));
             a.ldacc = pitch32(dp.N);
-            a.s_a = s_a + 2 * (i - 1);
+            a.s_a = s_a + 2 * j;
             a.st_s_a = 1;
-            a.s_w = state->s_w[i - 1];
+            a.s_w = state->s_w[j];
             a.st_s_w = 0;
-            a.per_sample = goodness + (int64_t)(i - 1) * 2 * B;
+            a.per_sample = goodness + (int64_t)j * 2 * B;
             a.st_per_sample = B;
             a.rows_per_sample = (int32_t)dp.rps;
             a.relu = Lp.relu ? 1 : 0;
             a.l2norm = Lp.l2norm_out ? 1 : 0;
         }
-        a.amax_bits = act_amax + 2 * i;
+        a.amax_bits = out_amax + 2 * (d.src + 1);
         a.st_amax = 1;
         a.round_mode = FF_ROUND_STOCHASTIC;
         a.key = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 0, FF_KIND_ACT));
@@ -777,11 +824,70 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         a.nb = 2;
         HIPCHK_T(FF_K_QUANT_ACT, launch_quantize(src, a, s));
 
+        const bool plain = d.role == FF_ROLE_LAYER && d.skip == FF_SKIP_NONE;   // goodness straight from the accumulators
         const ff_status fs = run_forward(d, L.relu ? 1 : 0, (const int8_t*)(base + w.off_aq[i]), (int64_t)w.st_aq[i],
                                          state->w_q[i], (int32_t*)(base + w.off_acc[i]),
-                                         (int64_t)(w.st_acc[i] / sizeof(int32_t)), gsum + (int64_t)i * 2 * B,
-                                         vmax + (int64_t)i * 2 * B, B, (int8_t*)(base + w.off_col), (int64_t)w.st_col, 2, s);
+                                         (int64_t)(w.st_acc[i] / sizeof(int32_t)),
+                                         plain ? gsum + (int64_t)i * 2 * B : nullptr, vmax + (int64_t)i * 2 * B, B,
+                                         (int8_t*)(base + w.off_col), (int64_t)w.st_col, 2, s);
         if (fs != FF_OK) return fs;
+        if (d.role == FF_ROLE_PROJECTION) {
+            // no activity of its own: zero coefficients (nothing enters the look-ahead sums), zero loss / goodness rows
+            HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(c + (int64_t)i * 2 * B), 2 * B, 0u, s));
+            HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(goodness + (int64_t)i * 2 * B), 2 * B, 0u, s));
+            HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(loss + 2 * i), 2, 0u, s));
+            continue;
+        }
+        if (!plain) {
+            ResidualArgs ra;
+            memset(&ra, 0, sizeof(ra));
+            ra.acc = (const int32_t*)(base + w.off_acc[i]);
+            ra.ldacc = pitch32(d.N);
+            ra.st_acc = (int64_t)(w.st_acc[i] / sizeof(int32_t));
+            ra.s_a = s_a + 2 * i;
+            ra.st_s_a = 1;
+            ra.s_w = state->s_w[i];
+            ra.skip = d.skip;
+            if (d.skip == FF_SKIP_IDENTITY) {
+                ra.xq = (const int8_t*)(base + w.off_aq[i - 1]);
+                ra.ldx = pitch8(w.d[i - 1].in_cols);
+                ra.st_xq = (int64_t)w.st_aq[i - 1];
+                ra.s_x = s_a + 2 * (i - 1);
+                ra.st_s_x = 1;
+            } else {
+                ra.accp = (const int32_t*)(base + w.off_acc[i - 2]);
+                ra.ldaccp = pitch32(w.d[i - 2].N);
+                ra.st_accp = (int64_t)(w.st_acc[i - 2] / sizeof(int32_t));
+                ra.s_ap = s_a + 2 * (i - 2);
+                ra.st_s_ap = 1;
+                ra.s_wp = state->s_w[i - 2];
+            }
+            ra.relu = L.relu ? 1 : 0;
+            ra.M = d.M;
+            ra.N = d.N;
+            ra.rows_per_sample = (int32_t)d.rps;
+            ra.y = (float*)(base + w.off_y[i]);
+            ra.st_y = (int64_t)(w.st_y[i] / sizeof(float));
+            ra.ymax_bits = (uint32_t*)(vmax + (int64_t)i * 2 * B);
+            ra.st_b = B;
+            ra.amax_bits = out_amax + 2 * (i + 1);
+            ra.st_amax = 1;
+            ra.nb = 2;
+            HIPCHK_T(FF_K_RESIDUAL, launch_residual_act(ra, s));
+            GoodnessFxArgs fa;
+            memset(&fa, 0, sizeof(fa));
+            fa.y = ra.y;
+            fa.st_y = ra.st_y;
+            fa.M = d.M;
+            fa.N = d.N;
+            fa.rows_per_sample = (int32_t)d.rps;
+            fa.amax_bits = ra.amax_bits;
+            fa.st_amax = 1;
+            fa.gsum = gsum + (int64_t)i * 2 * B;
+            fa.st_b = B;
+            fa.nb = 2;
+            HIPCHK_T(FF_K_RESIDUAL, launch_goodness_fx(fa, s));
+        }
 
         GoodnessArgs ga;
         memset(&ga, 0, sizeof(ga));
@@ -797,7 +903,9 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         ga.goodness = goodness + (int64_t)i * 2 * B;
         ga.coeff = c + (int64_t)i * 2 * B;
         ga.loss_mean = loss + 2 * i;
-        ga.next_amax_bits = (i + 1 < k) ? act_amax + 2 * (i + 1) : nullptr;
+        // the absmax of this layer's output, i.e. of the input of whichever layers read it
+        ga.next_amax_bits = plain ? out_amax + 2 * (i + 1) : nullptr;
+        ga.fx_amax_bits = plain ? nullptr : out_amax + 2 * (i + 1);
         ga.nb = 2;
         ga.st_b = B;
         ga.st_scalar = 1;
@@ -820,23 +928,83 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         la.s_a = s_a;
         la.s_w = state->s_w;
         la.g_amax_bits = g_amax;
+        for (int i = 0; i < k; ++i)
+            if (w.d[i].skip != FF_SKIP_NONE) la.fx_mask |= 1u << i;
         HIPCHK_T(FF_K_SMALL, launch_lookahead(la, s));
     }
 
     // ---- per layer: int8 local gradient, int8 weight gradient, update (Algorithm 1, inner loop) ----
-    for (int i = 0; i < k; ++i) {
-        if (net->train_layer && !net->train_layer[i]) continue;   // frozen layer: forward only
-        const Dims& d = w.d[i];
-        const ff_layer_desc& L = net->layers[i];
+    // weights of layer `t` from the transposed int8 gradient in the scratch (quantised for layer `gl`): weight-gradient
+    // contraction per pass and chunk, combined update, requantisation
+    auto wgrad_update = [&](int t, int gl) -> ff_status {
+        const Dims& d = w.d[t];
         const bool dense = d.kind == FF_DENSE;
+        const int64_t dw_elems = (int64_t)(w.dw_bytes / sizeof(int32_t));
+        const ff_status ws_ = run_wgrad(d, (const int8_t*)(base + w.off_gy), (int64_t)w.st_gy,
+                                        dense ? (const int8_t*)(base + w.off_aqt[t]) : (const int8_t*)(base + w.off_aq[t]),
+                                        dense ? (int64_t)w.st_aqt[t] : (int64_t)w.st_aq[t], (int8_t*)(base + w.off_col),
+                                        (int64_t)w.st_col, (int32_t*)(base + w.off_part),
+                                        (int64_t)(w.st_part / sizeof(int32_t)), (int32_t*)(base + w.off_dw),
+                                        (int64_t)(w.st_dw / sizeof(int32_t)), dw_elems, 2, s);
+        if (ws_ != FF_OK) return ws_;
+
+        UpdateArgs u;
+        memset(&u, 0, sizeof(u));
+        u.w = state->w_master[t];
+        u.N = d.N;
+        u.K = d.K;
+        u.lddw = pitch32(d.K);
+        u.n_terms = 2 * d.n_chunks;
+        for (int p = 0; p < 2; ++p)
+            for (int cc = 0; cc < d.n_chunks; ++cc) {
+                const int tt = p * d.n_chunks + cc;
+                u.dw[tt] = (const int32_t*)(base + w.off_dw + p * w.st_dw + cc * w.dw_bytes);
+                u.s_g[tt] = s_g + 2 * gl + p;
+                u.s_a[tt] = s_a + 2 * t + p;
+            }
+        u.lr = lr;
+        u.total_samples = (int32_t)(2 * B);
+        u.w_amax_bits = w_amax + t;
+        HIPCHK_T(FF_K_UPDATE, launch_update(u, s));
+
+        QuantArgs qa;
+        memset(&qa, 0, sizeof(qa));
+        qa.x = state->w_master[t];
+        qa.amax_bits = w_amax + t;
+        qa.round_mode = FF_ROUND_NEAREST_EVEN;
+        qa.rows = d.N;
+        qa.cols = d.K;
+        qa.q = state->w_q[t];
+        qa.ldq = pitch8(d.K);
+        qa.scale = state->s_w[t];
+        qa.nb = 1;
+        qa.rows_per_sample = 1;
+        HIPCHK_T(FF_K_QUANT_W, launch_quantize(QSRC_F32, qa, s));
+        return FF_OK;
+    };
+    auto trained = [&](int t) { return !net->train_layer || net->train_layer[t]; };
+
+    for (int i = 0; i < k; ++i) {
+        const Dims& d = w.d[i];
+        if (d.role == FF_ROLE_PROJECTION) continue;   // updated with the gradient of the block output, layer i + 2
+        const bool with_proj = d.skip == FF_SKIP_PROJECTION && trained(i - 2);
+        if (!trained(i) && !with_proj) continue;      // frozen layer: forward only
+        const ff_layer_desc& L = net->layers[i];
         QuantArgs a;
         memset(&a, 0, sizeof(a));
-        a.acc = (const int32_t*)(base + w.off_acc[i]);
-        a.st_acc = (int64_t)(w.st_acc[i] / sizeof(int32_t));
-        a.ldacc = pitch32(d.N);
-        a.s_a = s_a + 2 * i;
-        a.st_s_a = 1;
-        a.s_w = state->s_w[i];
+        int src = QSRC_GRAD;
+        if (d.skip != FF_SKIP_NONE) {
+            src = QSRC_F32_GRAD;
+            a.x = (const float*)(base + w.off_y[i]);
+            a.st_x = (int64_t)(w.st_y[i] / sizeof(float));
+        } else {
+            a.acc = (const int32_t*)(base + w.off_acc[i]);
+            a.st_acc = (int64_t)(w.st_acc[i] / sizeof(int32_t));
+            a.ldacc = pitch32(d.N);
+            a.s_a = s_a + 2 * i;
+            a.st_s_a = 1;
+            a.s_w = state->s_w[i];
+        }
         a.per_sample = ct + (int64_t)i * 2 * B;
         a.st_per_sample = B;
         a.rows_per_sample = (int32_t)d.rps;
@@ -858,49 +1026,16 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         a.scale = s_g + 2 * i;
         a.st_scale = 1;
         a.nb = 2;
-        HIPCHK_T(FF_K_QUANT_GRAD, launch_quantize(QSRC_GRAD, a, s));
+        HIPCHK_T(FF_K_QUANT_GRAD, launch_quantize(src, a, s));
 
-        const int64_t dw_elems = (int64_t)(w.dw_bytes / sizeof(int32_t));
-        const ff_status ws_ = run_wgrad(d, (const int8_t*)(base + w.off_gy), (int64_t)w.st_gy,
-                                        dense ? (const int8_t*)(base + w.off_aqt[i]) : (const int8_t*)(base + w.off_aq[i]),
-                                        dense ? (int64_t)w.st_aqt[i] : (int64_t)w.st_aq[i], (int8_t*)(base + w.off_col),
-                                        (int64_t)w.st_col, (int32_t*)(base + w.off_part),
-                                        (int64_t)(w.st_part / sizeof(int32_t)), (int32_t*)(base + w.off_dw),
-                                        (int64_t)(w.st_dw / sizeof(int32_t)), dw_elems, 2, s);
-        if (ws_ != FF_OK) return ws_;
-
-        UpdateArgs u;
-        memset(&u, 0, sizeof(u));
-        u.w = state->w_master[i];
-        u.N = d.N;
-        u.K = d.K;
-        u.lddw = pitch32(d.K);
-        u.n_terms = 2 * d.n_chunks;
-        for (int p = 0; p < 2; ++p)
-            for (int cc = 0; cc < d.n_chunks; ++cc) {
-                const int t = p * d.n_chunks + cc;
-                u.dw[t] = (const int32_t*)(base + w.off_dw + p * w.st_dw + cc * w.dw_bytes);
-                u.s_g[t] = s_g + 2 * i + p;
-                u.s_a[t] = s_a + 2 * i + p;
-            }
-        u.lr = lr;
-        u.total_samples = (int32_t)(2 * B);
-        u.w_amax_bits = w_amax + i;
-        HIPCHK_T(FF_K_UPDATE, launch_update(u, s));
-
-        QuantArgs qa;
-        memset(&qa, 0, sizeof(qa));
-        qa.x = state->w_master[i];
-        qa.amax_bits = w_amax + i;
-        qa.round_mode = FF_ROUND_NEAREST_EVEN;
-        qa.rows = d.N;
-        qa.cols = d.K;
-        qa.q = state->w_q[i];
-        qa.ldq = pitch8(d.K);
-        qa.scale = state->s_w[i];
-        qa.nb = 1;
-        qa.rows_per_sample = 1;
-        HIPCHK_T(FF_K_QUANT_W, launch_quantize(QSRC_F32, qa, s));
+        if (trained(i)) {
+            const ff_status us = wgrad_update(i, i);
+            if (us != FF_OK) return us;
+        }
+        if (with_proj) {
+            const ff_status us = wgrad_update(i - 2, i);
+            if (us != FF_OK) return us;
+        }
     }
     if (step_dev && advance) HIPCHK_T(FF_K_SMALL, launch_advance_u64(step_dev, s));
     return FF_OK;

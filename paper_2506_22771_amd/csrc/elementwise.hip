@@ -192,8 +192,9 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
         a.scale[z * a.st_scale] = live ? amax / 127.0f : 1.0f;
 
+    constexpr bool F32SRC = SRC == QSRC_F32 || SRC == QSRC_F32_GRAD;   // the source is an fp32 tensor
     float s_y = 1.0f;
-    if (SRC != QSRC_F32) s_y = a.s_a[z * a.st_s_a] * a.s_w[z * a.st_s_w];
+    if (!F32SRC) s_y = a.s_a[z * a.st_s_a] * a.s_w[z * a.st_s_w];
 
     const int64_t r0 = (int64_t)blockIdx.y * QT_ROWS;
     const int64_t c0 = (int64_t)blockIdx.x * QT_COLS;
@@ -207,8 +208,8 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
     // ---- loads: 2 blocks x 4 rows x 16 bytes, raw bits.  Row (u, j) of this thread is rowb + 64*u + j:
     // all per-row offsets are (compile-time constant) x (uniform pitch), i.e. scalar-unit work.
     const int64_t rowb = r0 + 4 * (t >> 4);
-    const float* __restrict__ px0 = SRC == QSRC_F32 ? x + rowb * a.cols + col : nullptr;
-    const int32_t* __restrict__ pa0 = SRC != QSRC_F32 ? acc + rowb * a.ldacc + col : nullptr;
+    const float* __restrict__ px0 = F32SRC ? x + rowb * a.cols + col : nullptr;
+    const int32_t* __restrict__ pa0 = !F32SRC ? acc + rowb * a.ldacc + col : nullptr;
     int8_t* __restrict__ pq0 = q ? q + rowb * a.ldq + col : nullptr;
     uint32_t raw[2][4][4];
     float rowf[2][4];   // per-row factor (GRAD: 2*coeff; HANDOFF+l2norm: sqrt(goodness))
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
             const int64_t row = rowb + dr;
             const bool in = row < a.rows && col_in;
             uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
-            if (SRC == QSRC_F32) {
+            if (F32SRC) {
                 const float* px = px0 + (int64_t)dr * a.cols;
                 if (VEC) {
                     if (in) {
@@ -245,11 +246,11 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
             }
             raw[u][j][0] = w0; raw[u][j][1] = w1; raw[u][j][2] = w2; raw[u][j][3] = w3;
             float rf = 1.0f;
-            if (SRC == QSRC_GRAD || (SRC == QSRC_HANDOFF && a.l2norm)) {
+            if (SRC == QSRC_GRAD || SRC == QSRC_F32_GRAD || (SRC == QSRC_HANDOFF && a.l2norm)) {
                 rf = 0.0f;
                 if (in) {
                     const int64_t smp = a.rows_per_sample == 1 ? row : row / a.rows_per_sample;
-                    rf = SRC == QSRC_GRAD ? 2.0f * per_sample[smp] : sqrtf(per_sample[smp]);
+                    rf = SRC == QSRC_HANDOFF ? sqrtf(per_sample[smp]) : 2.0f * per_sample[smp];
                 }
             }
             rowf[u][j] = rf;
@@ -281,8 +282,9 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
             uint32_t pack = 0;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                float v = SRC == QSRC_F32 ? __uint_as_float(raw[u][j][c]) : (float)(int)raw[u][j][c];
-                if (SRC != QSRC_F32) {
+                float v = F32SRC ? __uint_as_float(raw[u][j][c]) : (float)(int)raw[u][j][c];
+                if (SRC == QSRC_F32_GRAD) v = rowf[u][j] * v;
+                if (!F32SRC) {
                     v = v * s_y;
                     if (a.relu) v = fmaxf(v, 0.0f);
                     if (SRC == QSRC_GRAD) v = rowf[u][j] * v;
@@ -335,15 +337,15 @@ static void launch_quantize_t(const QuantArgs& a, dim3 grid, dim3 block, hipStre
 {
     const bool big = (uint64_t)a.rows * (uint64_t)a.cols >= (uint64_t(1) << 32);
     bool vec = true;
-    if (SRC == QSRC_F32) {
+    if (SRC == QSRC_F32 || SRC == QSRC_F32_GRAD) {
         vec = (a.cols & 3) == 0 && (((uintptr_t)a.x) & 15) == 0 && ((a.st_x & 3) == 0 || a.nb == 1);
     }
     if (big) {
         if (vec) hipLaunchKernelGGL((k_quantize<SRC, STOCH, true, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_quantize<SRC, STOCH, SRC != QSRC_F32, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_quantize<SRC, STOCH, SRC != QSRC_F32 && SRC != QSRC_F32_GRAD, true>), grid, block, 0, s, a);
     } else {
         if (vec) hipLaunchKernelGGL((k_quantize<SRC, STOCH, true, false>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_quantize<SRC, STOCH, SRC != QSRC_F32, false>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_quantize<SRC, STOCH, SRC != QSRC_F32 && SRC != QSRC_F32_GRAD, false>), grid, block, 0, s, a);
     }
 }
 
@@ -362,6 +364,10 @@ hipError_t launch_quantize(int src, const QuantArgs& a, hipStream_t s)
         case QSRC_HANDOFF:
             if (st) launch_quantize_t<QSRC_HANDOFF, true>(a, grid, block, s);
             else launch_quantize_t<QSRC_HANDOFF, false>(a, grid, block, s);
+            break;
+        case QSRC_F32_GRAD:
+            if (st) launch_quantize_t<QSRC_F32_GRAD, true>(a, grid, block, s);
+            else launch_quantize_t<QSRC_F32_GRAD, false>(a, grid, block, s);
             break;
         default:
             if (st) launch_quantize_t<QSRC_GRAD, true>(a, grid, block, s);
@@ -403,9 +409,11 @@ __global__ __launch_bounds__(GL_THREADS) void k_goodness_loss(GoodnessArgs a)
     float* goodness = a.goodness + z * a.st_b;
     float* coeff = a.coeff + z * a.st_b;
     const int sign = z ? -a.pass_sign : a.pass_sign;
-    const float s_y = a.s_a[z * a.st_scalar] * a.s_w[0];
-    const double s_yd = (double)s_y;
-    const double pow2r = (double)(1ull << a.rshift);
+    const bool fx = a.fx_amax_bits != nullptr;
+    const float s_y = fx ? 1.0f : a.s_a[z * a.st_scalar] * a.s_w[0];
+    const float fx_amax = fx ? __uint_as_float(a.fx_amax_bits[z * a.st_scalar]) : 0.0f;
+    const double s_yd = fx ? (double)fx_amax : (double)s_y;
+    const double pow2r = fx ? 0x1p-40 : (double)(1ull << a.rshift);
 
     double lsum = 0.0;
     uint32_t amax_bits = 0;
@@ -414,7 +422,7 @@ __global__ __launch_bounds__(GL_THREADS) void k_goodness_loss(GoodnessArgs a)
         g = g * pow2r;
         g = g * s_yd;
         g = g * s_yd;
-        const float G = (float)g;
+        const float G = (fx && fx_amax < 0x1p-100f) ? 0.0f : (float)g;
         goodness[b] = G;
         const float x = G - a.theta;
         const float e = exp_nonpos(-fabsf(x));
@@ -466,6 +474,126 @@ hipError_t launch_goodness_loss(const GoodnessArgs& a, hipStream_t s)
 }
 
 // ------------------------------------------------------------------------------------------------
+// residual layers: block output y = act(fp32(acc) * s_y + skip), one rounding per operation, stored as
+// fp32; max|y| per sample and over the pass (bit patterns, atomic max).  A thread owns four columns.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned lo = (unsigned)__shfl_xor((int)(unsigned)v, d), hi = (unsigned)__shfl_xor((int)(unsigned)(v >> 32), d);
+        v += ((unsigned long long)hi << 32) | lo;
+    }
+    return v;
+}
+
+// true when every live lane of the wavefront has the same sample index (dead lanes pass -1 and never match)
+__device__ __forceinline__ bool wave_uniform(int64_t smp, bool live, int64_t* first)
+{
+    const int lo = __builtin_amdgcn_readfirstlane((int)(uint32_t)smp), hi = __builtin_amdgcn_readfirstlane((int)(uint32_t)(smp >> 32));
+    *first = ((int64_t)(uint32_t)hi << 32) | (uint32_t)lo;
+    return __all(live && smp == *first);
+}
+
+__global__ __launch_bounds__(256) void k_residual_act(ResidualArgs a)
+{
+    const int z = blockIdx.y;
+    const int64_t n4 = a.N >> 2;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool live = idx < a.M * n4;
+    const int64_t row = live ? idx / n4 : 0;
+    const int64_t col = live ? (idx - row * n4) * 4 : 0;
+    const float s_y = a.s_a[z * a.st_s_a] * a.s_w[0];
+    float yv[4] = {0.f, 0.f, 0.f, 0.f};
+    if (live) {
+        const int4 c = *(const int4*)(a.acc + z * a.st_acc + row * a.ldacc + col);
+        float u[4];
+        if (a.skip == FF_SKIP_IDENTITY) {
+            const float s_x = a.s_x[z * a.st_s_x];
+            const uint32_t xw = *(const uint32_t*)(a.xq + z * a.st_xq + row * a.ldx + col);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) u[e] = (float)(int)(int8_t)(xw >> (8 * e)) * s_x;
+        } else {
+            const float s_p = a.s_ap[z * a.st_s_ap] * a.s_wp[0];
+            const int4 cp = *(const int4*)(a.accp + z * a.st_accp + row * a.ldaccp + col);
+            u[0] = (float)cp.x * s_p; u[1] = (float)cp.y * s_p; u[2] = (float)cp.z * s_p; u[3] = (float)cp.w * s_p;
+        }
+        const int cc[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float t = (float)cc[e] * s_y;
+            float v = t + u[e];
+            if (a.relu) v = fmaxf(v, 0.0f);
+            yv[e] = v;
+        }
+        *(float4*)(a.y + z * a.st_y + row * a.N + col) = make_float4(yv[0], yv[1], yv[2], yv[3]);
+    }
+    uint32_t m = max(max(__float_as_uint(fabsf(yv[0])), __float_as_uint(fabsf(yv[1]))),
+                     max(__float_as_uint(fabsf(yv[2])), __float_as_uint(fabsf(yv[3]))));
+    const int64_t smp = live ? row / a.rows_per_sample : -1;
+    uint32_t* ymax = a.ymax_bits + z * a.st_b;
+    int64_t first;
+    const uint32_t wm = wave_max_u32(m);
+    if (wave_uniform(smp, live, &first)) {
+        if ((threadIdx.x & 63) == 0 && wm > __hip_atomic_load(ymax + first, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            atomicMax(ymax + first, wm);
+    } else if (live && m > __hip_atomic_load(ymax + smp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+        atomicMax(ymax + smp, m);
+    }
+    uint32_t* slot = a.amax_bits + z * a.st_amax;
+    if ((threadIdx.x & 63) == 0 && wm > __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(slot, wm);
+}
+
+hipError_t launch_residual_act(const ResidualArgs& a, hipStream_t s)
+{
+    if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    const int64_t n = a.M * (a.N >> 2);
+    hipLaunchKernelGGL(k_residual_act, dim3((unsigned)((n + 255) / 256), (unsigned)a.nb), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// Fixed-point goodness sums of an fp32 activity tensor: per element floor(r * r * 2^40), r = y * (1 / amax) in
+// fp32, the product in fp64 (exact); unsigned 64-bit integer sums per sample (order-free).
+__global__ __launch_bounds__(256) void k_goodness_fx(GoodnessFxArgs a)
+{
+    const int z = blockIdx.y;
+    const int64_t n4 = a.N >> 2;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool live = idx < a.M * n4;
+    const float amax = __uint_as_float(a.amax_bits[z * a.st_amax]);
+    const float inv = amax >= 0x1p-100f ? 1.0f / amax : 0.0f;
+    unsigned long long q = 0;
+    int64_t row = 0;
+    if (live) {
+        row = idx / n4;
+        const float4 v = *(const float4*)(a.y + z * a.st_y + idx * 4);
+        const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float r = vv[e] * inv;
+            q += (unsigned long long)((double)r * (double)r * 0x1p40);
+        }
+    }
+    const int64_t smp = live ? row / a.rows_per_sample : -1;
+    unsigned long long* gs = a.gsum + z * a.st_b;
+    int64_t first;
+    if (wave_uniform(smp, live, &first)) {
+        const unsigned long long t = wave_sum_u64(q);
+        if ((threadIdx.x & 63) == 0 && t) atomicAdd(gs + first, t);
+    } else if (live && q) {
+        atomicAdd(gs + smp, q);
+    }
+}
+
+hipError_t launch_goodness_fx(const GoodnessFxArgs& a, hipStream_t s)
+{
+    if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    const int64_t n = a.M * (a.N >> 2);
+    hipLaunchKernelGGL(k_goodness_fx, dim3((unsigned)((n + 255) / 256), (unsigned)a.nb), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // look-ahead (Eq. (3)/(4)): per sample, walk the layers from the last to the first
 // ------------------------------------------------------------------------------------------------
 struct LookaheadKArgs {
@@ -489,8 +617,13 @@ __global__ __launch_bounds__(256) void k_lookahead(LookaheadKArgs ka)
         if (a.vmax) {
             uint32_t bits = 0;
             if (live) {
-                const float s_y = a.s_a[i * a.np + p] * ka.s_w[i][0];
-                const float ymax = (float)a.vmax[off] * s_y;
+                float ymax;
+                if ((a.fx_mask >> i) & 1u) {
+                    ymax = __uint_as_float((uint32_t)a.vmax[off]);
+                } else {
+                    const float s_y = a.s_a[i * a.np + p] * ka.s_w[i][0];
+                    ymax = (float)a.vmax[off] * s_y;
+                }
                 bits = __float_as_uint(fabsf(2.0f * ct) * ymax);
             }
             bits = wave_max_u32(bits);

@@ -42,7 +42,8 @@ __host__ __device__ inline uint64_t stream_tag_of(uint64_t step, uint32_t layer,
 }
 
 // ---- quantise kernels (elementwise.hip) -----------------------------------------------------
-enum QSource { QSRC_F32 = 0, QSRC_HANDOFF = 1, QSRC_GRAD = 2 };
+// QSRC_F32_GRAD: fp32 activities times the per-sample factor 2*coeff_total (local gradient of a residual layer)
+enum QSource { QSRC_F32 = 0, QSRC_HANDOFF = 1, QSRC_GRAD = 2, QSRC_F32_GRAD = 3 };
 
 // One quantisation problem; `nb` problems (1 or 2) are launched together with the strides below.
 struct QuantArgs {
@@ -52,7 +53,7 @@ struct QuantArgs {
     int64_t ldacc;
     const float* s_a;        // device scalars (HANDOFF / GRAD)
     const float* s_w;
-    const float* per_sample; // HANDOFF with l2norm: goodness[B]; GRAD: coeff_total[B]
+    const float* per_sample; // HANDOFF with l2norm: goodness[B]; GRAD, F32_GRAD: coeff_total[B]
     int32_t rows_per_sample;
     int32_t relu, l2norm;
     // quantiser
@@ -99,6 +100,9 @@ struct GoodnessArgs {
     float* coeff;
     float* loss_mean;
     uint32_t* next_amax_bits;  // may be null
+    // non-null: gsum holds the fixed-point sums of a residual layer, G = fp32(gsum * 2^-40 * amax^2) with amax
+    // from this slot (stride st_scalar); s_a, s_w and vmax are then unused
+    const uint32_t* fx_amax_bits;
     int32_t nb;
     int64_t st_b;  // stride between problems for the [B] arrays
     int32_t st_scalar;  // stride for s_a / loss_mean / next_amax (s_w is shared)
@@ -118,8 +122,52 @@ struct LookaheadArgs {
     const float* s_a;          // [k][np]
     const float* const* s_w;   // device array of k pointers to the layers' weight scales (may be null if vmax null)
     uint32_t* g_amax_bits;     // [k][np], zeroed
+    uint32_t fx_mask;          // bit i: layer i's vmax entries are the fp32 bit patterns of max|y| (residual layer)
 };
 hipError_t launch_lookahead(const LookaheadArgs& a, hipStream_t s);
+
+// ---- residual layers: block output y = act(s*acc + skip) as fp32, and its order-free goodness sums ------------
+struct ResidualArgs {
+    const int32_t* acc;  // [M, ldacc]
+    int64_t ldacc, st_acc;
+    const float* s_a;    // [z * st_s_a]
+    const float* s_w;
+    int32_t st_s_a;
+    int32_t skip;        // FF_SKIP_IDENTITY / FF_SKIP_PROJECTION
+    const int8_t* xq;    // identity: int8 [M, ldx] with scale s_x[z * st_s_x]
+    int64_t ldx, st_xq;
+    const float* s_x;
+    int32_t st_s_x;
+    const int32_t* accp; // projection: int32 [M, ldaccp] with scale s_ap[z * st_s_ap] * s_wp[0]
+    int64_t ldaccp, st_accp;
+    const float* s_ap;
+    int32_t st_s_ap;
+    const float* s_wp;
+    int32_t relu;
+    int64_t M, N;        // N % 4 == 0
+    int32_t rows_per_sample;
+    float* y;            // [M, N] contiguous
+    int64_t st_y;
+    uint32_t* ymax_bits; // [B] per pass (stride st_b), zeroed: bit pattern of max|y| per sample
+    int64_t st_b;
+    uint32_t* amax_bits; // slot per pass (stride st_amax), zeroed: bit pattern of max|y| over the pass
+    int32_t st_amax;
+    int32_t nb;
+};
+hipError_t launch_residual_act(const ResidualArgs& a, hipStream_t s);
+
+struct GoodnessFxArgs {
+    const float* y;      // [M, N] contiguous
+    int64_t st_y;
+    int64_t M, N;
+    int32_t rows_per_sample;
+    const uint32_t* amax_bits;
+    int32_t st_amax;
+    unsigned long long* gsum;  // [B] per pass (stride st_b), zeroed
+    int64_t st_b;
+    int32_t nb;
+};
+hipError_t launch_goodness_fx(const GoodnessFxArgs& a, hipStream_t s);
 
 // absmax of the local gradient for one layer / pass: max_b |2 c[b]| * (float(vmax[b]) * s_y) -> slot bits.
 hipError_t launch_grad_amax(const float* coeff_total, const int32_t* vmax, const float* s_a,

@@ -342,7 +342,7 @@ def _run_steps(ff, wl, n_steps, lam=None):
 
 
 @pytest.mark.parametrize("name,steps", [("tiny", 3), ("tiny_l2", 3), ("cfg1", 3), ("cfg2", 1), ("tiny_conv", 3),
-                                        ("tiny_conv16", 3), ("tiny_conv_s2", 3)])
+                                        ("tiny_conv16", 3), ("tiny_conv_s2", 3), ("tiny_res", 3)])
 def test_train_step(ff, name, steps):
     _run_steps(ff, workload(name), steps)
 
@@ -361,6 +361,14 @@ def test_train_step_cfg4_plain_full_size(ff):
     """The seventeen 3x3 convolutions of a ResNet-18-shaped stack (stride-2 layers, 8x8 and 4x4 maps, up to 4608
     reduction bytes, look-ahead over 17 layers) at 256+256 images, as a plain sequence without the residual adds."""
     _run_steps(ff, workload("cfg4_plain"), 1)
+
+
+@pytest.mark.slow
+@pytest.mark.timeout(1500)
+def test_train_step_cfg4_full_size(ff):
+    """The ResNet-18-shaped stack with its residual additions and the three 1x1 projections (20 convolutions,
+    11.16 M weights, 256+256 images) at its full size."""
+    _run_steps(ff, workload("cfg4"), 1)
 
 
 @pytest.mark.slow

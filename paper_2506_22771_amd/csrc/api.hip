@@ -870,8 +870,6 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
             ra.st_y = (int64_t)(w.st_y[i] / sizeof(float));
             ra.ymax_bits = (uint32_t*)(vmax + (int64_t)i * 2 * B);
             ra.st_b = B;
-            ra.amax_bits = out_amax + 2 * (i + 1);
-            ra.st_amax = 1;
             ra.nb = 2;
             HIPCHK_T(FF_K_RESIDUAL, launch_residual_act(ra, s));
             GoodnessFxArgs fa;
@@ -881,7 +879,8 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
             fa.M = d.M;
             fa.N = d.N;
             fa.rows_per_sample = (int32_t)d.rps;
-            fa.amax_bits = ra.amax_bits;
+            fa.ymax_bits = ra.ymax_bits;
+            fa.amax_bits = out_amax + 2 * (i + 1);
             fa.st_amax = 1;
             fa.gsum = gsum + (int64_t)i * 2 * B;
             fa.st_b = B;

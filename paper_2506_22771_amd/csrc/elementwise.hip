@@ -487,109 +487,119 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
     return v;
 }
 
-// true when every live lane of the wavefront has the same sample index (dead lanes pass -1 and never match)
-__device__ __forceinline__ bool wave_uniform(int64_t smp, bool live, int64_t* first)
+// Work split of the two residual kernels: blockIdx.y = sample, blockIdx.x = a contiguous share of the sample's
+// terms (RES_VPT four-element vectors per thread), blockIdx.z = pass.  A workgroup therefore reduces for ONE
+// sample and issues one atomic.
+constexpr int RES_VPT = 4;
+
+template <typename T, typename F>
+__device__ __forceinline__ T block_reduce_256(T v, F op, T* red)
 {
-    const int lo = __builtin_amdgcn_readfirstlane((int)(uint32_t)smp), hi = __builtin_amdgcn_readfirstlane((int)(uint32_t)(smp >> 32));
-    *first = ((int64_t)(uint32_t)hi << 32) | (uint32_t)lo;
-    return __all(live && smp == *first);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return op(op(red[0], red[1]), op(red[2], red[3]));
 }
 
 __global__ __launch_bounds__(256) void k_residual_act(ResidualArgs a)
 {
-    const int z = blockIdx.y;
-    const int64_t n4 = a.N >> 2;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const bool live = idx < a.M * n4;
-    const int64_t row = live ? idx / n4 : 0;
-    const int64_t col = live ? (idx - row * n4) * 4 : 0;
+    const int z = blockIdx.z;
+    const int64_t smp = blockIdx.y;
+    const int N = (int)a.N;
+    const int tv = a.rows_per_sample * (N >> 2);   // vectors per sample
     const float s_y = a.s_a[z * a.st_s_a] * a.s_w[0];
-    float yv[4] = {0.f, 0.f, 0.f, 0.f};
-    if (live) {
+    const float s_u = a.skip == FF_SKIP_IDENTITY ? a.s_x[z * a.st_s_x] : a.s_ap[z * a.st_s_ap] * a.s_wp[0];
+    const int64_t row0 = smp * a.rows_per_sample;
+    uint32_t m = 0;
+#pragma unroll
+    for (int it = 0; it < RES_VPT; ++it) {
+        const int v = ((int)blockIdx.x * RES_VPT + it) * 256 + (int)threadIdx.x;
+        if (v >= tv) break;
+        const int e = v * 4;
+        const int r = e / N, col = e - r * N;
+        const int64_t row = row0 + r;
         const int4 c = *(const int4*)(a.acc + z * a.st_acc + row * a.ldacc + col);
         float u[4];
         if (a.skip == FF_SKIP_IDENTITY) {
-            const float s_x = a.s_x[z * a.st_s_x];
             const uint32_t xw = *(const uint32_t*)(a.xq + z * a.st_xq + row * a.ldx + col);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) u[e] = (float)(int)(int8_t)(xw >> (8 * e)) * s_x;
+            for (int q = 0; q < 4; ++q) u[q] = (float)(int)(int8_t)(xw >> (8 * q)) * s_u;
         } else {
-            const float s_p = a.s_ap[z * a.st_s_ap] * a.s_wp[0];
             const int4 cp = *(const int4*)(a.accp + z * a.st_accp + row * a.ldaccp + col);
-            u[0] = (float)cp.x * s_p; u[1] = (float)cp.y * s_p; u[2] = (float)cp.z * s_p; u[3] = (float)cp.w * s_p;
+            u[0] = (float)cp.x * s_u; u[1] = (float)cp.y * s_u; u[2] = (float)cp.z * s_u; u[3] = (float)cp.w * s_u;
         }
         const int cc[4] = {c.x, c.y, c.z, c.w};
+        float yv[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float t = (float)cc[e] * s_y;
-            float v = t + u[e];
-            if (a.relu) v = fmaxf(v, 0.0f);
-            yv[e] = v;
+        for (int q = 0; q < 4; ++q) {
+            const float t = (float)cc[q] * s_y;
+            float w = t + u[q];
+            if (a.relu) w = fmaxf(w, 0.0f);
+            yv[q] = w;
+            m = max(m, __float_as_uint(fabsf(w)));
         }
-        *(float4*)(a.y + z * a.st_y + row * a.N + col) = make_float4(yv[0], yv[1], yv[2], yv[3]);
+        *(float4*)(a.y + z * a.st_y + row * N + col) = make_float4(yv[0], yv[1], yv[2], yv[3]);
     }
-    uint32_t m = max(max(__float_as_uint(fabsf(yv[0])), __float_as_uint(fabsf(yv[1]))),
-                     max(__float_as_uint(fabsf(yv[2])), __float_as_uint(fabsf(yv[3]))));
-    const int64_t smp = live ? row / a.rows_per_sample : -1;
-    uint32_t* ymax = a.ymax_bits + z * a.st_b;
-    int64_t first;
-    const uint32_t wm = wave_max_u32(m);
-    if (wave_uniform(smp, live, &first)) {
-        if ((threadIdx.x & 63) == 0 && wm > __hip_atomic_load(ymax + first, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-            atomicMax(ymax + first, wm);
-    } else if (live && m > __hip_atomic_load(ymax + smp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
-        atomicMax(ymax + smp, m);
-    }
-    uint32_t* slot = a.amax_bits + z * a.st_amax;
-    if ((threadIdx.x & 63) == 0 && wm > __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(slot, wm);
+    __shared__ uint32_t red[4];
+    const uint32_t bm = block_reduce_256(wave_max_u32(m), [](uint32_t x, uint32_t y) { return max(x, y); }, red);
+    if (threadIdx.x == 0 && bm) atomicMax(a.ymax_bits + z * a.st_b + smp, bm);
 }
 
 hipError_t launch_residual_act(const ResidualArgs& a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
-    const int64_t n = a.M * (a.N >> 2);
-    hipLaunchKernelGGL(k_residual_act, dim3((unsigned)((n + 255) / 256), (unsigned)a.nb), dim3(256), 0, s, a);
+    const int64_t tv = (int64_t)a.rows_per_sample * (a.N >> 2);
+    const int64_t B = a.M / a.rows_per_sample;
+    const unsigned bx = (unsigned)((tv + 256 * RES_VPT - 1) / (256 * RES_VPT));
+    if (B > 65535 || tv > (int64_t(1) << 28)) return hipErrorInvalidValue;   // grid y limit; 32-bit in-sample offsets
+    hipLaunchKernelGGL(k_residual_act, dim3(bx, (unsigned)B, (unsigned)a.nb), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
 // Fixed-point goodness sums of an fp32 activity tensor: per element floor(r * r * 2^40), r = y * (1 / amax) in
-// fp32, the product in fp64 (exact); unsigned 64-bit integer sums per sample (order-free).
+// fp32, the product in fp64 (exact); unsigned 64-bit integer sums per sample (order-free).  amax is the maximum
+// of the per-sample maxima, recomputed by every workgroup; workgroup (0, 0) of a pass also stores it to the slot
+// the quantisers of the next layers read.
 __global__ __launch_bounds__(256) void k_goodness_fx(GoodnessFxArgs a)
 {
-    const int z = blockIdx.y;
-    const int64_t n4 = a.N >> 2;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const bool live = idx < a.M * n4;
-    const float amax = __uint_as_float(a.amax_bits[z * a.st_amax]);
+    const int z = blockIdx.z;
+    const int64_t smp = blockIdx.y;
+    const int64_t B = gridDim.y;
+    __shared__ uint32_t redm[4];
+    __shared__ unsigned long long reds[4];
+    uint32_t mb = 0;
+    for (int64_t b = threadIdx.x; b < B; b += 256) mb = max(mb, a.ymax_bits[z * a.st_b + b]);
+    mb = block_reduce_256(wave_max_u32(mb), [](uint32_t x, uint32_t y) { return max(x, y); }, redm);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) a.amax_bits[z * a.st_amax] = mb;
+    const float amax = __uint_as_float(mb);
     const float inv = amax >= 0x1p-100f ? 1.0f / amax : 0.0f;
+    const int64_t tv = (int64_t)a.rows_per_sample * (a.N >> 2);
+    const float* ys = a.y + z * a.st_y + smp * tv * 4;
     unsigned long long q = 0;
-    int64_t row = 0;
-    if (live) {
-        row = idx / n4;
-        const float4 v = *(const float4*)(a.y + z * a.st_y + idx * 4);
-        const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int it = 0; it < RES_VPT; ++it) {
+        const int64_t v = ((int64_t)blockIdx.x * RES_VPT + it) * 256 + threadIdx.x;
+        if (v >= tv) break;
+        const float4 w = *(const float4*)(ys + v * 4);
+        const float ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const float r = vv[e] * inv;
+            const float r = ww[e] * inv;
             q += (unsigned long long)((double)r * (double)r * 0x1p40);
         }
     }
-    const int64_t smp = live ? row / a.rows_per_sample : -1;
-    unsigned long long* gs = a.gsum + z * a.st_b;
-    int64_t first;
-    if (wave_uniform(smp, live, &first)) {
-        const unsigned long long t = wave_sum_u64(q);
-        if ((threadIdx.x & 63) == 0 && t) atomicAdd(gs + first, t);
-    } else if (live && q) {
-        atomicAdd(gs + smp, q);
-    }
+    const unsigned long long t =
+        block_reduce_256(wave_sum_u64(q), [](unsigned long long x, unsigned long long y) { return x + y; }, reds);
+    if (threadIdx.x == 0 && t) atomicAdd(a.gsum + z * a.st_b + smp, t);
 }
 
 hipError_t launch_goodness_fx(const GoodnessFxArgs& a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
-    const int64_t n = a.M * (a.N >> 2);
-    hipLaunchKernelGGL(k_goodness_fx, dim3((unsigned)((n + 255) / 256), (unsigned)a.nb), dim3(256), 0, s, a);
+    const int64_t tv = (int64_t)a.rows_per_sample * (a.N >> 2);
+    const int64_t B = a.M / a.rows_per_sample;
+    const unsigned bx = (unsigned)((tv + 256 * RES_VPT - 1) / (256 * RES_VPT));
+    if (B > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_goodness_fx, dim3(bx, (unsigned)B, (unsigned)a.nb), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

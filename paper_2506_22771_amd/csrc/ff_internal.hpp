@@ -150,8 +150,6 @@ struct ResidualArgs {
     int64_t st_y;
     uint32_t* ymax_bits; // [B] per pass (stride st_b), zeroed: bit pattern of max|y| per sample
     int64_t st_b;
-    uint32_t* amax_bits; // slot per pass (stride st_amax), zeroed: bit pattern of max|y| over the pass
-    int32_t st_amax;
     int32_t nb;
 };
 hipError_t launch_residual_act(const ResidualArgs& a, hipStream_t s);
@@ -161,7 +159,8 @@ struct GoodnessFxArgs {
     int64_t st_y;
     int64_t M, N;
     int32_t rows_per_sample;
-    const uint32_t* amax_bits;
+    const uint32_t* ymax_bits; // [B] per pass (stride st_b): bit patterns of max|y| per sample
+    uint32_t* amax_bits;       // slot per pass (stride st_amax), written: max|y| over the pass
     int32_t st_amax;
     unsigned long long* gsum;  // [B] per pass (stride st_b), zeroed
     int64_t st_b;

@@ -355,6 +355,15 @@ static ff_status run_forward(const Dims& d, int relu, const int8_t* aq, int64_t 
     return FF_OK;
 }
 
+// Convolutions whose weight gradient reads column-shifted planes of the input instead of the full transposed
+// patch matrix (see GemmArgs::conv == 2).
+static bool wgrad_uses_planes(const Dims& d, int64_t nbatch, int nb)
+{
+    if (d.kind != FF_CONV2D || d.g.ks != 3 || (d.g.Wo & 15) != 0) return false;
+    const int64_t bytes = (int64_t)d.g.ks * d.g.Cin * pitch8(nbatch * d.g.H * d.g.Wo);
+    return bytes < (int64_t(1) << 31) && im2col_planes_ok(d.g, nbatch * nb);
+}
+
 // Weight gradient: dw[z][c] = gy_q_t[z][:, chunk c] x (patches of chunk c)^T for every chunk c.
 // `aqt` is the transposed quantised input (dense) or the NHWC quantised input (conv; patches are materialised
 // chunk by chunk into `colT`).  dw accumulators of one pass are dw_elems apart.
@@ -390,15 +399,30 @@ static ff_status run_wgrad(const Dims& d, const int8_t* gy_t, int64_t st_gy, con
             ic.out = colT;
             ic.st_out = st_colT;
             ic.g = d.g;
-            ic.K = (int32_t)d.K;
             ic.b0 = (int32_t)b0;
             ic.b1 = (int32_t)b1;
-            ic.ld_out = pitch8(mc);
             ic.nb = nb;
-            HIPCHK_T(FF_K_IM2COL, launch_im2col(ic, true, s));
             g.Q = colT;
             g.st_q = st_colT;
-            g.ldq = pitch8(mc);
+            if (wgrad_uses_planes(d, b1 - b0, nb)) {
+                // 3x3 convolution on rows of whole 16-pixel chunks: only the three column-shifted planes of the input
+                // are written (a third of the patch matrix); the contraction applies the row offsets itself
+                const int64_t ld3 = pitch8((b1 - b0) * d.g.H * d.g.Wo);
+                ic.K = (int32_t)(d.g.ks * d.g.Cin);
+                ic.ld_out = ld3;
+                ic.wtaps_only = 1;
+                HIPCHK_T(FF_K_IM2COL, launch_im2col(ic, true, s));
+                g.ldq = ld3;
+                g.conv = 2;
+                g.H = d.g.H; g.W = d.g.W; g.Cin = d.g.Cin; g.cpitch = d.g.cpitch; g.ks = d.g.ks;
+                g.stride = d.g.stride; g.pad = d.g.pad; g.Ho = d.g.Ho; g.Wo = d.g.Wo;
+                g.p_bytes = (int64_t)ic.K * ld3;
+            } else {
+                ic.K = (int32_t)d.K;
+                ic.ld_out = pitch8(mc);
+                HIPCHK_T(FF_K_IM2COL, launch_im2col(ic, true, s));
+                g.ldq = pitch8(mc);
+            }
         }
         g.splits = gemm_plan(g.I, g.J, g.R, nb, true).splits;
         if (g.splits > 1) {

@@ -105,8 +105,11 @@ __global__ __launch_bounds__(256) void k_im2col_t_slab(Im2colArgs p, int RH)
     const int z = blockIdx.z / nbatch, bl = blockIdx.z - z * nbatch, b = p.b0 + bl;
     const int8_t* __restrict__ a = p.a + z * p.st_a;
     int8_t* __restrict__ out = p.out + z * p.st_out;
+    // vertical geometry: the full patch rows, or (planes of horizontal taps only) the input rows themselves
+    const int vks = p.wtaps_only ? 1 : g.ks, vstride = p.wtaps_only ? 1 : g.stride, vpad = p.wtaps_only ? 0 : g.pad;
+    const int HoE = p.wtaps_only ? g.H : g.Ho;
     const int ho0 = blockIdx.x * RH, c0 = blockIdx.y * FT_CT;
-    const int NR = (RH - 1) * g.stride + g.ks;       // input rows of the slab
+    const int NR = (RH - 1) * vstride + vks;         // input rows of the slab
     const int WP = (g.W + 2 * g.pad + 3 + 4) & ~3;   // padded row length, a spare word for the 5-word read
     const int t = threadIdx.x;
     // ---- stage: every slab position (row, padded column, 16-channel group) is written once, zero outside the image
@@ -115,7 +118,7 @@ __global__ __launch_bounds__(256) void k_im2col_t_slab(Im2colArgs p, int RH)
     for (int e = t; e < npos; e += 256) {
         const int cg = e % ngroups, pos = e / ngroups;
         const int wp = pos % WP, hl = pos / WP;
-        const int hi = ho0 * g.stride - g.pad + hl, wi = wp - g.pad;
+        const int hi = ho0 * vstride - vpad + hl, wi = wp - g.pad;
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
         if ((unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W && c0 + 16 * cg < g.cpitch)
             v = *(const uint4*)(a + (((int64_t)b * g.H + hi) * g.W + wi) * g.cpitch + c0 + 16 * cg);
@@ -127,10 +130,10 @@ __global__ __launch_bounds__(256) void k_im2col_t_slab(Im2colArgs p, int RH)
     __syncthreads();
     // ---- emit
     const int nchunk = (RH * g.Wo) >> 4;    // 16-byte chunks of one colT row in this workgroup
-    const int ntap = g.ks * g.ks;
+    const int ntap = vks * g.ks;
     const int nct = min(FT_CT, g.Cin - c0);
     const int total = ntap * nct * nchunk;
-    const int64_t mbase = (int64_t)bl * g.Ho * g.Wo + (int64_t)ho0 * g.Wo;
+    const int64_t mbase = (int64_t)bl * HoE * g.Wo + (int64_t)ho0 * g.Wo;
     for (int e = t; e < total; e += 256) {
         const int ch = e % nchunk, r = e / nchunk;
         const int ci = r % nct, tap = r / nct;
@@ -154,7 +157,7 @@ __global__ __launch_bounds__(256) void k_im2col_t_slab(Im2colArgs p, int RH)
             const uint8_t* base = slab + (ci * NR + kh) * WP + kw;
 #pragma unroll
             for (int tt = 0; tt < 16; ++tt) {
-                w[tt >> 2] |= (uint32_t)base[hl * g.stride * WP + wo * g.stride] << (8 * (tt & 3));
+                w[tt >> 2] |= (uint32_t)base[hl * vstride * WP + wo * g.stride] << (8 * (tt & 3));
                 if (++wo == g.Wo) { wo = 0; ++hl; }
             }
             o = make_uint4(w[0], w[1], w[2], w[3]);
@@ -163,27 +166,46 @@ __global__ __launch_bounds__(256) void k_im2col_t_slab(Im2colArgs p, int RH)
     }
 }
 
+// Rows per workgroup of the slab kernel: about 256 contiguous bytes per output row, a divisor of the row count,
+// RH * W_out % 16 == 0.  Returns 0 when the slab path cannot serve the geometry.
+static int slab_rows(const ConvGeom& g, bool wtaps_only, int64_t grid_z, size_t* lds_bytes)
+{
+    const int HoE = wtaps_only ? g.H : g.Ho;
+    if (((HoE * g.Wo) & 15) != 0 || grid_z > 65535) return 0;
+    int RH = 256 / g.Wo;
+    if (RH < 1) RH = 1;
+    if (RH > HoE) RH = HoE;
+    while (RH > 1 && (HoE % RH || ((RH * g.Wo) & 15))) --RH;
+    if (HoE % RH || ((RH * g.Wo) & 15)) RH = HoE;
+    const int vks = wtaps_only ? 1 : g.ks, vstride = wtaps_only ? 1 : g.stride;
+    const int NR = (RH - 1) * vstride + vks, WP = (g.W + 2 * g.pad + 3 + 4) & ~3;
+    *lds_bytes = (size_t)FT_CT * NR * WP + 16;
+    return *lds_bytes <= 64 * 1024 ? RH : 0;
+}
+
+bool im2col_planes_ok(const ConvGeom& g, int64_t nbatch_times_nb)
+{
+    size_t lds;
+    return (g.Wo & 15) == 0 && slab_rows(g, true, nbatch_times_nb, &lds) > 0;
+}
+
 hipError_t launch_im2col(const Im2colArgs& p, bool transposed, hipStream_t s)
 {
     const int64_t rows = transposed ? p.K : (int64_t)(p.b1 - p.b0) * p.g.Ho * p.g.Wo;
     const int64_t total = rows * (p.ld_out >> 4);
     if (total <= 0) return hipSuccess;
     const ConvGeom& g = p.g;
-    if (transposed && ((g.Ho * g.Wo) & 15) == 0 && (int64_t)p.nb * (p.b1 - p.b0) <= 65535) {
-        // rows per workgroup: about 256 contiguous bytes per colT row, a divisor of H_out, RH * W_out % 16 == 0
-        int RH = 256 / g.Wo;
-        if (RH < 1) RH = 1;
-        if (RH > g.Ho) RH = g.Ho;
-        while (RH > 1 && (g.Ho % RH || ((RH * g.Wo) & 15))) --RH;
-        if (g.Ho % RH || ((RH * g.Wo) & 15)) RH = g.Ho;
-        const int NR = (RH - 1) * g.stride + g.ks, WP = (g.W + 2 * g.pad + 3 + 4) & ~3;
-        const size_t lds = (size_t)FT_CT * NR * WP + 16;
-        if (lds <= 64 * 1024) {
-            const dim3 grid((unsigned)(g.Ho / RH), (unsigned)((g.Cin + FT_CT - 1) / FT_CT), (unsigned)(p.nb * (p.b1 - p.b0)));
+    if (transposed) {
+        size_t lds = 0;
+        const int RH = slab_rows(g, p.wtaps_only != 0, (int64_t)p.nb * (p.b1 - p.b0), &lds);
+        if (RH > 0) {
+            const int HoE = p.wtaps_only ? g.H : g.Ho;
+            const dim3 grid((unsigned)(HoE / RH), (unsigned)((g.Cin + FT_CT - 1) / FT_CT), (unsigned)(p.nb * (p.b1 - p.b0)));
             if (g.stride == 1 && (g.Wo & 15) == 0) hipLaunchKernelGGL(k_im2col_t_slab<true>, grid, dim3(256), lds, s, p, RH);
             else hipLaunchKernelGGL(k_im2col_t_slab<false>, grid, dim3(256), lds, s, p, RH);
             return hipGetLastError();
         }
+        if (p.wtaps_only) return hipErrorInvalidValue;   // the generic kernel below writes full patches only
     }
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65535) blocks = 65535;

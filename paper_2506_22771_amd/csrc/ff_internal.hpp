@@ -205,8 +205,10 @@ struct GemmArgs {
     int64_t st_split;
     // implicit-GEMM convolution (conv != 0): P is an NHWC int8 tensor [B, H, W, cpitch] and row i of the
     // contraction is output pixel (b, ho, wo); reduction index r = (kh*ks + kw)*Cin + ci.  Cin % 16 == 0.
+    // conv == 2: Q is a set of planes S[kw][ci][(b, h, wo)] (row pitch ldq bytes) written by launch_im2col with
+    // wtaps_only; row j of the contraction is (kh, kw, ci), the reduction runs over output pixels.  W_out % 16 == 0.
     int32_t conv, H, W, Cin, cpitch, ks, stride, pad, Ho, Wo;
-    int64_t p_bytes;  // bytes of one P tensor (conv only; must be < 2^31)
+    int64_t p_bytes;  // bytes of one implicit operand tensor (conv only; must be < 2^31)
 };
 hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s);
 struct GemmPlan {
@@ -229,7 +231,12 @@ struct Im2colArgs {
     int64_t ld_out;
     int32_t nb;
     int64_t st_a, st_out;
+    // transposed only: write the horizontal taps alone, as planes S[kw][ci][(b, h, wo)] over INPUT rows h:
+    // S = A[b][h][wo * stride + kw - pad][ci], zero outside the image (K = ks * C_in rows of ld_out bytes)
+    int32_t wtaps_only;
 };
 hipError_t launch_im2col(const Im2colArgs& p, bool transposed, hipStream_t s);
+// true when launch_im2col can write the planes for this geometry (LDS slab fits, grid limits)
+bool im2col_planes_ok(const ConvGeom& g, int64_t nbatch_times_nb);
 
 }  // namespace ffi

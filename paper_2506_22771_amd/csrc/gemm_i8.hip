@@ -65,7 +65,13 @@ __device__ __forceinline__ int swz(int row, int kc) { return row * BK + ((kc ^ (
 
 // MODE 0: store C; 1: store C and accumulate the per-sample goodness sums / maxima; 2: split reduction, this
 // workgroup stores the partial sums of its share of the reduction steps at C + blockIdx.y * st_split.
-template <int BM, int BN, int WM, int WN, int MODE, bool CONV>
+// CONV 0: both operands are matrices.  1: P is an NHWC tensor, row i of the contraction is an output pixel and
+// the reduction runs over (tap, channel) (forward pass of a convolution as an implicit GEMM).  2: Q is a set of
+// column-shifted channel-major planes S[kw][ci][(b, h, wo)] of the layer input, row j of the contraction is
+// (tap, channel) and the reduction runs over output pixels (weight gradient of a convolution as an implicit
+// GEMM: the vertical tap offset is an address offset of whole 16-byte chunks, rows outside the image read as
+// zero through the range check).
+template <int BM, int BN, int WM, int WN, int MODE, int CONV>
 __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
 {
     constexpr bool EPI = MODE == 1;
@@ -100,18 +106,20 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     if (MODE == 2) C += (int64_t)blockIdx.y * a.st_split;
 
     const int rows_p = min(BM, a.I - i0), rows_q = min(BN, a.J - j0);
-    __amdgpu_buffer_rsrc_t rp = CONV ? __builtin_amdgcn_make_buffer_rsrc((void*)P, 0, (int)a.p_bytes, 0x00020000)
-                                     : __builtin_amdgcn_make_buffer_rsrc((void*)(P + (int64_t)i0 * a.ldp), 0, (int)(rows_p * a.ldp), 0x00020000);
-    __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc((void*)(Q + (int64_t)j0 * a.ldq), 0, (int)(rows_q * a.ldq), 0x00020000);
+    __amdgpu_buffer_rsrc_t rp = CONV == 1 ? __builtin_amdgcn_make_buffer_rsrc((void*)P, 0, (int)a.p_bytes, 0x00020000)
+                                          : __builtin_amdgcn_make_buffer_rsrc((void*)(P + (int64_t)i0 * a.ldp), 0, (int)(rows_p * a.ldp), 0x00020000);
+    __amdgpu_buffer_rsrc_t rq = CONV == 2 ? __builtin_amdgcn_make_buffer_rsrc((void*)Q, 0, (int)a.p_bytes, 0x00020000)
+                                          : __builtin_amdgcn_make_buffer_rsrc((void*)(Q + (int64_t)j0 * a.ldq), 0, (int)(rows_q * a.ldq), 0x00020000);
     // Every chunk of one thread has the same k column: chunk index c = s*T + tid, T a multiple of 8,
     // LDS slot (row = c >> 3, c & 7) holds reduction chunk (c & 7) ^ ((row >> 1) & 7) of that row.
     const int kcol = (((tid & 7) ^ ((tid >> 4) & 7))) * 16;
     int offP[CH_P], offQ[CH_Q];
-    int hi0[CONV ? CH_P : 1], wi0[CONV ? CH_P : 1];   // conv: input pixel of tap (0,0) for the chunk's output pixel
+    int hi0[CONV == 1 ? CH_P : 1], wi0[CONV == 1 ? CH_P : 1];   // conv: input pixel of tap (0,0) for the chunk's output pixel
+    int khq[CONV == 2 ? CH_Q : 1];                              // planes: vertical tap offset (kh - pad) of the chunk's row
 #pragma unroll
     for (int s = 0; s < CH_P; ++s) {
         const int row = (s * T + tid) >> 3;
-        if (CONV) {
+        if (CONV == 1) {
             const int m = i0 + row;
             const int b = m / (a.Ho * a.Wo), rem = m - b * (a.Ho * a.Wo);
             const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
@@ -123,12 +131,23 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
         }
     }
 #pragma unroll
-    for (int s = 0; s < CH_Q; ++s) offQ[s] = ((s * T + tid) >> 3) * (int)a.ldq + kcol;
+    for (int s = 0; s < CH_Q; ++s) {
+        const int row = (s * T + tid) >> 3;
+        if (CONV == 2) {
+            const int j = j0 + row;   // (tap, channel) = (kh, kw, ci)
+            const int tap = j / a.Cin, ci = j - tap * a.Cin;
+            const int kh = tap / a.ks, kw = tap - kh * a.ks;
+            khq[s] = j < a.J ? kh - a.pad : -(1 << 20);   // rows beyond the matrix never pass the bounds test
+            offQ[s] = (kw * a.Cin + ci) * (int)a.ldq;
+        } else {
+            offQ[s] = row * (int)a.ldq + kcol;
+        }
+    }
     auto issue = [&](int kt, int buf) {
         const int k0 = __builtin_amdgcn_readfirstlane(kt * BK);   // wave-uniform: it travels in a scalar register
         const bool ok = k0 + kcol < Rpad;   // only the last step can have chunks beyond the reduction length
         int8_t* base = lds + buf * STAGE_BYTES;
-        if (CONV) {
+        if (CONV == 1) {
             const int k = k0 + kcol;
             const int tap = k / a.Cin, ci0 = k - tap * a.Cin;
             const int kh = tap / a.ks, kw = tap - kh * a.ks;
@@ -143,9 +162,26 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
             for (int s = 0; s < CH_P; ++s)
                 lds_dma16(rp, ok ? offP[s] : OOB - k0, k0, (unsigned)(uintptr_t)(base + (s * T + wave * 64) * 16));
         }
+        if (CONV == 2) {
+            // the chunk's 16 reduction positions are 16 consecutive output pixels of one output row (W_out % 16 == 0)
+            const int m = k0 + kcol;
+            const int hw = a.Ho * a.Wo;
+            const int b = m / hw, rem = m - b * hw;
+            const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
+            const int hb = ho * a.stride;
+            const int base_in = b * a.H * a.Wo + wo;
 #pragma unroll
-        for (int s = 0; s < CH_Q; ++s)
-            lds_dma16(rq, ok ? offQ[s] : OOB - k0, k0, (unsigned)(uintptr_t)(base + BM * BK + (s * T + wave * 64) * 16));
+            for (int s = 0; s < CH_Q; ++s) {
+                const int hi = hb + khq[s];
+                const bool in = ok && (unsigned)hi < (unsigned)a.H;
+                lds_dma16(rq, in ? offQ[s] + base_in + hi * a.Wo : OOB, 0,
+                          (unsigned)(uintptr_t)(base + BM * BK + (s * T + wave * 64) * 16));
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < CH_Q; ++s)
+                lds_dma16(rq, ok ? offQ[s] : OOB - k0, k0, (unsigned)(uintptr_t)(base + BM * BK + (s * T + wave * 64) * 16));
+        }
     };
 
     v16i acc[TI][TJ];
@@ -290,14 +326,18 @@ static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s)
     const int tiles_i = (a.I + BM - 1) / BM, tiles_j = (a.J + BN - 1) / BN;
     const dim3 grid((unsigned)(tiles_i * tiles_j), (unsigned)a.splits, (unsigned)a.nb), block(WM * WN * 64);
     const int mode = a.splits > 1 ? 2 : (a.gsum ? 1 : 0);
-    if (a.conv) {
-        if (mode == 1) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 1, true>), grid, block, 0, s, a);
-        else if (mode == 0) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 0, true>), grid, block, 0, s, a);
+    if (a.conv == 1) {
+        if (mode == 1) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 1, 1>), grid, block, 0, s, a);
+        else if (mode == 0) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 0, 1>), grid, block, 0, s, a);
+        else return hipErrorInvalidValue;
+    } else if (a.conv == 2) {
+        if (mode == 2) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 2, 2>), grid, block, 0, s, a);
+        else if (mode == 0) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 0, 2>), grid, block, 0, s, a);
         else return hipErrorInvalidValue;
     } else {
-        if (mode == 1) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 1, false>), grid, block, 0, s, a);
-        else if (mode == 0) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 0, false>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 2, false>), grid, block, 0, s, a);
+        if (mode == 1) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 1, 0>), grid, block, 0, s, a);
+        else if (mode == 0) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 0, 0>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 2, 0>), grid, block, 0, s, a);
     }
     return hipGetLastError();
 }
@@ -379,8 +419,12 @@ hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s)
     if (a.I <= 0 || a.J <= 0) return hipSuccess;
     // byte offsets of the operand copies are 32-bit (tile-relative for dense operands, tensor-relative for conv)
     if (a.ldp >= (int64_t(1) << 22) || a.ldq >= (int64_t(1) << 22)) return hipErrorInvalidValue;
-    if (a.conv && (a.p_bytes >= (int64_t(1) << 31) || (a.Cin & 15) != 0)) return hipErrorInvalidValue;
-    if (a.splits < 1 || (a.splits > 1 && (a.gsum || a.conv))) return hipErrorInvalidValue;
+    if (a.conv == 1 && (a.p_bytes >= (int64_t(1) << 31) || (a.Cin & 15) != 0)) return hipErrorInvalidValue;
+    // planes: chunks of 16 output pixels must lie in one output row; the reduction covers whole samples
+    if (a.conv == 2 && (a.p_bytes >= (int64_t(1) << 31) || (a.Wo & 15) != 0 || a.R % (a.Ho * a.Wo) != 0 || a.gsum))
+        return hipErrorInvalidValue;
+    if (a.conv < 0 || a.conv > 2) return hipErrorInvalidValue;
+    if (a.splits < 1 || (a.splits > 1 && (a.gsum || a.conv == 1))) return hipErrorInvalidValue;
     GemmPlan p = gemm_plan(a.I, a.J, a.R, a.nb, a.splits > 1);
     const int bm = p.bm, bn = p.bn;
     if (bn == 256) {

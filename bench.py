@@ -241,6 +241,23 @@ def main() -> int:
                 "dw_TOPs": (ops_per_step / 2) / (kern["gemm_dw"]["ms_per_step"] * 1e-3) / 1e12
                 if kern["gemm_dw"]["ms_per_step"] > 0 else 0.0}
 
+    # HBM-bound kernel classes (dense stacks): algorithmic bytes per step / time of the fully instrumented pass
+    hbm = None
+    if all(l.kind == "dense" for l in wl.layers):
+        S = 2 * B   # samples per step, both passes
+        byts = {"absmax": 4.0 * wl.layers[0].K * S,
+                "quant_act": sum((4.0 * l.K + 2.0 * l.K) * S for l in wl.layers),    # read fp32 / int32, write q and q^T
+                "quant_grad": sum((4.0 * l.N + 1.0 * l.N) * S for l in wl.layers),   # read int32, write g^T
+                "update": sum(16.0 * l.K * l.N for l in wl.layers),                  # read w, dW+, dW-, write w
+                "quant_w": sum(5.0 * l.K * l.N for l in wl.layers)}                  # read w, write w_q
+        hbm = {}
+        for name, nbytes in byts.items():
+            ms = breakdown[name]["ms_per_step"]
+            if ms > 0:
+                gbs = nbytes / (ms * 1e-3) / 1e9
+                hbm[name] = {"algorithmic_MB_per_step": round(nbytes / 1e6, 1), "GBps": round(gbs, 1),
+                             "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
     out = {
         "metric": "FF-INT8 train samples/sec per layer step; int8 MFMA TOPS as % of peak",
         "value": samples * k / (ms_per_step * 1e-3),
@@ -255,6 +272,7 @@ def main() -> int:
         "int8_mfma_pct_of_peak": 100.0 * achieved / INT8_MFMA_PEAK_TOPS,
         "roofline": roofline,
         "kernels_ms_per_step": {n: round(v["ms_per_step"], 5) for n, v in breakdown.items()},
+        "hbm_bound_kernels": hbm,
         "other_launch_modes": extra,
         "paper_context": "Jetson Orin Nano, whole training runs: 4.6% faster, 8.3% less energy, 27.0% less memory "
                          "than BP-GDAI8 (Table V); no per-step figure is published",

@@ -90,3 +90,37 @@ def test_workspace_bytes_and_train_step_validation(ff):
     mism = (ff.binding.LayerDesc * 2)(ff.layer_desc(wl.layers[0], wl.batch), ff.layer_desc(wl.layers[0], wl.batch))
     assert ff.lib().ff_workspace_bytes(C.byref(ff.binding.NetDesc(2, wl.batch, mism))) == 0   # 500 != 784
     assert ff.lib().ff_train_step(C.byref(net), None, None, None, 2.0, 0.0, 0.1, 0, 0, None, None, None, 0, None) == -1
+
+
+def test_residual_topology_validation(ff):
+    """Host-side checks of the residual-block wiring in ff_net_desc: valid stacks get a workspace size, every
+    inconsistent wiring is rejected (size 0) before anything could be launched."""
+    import ctypes as C
+    import dataclasses
+    from workloads import workload
+
+    def ws_bytes(layers, batch):
+        descs = (ff.binding.LayerDesc * len(layers))(*[ff.layer_desc(l, batch) for l in layers])
+        return ff.lib().ff_workspace_bytes(C.byref(ff.binding.NetDesc(len(layers), batch, descs)))
+
+    for name in ("tiny_res", "cfg4"):
+        wl = workload(name)
+        assert ws_bytes(wl.layers, wl.batch) > 0
+    wl = workload("tiny_res")
+    L = list(wl.layers)   # stem, conv1, conv2(identity), proj, conv1(input_back=1), conv2(projection)
+    rep = dataclasses.replace
+
+    def bad(i, **kw):
+        layers = list(L)
+        layers[i] = rep(layers[i], **kw)
+        return ws_bytes(layers, wl.batch)
+
+    assert bad(2, skip="projection") == 0          # no projection two layers back
+    assert bad(2, C_out=24) == 0                   # identity skip with a different channel count
+    assert bad(5, skip="identity") == 0            # block input 16 channels at 8x16, output 32 channels at 4x8
+    assert bad(5, skip="none") == 0                # a projection nobody adds
+    assert bad(4, input_back=0) == 0               # conv1 after a projection must read the block input
+    assert bad(3, relu=1) == 0                     # a projection has no activation of its own
+    assert bad(1, input_back=2) == 0               # only the previous layer or the one before it
+    assert bad(2, l2norm_out=1) == 0               # no normalised hand-off from a block output
+    assert ws_bytes(L[:4], wl.batch) == 0          # stack ends in a projection

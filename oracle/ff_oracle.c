@@ -27,7 +27,8 @@
  * loss for the local gradient, a hand-computed look-ahead example, and for
  * the residual-block functions: zero skip == plain layer, zero weights ==
  * dequantised input, exact goodness of power-of-two activities, order
- * independence and agreement with the fp64 sum of squares.
+ * independence and agreement with the fp64 sum of squares; depthwise
+ * convolution == full convolution with channel-diagonal weights.
  * The look-ahead *semantics* (which reading of Eq. (4) is meant) has no pin in
  * the paper: parity unpinned for that choice; its arithmetic is pinned.
  */
@@ -190,6 +191,31 @@ int ffo_conv_forward(const int8_t *a_q, const int8_t *w_q, int64_t B, int64_t H,
             }
     }
     return bad ? FFO_ERR_OVERFLOW : FFO_OK;
+}
+
+/* Depthwise convolution (one filter per channel; the inverted-bottleneck stacks of Table II are built from it):
+ * acc[b][ho][wo][c] = sum over taps of a_q[b][hi][wi][c] * w_q[c][kh][kw]; NHWC input, weights [C][kh][kw]. */
+int ffo_dwconv_forward(const int8_t *a_q, const int8_t *w_q, int64_t B, int64_t H, int64_t W, int64_t C,
+                       int64_t ks, int64_t stride, int64_t pad, int32_t *acc)
+{
+    if (!a_q || !w_q || !acc || stride < 1 || ks < 1) return FFO_ERR_ARG;
+    const int64_t Ho = (H + 2 * pad - ks) / stride + 1, Wo = (W + 2 * pad - ks) / stride + 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t bh = 0; bh < B * Ho; ++bh) {
+        const int64_t b = bh / Ho, ho = bh % Ho;
+        for (int64_t wo = 0; wo < Wo; ++wo)
+            for (int64_t c = 0; c < C; ++c) {
+                int64_t s = 0;
+                for (int64_t kh = 0; kh < ks; ++kh)
+                    for (int64_t kw = 0; kw < ks; ++kw) {
+                        const int64_t hi = ho * stride + kh - pad, wi = wo * stride + kw - pad;
+                        if (hi < 0 || hi >= H || wi < 0 || wi >= W) continue;
+                        s += (int32_t)a_q[((b * H + hi) * W + wi) * C + c] * (int32_t)w_q[(c * ks + kh) * ks + kw];
+                    }
+                acc[((b * Ho + ho) * Wo + wo) * C + c] = (int32_t)s;
+            }
+    }
+    return FFO_OK;
 }
 
 /* ------------------------------------------------------------------------
@@ -507,6 +533,33 @@ int ffo_conv_wgrad(const int8_t *gy_q, const int8_t *a_q, int64_t b0, int64_t b1
                     if (s > INT32_MAX || s < INT32_MIN) bad |= 1;
                     dw[((co * ks + kh) * ks + kw) * Cin + ci] = (int32_t)s;
                 }
+    return bad ? FFO_ERR_OVERFLOW : FFO_OK;
+}
+
+/* Weight gradient of a depthwise convolution over the samples [b0, b1):
+ * dw[c][kh][kw] = sum over (b, ho, wo) of gy_q[b][ho][wo][c] * a_q[b][hi][wi][c]. */
+int ffo_dwconv_wgrad(const int8_t *gy_q, const int8_t *a_q, int64_t b0, int64_t b1, int64_t H, int64_t W,
+                     int64_t C, int64_t ks, int64_t stride, int64_t pad, int32_t *dw)
+{
+    if (!gy_q || !a_q || !dw || stride < 1 || ks < 1 || b1 < b0) return FFO_ERR_ARG;
+    const int64_t Ho = (H + 2 * pad - ks) / stride + 1, Wo = (W + 2 * pad - ks) / stride + 1;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t c = 0; c < C; ++c)
+        for (int64_t kh = 0; kh < ks; ++kh)
+            for (int64_t kw = 0; kw < ks; ++kw) {
+                int64_t s = 0;
+                for (int64_t b = b0; b < b1; ++b)
+                    for (int64_t ho = 0; ho < Ho; ++ho)
+                        for (int64_t wo = 0; wo < Wo; ++wo) {
+                            const int64_t hi = ho * stride + kh - pad, wi = wo * stride + kw - pad;
+                            if (hi < 0 || hi >= H || wi < 0 || wi >= W) continue;
+                            s += (int32_t)gy_q[((b * Ho + ho) * Wo + wo) * C + c] *
+                                 (int32_t)a_q[((b * H + hi) * W + wi) * C + c];
+                        }
+                if (s > INT32_MAX || s < INT32_MIN) bad |= 1;
+                dw[(c * ks + kh) * ks + kw] = (int32_t)s;
+            }
     return bad ? FFO_ERR_OVERFLOW : FFO_OK;
 }
 

@@ -55,6 +55,8 @@ def lib() -> C.CDLL:
         L.ffo_lookahead.argtypes = [P, i32, i64, f32, P]
         L.ffo_local_grad.argtypes = [P, i64, i64, i32, f32, f32, P, P]
         L.ffo_dense_wgrad.argtypes = [P, P, i64, i64, i64, P]
+        L.ffo_dwconv_forward.argtypes = [P, P, i64, i64, i64, i64, i64, i64, i64, P]
+        L.ffo_dwconv_wgrad.argtypes = [P, P, i64, i64, i64, i64, i64, i64, i64, i64, P]
         L.ffo_skip_identity.argtypes = [P, i64, f32, P]
         L.ffo_skip_projection.argtypes = [P, i64, f32, f32, P]
         L.ffo_residual_act.argtypes = [P, P, i64, i32, f32, f32, P]
@@ -132,6 +134,25 @@ def conv_forward(a_q: np.ndarray, w_q: np.ndarray, stride: int, pad: int) -> np.
     _chk(lib().ffo_conv_forward(_p(a_q), _p(w_q), B, H, W, Cin, Cout, ks, stride, pad, _p(acc)),
          "conv_forward")
     return acc
+
+
+def dwconv_forward(a_q: np.ndarray, w_q: np.ndarray, stride: int, pad: int) -> np.ndarray:
+    """Depthwise convolution: a_q [B, H, W, C] int8, w_q [C, ks, ks] int8 -> int32 [B, Ho, Wo, C]."""
+    B, H, W, Cc = a_q.shape
+    C2, ks, ks2 = w_q.shape
+    assert ks == ks2 and Cc == C2
+    Ho = (H + 2 * pad - ks) // stride + 1
+    Wo = (W + 2 * pad - ks) // stride + 1
+    acc = np.empty((B, Ho, Wo, Cc), dtype=np.int32)
+    _chk(lib().ffo_dwconv_forward(_p(a_q), _p(w_q), B, H, W, Cc, ks, stride, pad, _p(acc)), "dwconv_forward")
+    return acc
+
+
+def dwconv_wgrad(gy_q: np.ndarray, a_q: np.ndarray, ks: int, stride: int, pad: int, b0: int, b1: int) -> np.ndarray:
+    B, H, W, Cc = a_q.shape
+    dw = np.empty((Cc, ks, ks), dtype=np.int32)
+    _chk(lib().ffo_dwconv_wgrad(_p(gy_q), _p(a_q), b0, b1, H, W, Cc, ks, stride, pad, _p(dw)), "dwconv_wgrad")
+    return dw
 
 
 def goodness_shift(K: int, terms: int) -> int:
@@ -297,6 +318,8 @@ def forward_layer(layer, a_f32: np.ndarray, w_q: np.ndarray, s_w, pass_sign: int
     a_q, s_a = quantize(a_f32, ROUND_STOCHASTIC, seed, tag_act)
     if layer.kind == "dense":
         acc = dense_forward(a_q, w_q)
+    elif layer.kind == "dwconv":
+        acc = dwconv_forward(a_q, w_q, layer.stride, layer.pad)
     else:
         acc = conv_forward(a_q, w_q, layer.stride, layer.pad)
     r = goodness_shift(layer.K, layer.terms_per_sample)
@@ -395,6 +418,8 @@ def train_step(layers, w_master: List[np.ndarray], x_pos: np.ndarray, x_neg: np.
             for (b0, b1) in chunks:
                 if layer.kind == "dense":
                     dw = dense_wgrad(gy_q[b0:b1], f["a_q"][b0:b1])
+                elif layer.kind == "dwconv":
+                    dw = dwconv_wgrad(gy_q, f["a_q"], layer.ksize, layer.stride, layer.pad, b0, b1)
                 else:
                     dw = conv_wgrad(gy_q, f["a_q"], layer.ksize, layer.stride, layer.pad, b0, b1)
                 dw_chunks.append(dw.reshape(-1))

@@ -25,7 +25,8 @@ NUM_CLASSES = 10
 @dataclasses.dataclass(frozen=True)
 class Layer:
     """One FF layer.  kind 'dense': in_features -> out_features.
-    kind 'conv': NHWC, H x W x C_in -> H_out x W_out x C_out, square kernel."""
+    kind 'conv': NHWC, H x W x C_in -> H_out x W_out x C_out, square kernel.
+    kind 'dwconv': depthwise convolution, one ks x ks filter per channel (C_in == C_out)."""
     kind: str
     in_features: int = 0
     out_features: int = 0
@@ -54,7 +55,11 @@ class Layer:
     @property
     def K(self) -> int:
         """Reduction length of the forward contraction."""
-        return self.in_features if self.kind == "dense" else self.ksize * self.ksize * self.C_in
+        if self.kind == "dense":
+            return self.in_features
+        if self.kind == "dwconv":
+            return self.ksize * self.ksize
+        return self.ksize * self.ksize * self.C_in
 
     @property
     def N(self) -> int:
@@ -77,6 +82,8 @@ class Layer:
     def weight_shape(self) -> Tuple[int, ...]:
         if self.kind == "dense":
             return (self.out_features, self.in_features)
+        if self.kind == "dwconv":
+            return (self.C_out, self.ksize, self.ksize)
         return (self.C_out, self.ksize, self.ksize, self.C_in)
 
     @property
@@ -134,6 +141,20 @@ def res_stack(stem_out: int, stages: List[Tuple[int, int, int]], h: int, w: int,
     return tuple(layers)
 
 
+def bottleneck_stack(stem_out: int, blocks: List[Tuple[int, int, int]], h: int, w: int, c_in: int = 3) -> Tuple[Layer, ...]:
+    """Stem conv3x3 + inverted bottlenecks without skip connections.  blocks: (expansion, C_out, stride):
+    conv1x1 C -> t*C, depthwise 3x3 (stride s), conv1x1 t*C -> C_out."""
+    layers = [Layer("conv", H=h, W=w, C_in=c_in, C_out=stem_out, ksize=3, stride=1, pad=1)]
+    c = stem_out
+    for (t, c_out, s) in blocks:
+        layers.append(Layer("conv", H=h, W=w, C_in=c, C_out=t * c, ksize=1, stride=1, pad=0))
+        layers.append(Layer("dwconv", H=h, W=w, C_in=t * c, C_out=t * c, ksize=3, stride=s, pad=1))
+        h, w = (h + 2 - 3) // s + 1, (w + 2 - 3) // s + 1
+        layers.append(Layer("conv", H=h, W=w, C_in=t * c, C_out=c_out, ksize=1, stride=1, pad=0))
+        c = c_out
+    return tuple(layers)
+
+
 def workload(name: str) -> Workload:
     """The benchmark configurations (shapes only; all data is synthetic)."""
     if name == "cfg1":   # small MLP, latency-bound
@@ -159,6 +180,13 @@ def workload(name: str) -> Workload:
                         "uniform_onehot", lam=0.05)
     if name == "tiny_res":   # stem 3->16 at 8x16, an identity block, a down-sampling block with projection
         return Workload("tiny_res", res_stack(16, [(16, 1, 1), (32, 2, 1)], 8, 16), 6, "uniform_onehot", lam=0.05)
+    if name == "mbv2_like":
+        # 1x1-heavy stack with depthwise 3x3 convolutions, shaped like the first stages of a MobileNet-V2 on
+        # 32x32x3 images (Table II lists such networks): stem 32, then (t, c, s) = (1,16,1), (6,24,1), (6,24,1), (6,32,2), (6,32,1)
+        return Workload("mbv2_like", bottleneck_stack(32, [(1, 16, 1), (6, 24, 1), (6, 24, 1), (6, 32, 2), (6, 32, 1)], 32, 32),
+                        256, "uniform_onehot", lam=0.05)
+    if name == "tiny_dw":   # stem 3->16 at 8x12, two bottlenecks (the second with stride 2)
+        return Workload("tiny_dw", bottleneck_stack(16, [(2, 16, 1), (3, 20, 2)], 8, 12), 5, "uniform_onehot", lam=0.05)
     if name == "cfg5":   # large-GEMM stress
         return Workload("cfg5", mlp([4096, 4096, 4096], False), 8192, "normal", lam=0.05)
     if name == "tiny":   # ragged shapes spanning tile tails, for quick parity tests

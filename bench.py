@@ -221,7 +221,8 @@ def main() -> int:
     # dominant kernel: the int8 contraction (forward + weight-gradient launches; each launch covers both passes)
     gemm_ms = kern["gemm_fwd"]["ms_per_step"] + kern["gemm_dw"]["ms_per_step"]
     gemm_launches = kern["gemm_fwd"]["launches_per_step"] + kern["gemm_dw"]["launches_per_step"]
-    ops_per_step = sum(2.0 * 2 * B * l.rows_per_sample * l.K * l.N * 2 for l in wl.layers)  # fwd + dW, both passes
+    # fwd + dW, both passes, of the layers that run on the MFMA contraction kernel (depthwise layers do not)
+    ops_per_step = sum(2.0 * 2 * B * l.rows_per_sample * l.K * l.N * 2 for l in wl.layers if l.kind != "dwconv")
     ops_per_launch = ops_per_step / max(gemm_launches, 1)
     avg_launch_ms = gemm_ms / max(gemm_launches, 1)
     achieved = ops_per_launch / (avg_launch_ms * 1e-3) / 1e12 if avg_launch_ms > 0 else 0.0

@@ -55,7 +55,7 @@ enum {
 };
 enum { FF_ROUND_NEAREST_EVEN = 0, FF_ROUND_STOCHASTIC = 1 };
 enum { FF_PASS_POS = +1, FF_PASS_NEG = -1 };
-enum { FF_DENSE = 0, FF_CONV2D = 1 };
+enum { FF_DENSE = 0, FF_CONV2D = 1, FF_DWCONV2D = 2 };
 
 /* Stochastic-rounding stream kinds used by ff_train_step (see ff_stream_tag). */
 enum { FF_KIND_ACT = 0, FF_KIND_GRAD = 1 };
@@ -66,6 +66,9 @@ enum { FF_KIND_ACT = 0, FF_KIND_GRAD = 1 };
 /* One FF layer.  kind FF_DENSE uses batch / in_features / out_features; kind FF_CONV2D
  * uses batch, H, W, C_in, C_out, ksize (1 or 3), stride (1 or 2), pad (= ksize/2),
  * input NHWC, weights [C_out][ksize][ksize][C_in].
+ * kind FF_DWCONV2D is a depthwise convolution (one ksize x ksize filter per channel): C_out == C_in, ksize 3,
+ * stride 1 or 2, pad 1; weights [C][ksize][ksize], i.e. a [N = C, K = ksize^2] matrix; a_q NHWC as for
+ * FF_CONV2D; w_q int8 [C, ff_pitch(ksize^2)].
  * batch = samples in ONE pass (positive or negative).
  * relu: 1 = activities are ReLU(s*acc) (the default reading), 0 = identity.
  * l2norm_out: 1 = the input handed to the next layer is y / ||y||_2 per sample. */
@@ -302,7 +305,8 @@ enum {
     FF_K_SMALL = 7,      /* fills, goodness/loss, look-ahead                  */
     FF_K_IM2COL = 8,     /* patch matrices of convolution layers              */
     FF_K_RESIDUAL = 9,   /* block output and its goodness (residual layers)   */
-    FF_K_COUNT = 10
+    FF_K_DWCONV = 10,    /* depthwise convolution: forward and weight gradient */
+    FF_K_COUNT = 11
 };
 #define FF_TIMING_MAX_RECORDS 16384
 ff_status ff_timing_enable(int32_t class_mask);

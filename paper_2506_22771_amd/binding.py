@@ -116,7 +116,7 @@ def _chk(st: int, what: str) -> None:
 
 def layer_desc(layer, batch: int) -> LayerDesc:
     """From a workloads.Layer (or any object with the same attributes)."""
-    kind = 0 if layer.kind == "dense" else 1
+    kind = {"dense": 0, "conv": 1, "dwconv": 2}[layer.kind]
     return LayerDesc(kind, batch, layer.in_features, layer.out_features, layer.H, layer.W, layer.C_in, layer.C_out,
                      layer.ksize, layer.stride, layer.pad, layer.relu, layer.l2norm_out,
                      getattr(layer, "input_back", 0), {"ff": 0, "proj": 1}[getattr(layer, "role", "ff")],
@@ -233,7 +233,7 @@ def ff_train_step_at(net: Net, x_pos, x_neg, theta, lam, lr, seed, step_dev, adv
 
 
 KERNEL_CLASSES = ("gemm_fwd", "gemm_dw", "quant_act", "quant_grad", "quant_w", "update", "absmax", "small", "im2col",
-                  "residual")
+                  "residual", "dwconv")
 
 
 def ff_timing_enable(on, classes: Optional[Sequence[str]] = None) -> None:

@@ -38,8 +38,9 @@ static ff_status layer_dims(const ff_layer_desc* L, Dims* d)
         d->rps = 1;
         d->in_rows = L->batch;
         d->in_cols = L->in_features;
-    } else if (L->kind == FF_CONV2D) {
+    } else if (L->kind == FF_CONV2D || L->kind == FF_DWCONV2D) {
         if (L->H <= 0 || L->W <= 0 || L->C_in <= 0 || L->C_out <= 0) return FF_ERR_SHAPE;
+        if (L->kind == FF_DWCONV2D && (L->C_in != L->C_out || L->ksize != 3)) return FF_ERR_SHAPE;
         if ((L->ksize != 1 && L->ksize != 3) || (L->stride != 1 && L->stride != 2) || L->pad != L->ksize / 2)
             return FF_ERR_SHAPE;
         ConvGeom& g = d->g;
@@ -54,11 +55,11 @@ static ff_status layer_dims(const ff_layer_desc* L, Dims* d)
         g.Wo = (L->W + 2 * L->pad - L->ksize) / L->stride + 1;
         d->rps = (int64_t)g.Ho * g.Wo;
         d->M = d->B * d->rps;
-        d->K = (int64_t)L->ksize * L->ksize * L->C_in;
+        d->K = L->kind == FF_DWCONV2D ? (int64_t)L->ksize * L->ksize : (int64_t)L->ksize * L->ksize * L->C_in;
         d->N = L->C_out;
         d->in_rows = d->B * L->H * L->W;
         d->in_cols = L->C_in;
-        d->implicit = (L->C_in & 15) == 0;
+        d->implicit = L->kind == FF_CONV2D && (L->C_in & 15) == 0;
         if (d->in_rows * g.cpitch >= (int64_t(1) << 31) || d->M >= (int64_t(1) << 31)) return FF_ERR_UNSUPPORTED;
     } else {
         return FF_ERR_INVALID_ARG;
@@ -99,13 +100,14 @@ static int32_t goodness_shift(int64_t K, int64_t terms)
 // weight-gradient chunk (conv only).  `part`: partial accumulators of a split weight-gradient reduction.
 static size_t layer_col_bytes(const Dims& d)
 {
-    if (d.kind != FF_CONV2D) return 0;
+    if (d.kind != FF_CONV2D) return 0;   // dense and depthwise layers need no patch matrix
     const size_t fwd = d.implicit ? 0 : (size_t)(d.M * pitch8(d.K));
     const size_t bwd = (size_t)(d.K * pitch8(d.chunk_b * d.rps));
     return align_up(fwd > bwd ? fwd : bwd, 256);
 }
 static size_t layer_part_bytes(const Dims& d, int nb)
 {
+    if (d.kind == FF_DWCONV2D) return 0;
     const GemmPlan p = gemm_plan(d.N, d.K, min(d.M, d.chunk_b * d.rps), nb, true);
     if (p.splits <= 1) return 0;
     return align_up((size_t)p.splits * (size_t)(d.N * pitch32(d.K)) * sizeof(int32_t), 256);
@@ -162,13 +164,13 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
         if (dd.src >= 0) {
             const Dims& p = w->d[dd.src];
             if (p.role == FF_ROLE_PROJECTION) return FF_ERR_SHAPE;   // a projection has no output of its own
-            if (p.kind != d.kind) return FF_ERR_UNSUPPORTED;  // no dense <-> conv transitions in this build
+            if ((p.kind == FF_DENSE) != (d.kind == FF_DENSE)) return FF_ERR_UNSUPPORTED;  // no dense <-> conv transitions in this build
             if (d.kind == FF_DENSE && d.K != p.N) return FF_ERR_SHAPE;
-            if (d.kind == FF_CONV2D && (d.g.Cin != p.N || d.g.H != p.g.Ho || d.g.W != p.g.Wo)) return FF_ERR_SHAPE;
+            if (d.kind != FF_DENSE && (d.g.Cin != p.N || d.g.H != p.g.Ho || d.g.W != p.g.Wo)) return FF_ERR_SHAPE;
         }
         if (L.role == FF_ROLE_PROJECTION) {
             // [projection, conv1 (reads the same input), conv2 (adds the projection)]
-            if (d.kind != FF_CONV2D || L.relu || L.l2norm_out || L.skip != FF_SKIP_NONE) return FF_ERR_INVALID_ARG;
+            if (d.kind != FF_CONV2D || L.relu || L.l2norm_out || L.skip != FF_SKIP_NONE) return FF_ERR_INVALID_ARG;   // (a depthwise projection is not a case)
             if (i + 2 >= w->k || net->layers[i + 1].input_back != 1 || net->layers[i + 1].role != FF_ROLE_LAYER ||
                 net->layers[i + 2].skip != FF_SKIP_PROJECTION)
                 return FF_ERR_SHAPE;
@@ -210,7 +212,7 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
     for (int i = 0; i < w->k; ++i) {
         const Dims& d = w->d[i];
         if (d.kind == FF_DENSE) aq_dense = max(aq_dense, (size_t)(d.in_rows * pitch8(d.in_cols)));
-        gy = max(gy, (size_t)(d.N * pitch8(d.M)));
+        gy = max(gy, d.kind == FF_DWCONV2D ? (size_t)(d.M * pitch8(d.N)) : (size_t)(d.N * pitch8(d.M)));
         dw = max(dw, (size_t)(d.N * pitch32(d.K)) * sizeof(int32_t));
         col = max(col, layer_col_bytes(d));
         part = max(part, layer_part_bytes(d, 2));
@@ -302,6 +304,26 @@ static ff_status run_forward(const Dims& d, int relu, const int8_t* aq, int64_t 
                              int64_t st_acc, unsigned long long* gsum, int32_t* vmax, int64_t st_g, int8_t* col,
                              int64_t st_col, int nb, hipStream_t s)
 {
+    if (d.kind == FF_DWCONV2D) {
+        DwArgs p;
+        memset(&p, 0, sizeof(p));
+        p.a = aq;
+        p.st_a = st_aq;
+        p.w_q = w_q;
+        p.g = d.g;
+        p.B = (int32_t)d.B;
+        p.acc = acc;
+        p.ldacc = pitch32(d.N);
+        p.st_acc = st_acc;
+        p.gsum = gsum;
+        p.vmax = vmax;
+        p.st_g = st_g;
+        p.relu = relu;
+        p.rshift = goodness_shift(d.K, d.rps * d.N);
+        p.nb = nb;
+        HIPCHK_T(FF_K_DWCONV, launch_dwconv_forward(p, s));
+        return FF_OK;
+    }
     GemmArgs g;
     memset(&g, 0, sizeof(g));
     g.Q = w_q;
@@ -374,6 +396,27 @@ static ff_status run_wgrad(const Dims& d, const int8_t* gy_t, int64_t st_gy, con
     for (int c = 0; c < d.n_chunks; ++c) {
         const int64_t b0 = c * d.chunk_b, b1 = min(d.B, b0 + d.chunk_b);
         const int64_t m0 = b0 * d.rps, mc = (b1 - b0) * d.rps;
+        if (d.kind == FF_DWCONV2D) {
+            // gy_t holds the ROW-MAJOR int8 gradient [M, pitch(C)] for this layer kind
+            for (int z = 0; z < nb; ++z)
+                HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(dw + z * st_dw + c * dw_elems), d.N * pitch32(d.K), 0u, s));
+            DwArgs p;
+            memset(&p, 0, sizeof(p));
+            p.a = aqt;
+            p.st_a = st_aqt;
+            p.g = d.g;
+            p.B = (int32_t)d.B;
+            p.gy = gy_t;
+            p.ldg = pitch8(d.N);
+            p.st_gy = st_gy;
+            p.dw = dw + c * dw_elems;
+            p.st_dw = st_dw;
+            p.b0 = (int32_t)b0;
+            p.b1 = (int32_t)b1;
+            p.nb = nb;
+            HIPCHK_T(FF_K_DWCONV, launch_dwconv_wgrad(p, s));
+            continue;
+        }
         GemmArgs g;
         memset(&g, 0, sizeof(g));
         g.P = gy_t + m0;
@@ -676,8 +719,13 @@ ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc
     a.key = make_sr_key(seed, stream_tag);
     a.rows = d.M;
     a.cols = d.N;
-    a.q_t = gy_q_t;
-    a.ldqt = pitch8(d.M);
+    if (d.kind == FF_DWCONV2D) {   // the depthwise weight gradient reads the gradient row-major
+        a.q = gy_q_t;
+        a.ldq = pitch8(d.N);
+    } else {
+        a.q_t = gy_q_t;
+        a.ldqt = pitch8(d.M);
+    }
     a.scale = s_g;
     a.nb = 1;
     HIPCHK_T(FF_K_QUANT_GRAD, launch_quantize(QSRC_GRAD, a, s));
@@ -1043,9 +1091,15 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         a.tag_kind = FF_KIND_GRAD;
         a.rows = d.M;
         a.cols = d.N;
-        a.q_t = (int8_t*)(base + w.off_gy);
-        a.st_qt = (int64_t)w.st_gy;
-        a.ldqt = pitch8(d.M);
+        if (d.kind == FF_DWCONV2D) {   // the depthwise weight gradient reads the gradient row-major
+            a.q = (int8_t*)(base + w.off_gy);
+            a.st_q = (int64_t)w.st_gy;
+            a.ldq = pitch8(d.N);
+        } else {
+            a.q_t = (int8_t*)(base + w.off_gy);
+            a.st_qt = (int64_t)w.st_gy;
+            a.ldqt = pitch8(d.M);
+        }
         a.scale = s_g + 2 * i;
         a.st_scale = 1;
         a.nb = 2;

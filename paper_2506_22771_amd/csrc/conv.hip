@@ -215,4 +215,175 @@ hipError_t launch_im2col(const Im2colArgs& p, bool transposed, hipStream_t s)
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------------------
+// Depthwise convolution.  Forward: a thread owns four channels of one output pixel (nine 4-byte taps, 16-byte
+// store of the accumulators); blockIdx.y = sample, so the per-sample goodness sums / maxima are reduced in the
+// workgroup and leave as one atomic each.  HBM-bound on the int32 output (4 bytes written per input byte).
+// ------------------------------------------------------------------------------------------------------------
+constexpr int DW_VPT = 4;
+
+__device__ __forceinline__ unsigned long long dw_wave_sum_u64(unsigned long long v)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned lo = (unsigned)__shfl_xor((int)(unsigned)v, d), hi = (unsigned)__shfl_xor((int)(unsigned)(v >> 32), d);
+        v += ((unsigned long long)hi << 32) | lo;
+    }
+    return v;
+}
+
+__global__ __launch_bounds__(256) void k_dwconv_forward(DwArgs p)
+{
+    const ConvGeom& g = p.g;
+    const int z = blockIdx.z, b = blockIdx.y;
+    const int C = g.Cin, C4 = (C + 3) >> 2;
+    const int hw = g.Ho * g.Wo;
+    const int tv = hw * C4;
+    const int8_t* __restrict__ a = p.a + z * p.st_a;
+    unsigned long long sq = 0;
+    int vm = 0;
+#pragma unroll
+    for (int it = 0; it < DW_VPT; ++it) {
+        const int v = ((int)blockIdx.x * DW_VPT + it) * 256 + (int)threadIdx.x;
+        if (v >= tv) break;
+        const int pix = v / C4, c0 = (v - pix * C4) * 4;
+        const int ho = pix / g.Wo, wo = pix - ho * g.Wo;
+        int w[4][9];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint4 wr = make_uint4(0u, 0u, 0u, 0u);
+            if (c0 + e < C) wr = *(const uint4*)(p.w_q + (int64_t)(c0 + e) * 16);
+            const uint32_t ww[3] = {wr.x, wr.y, wr.z};
+#pragma unroll
+            for (int t = 0; t < 9; ++t) w[e][t] = (int)(int8_t)(ww[t >> 2] >> (8 * (t & 3)));
+        }
+        int acc[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+            for (int kw = 0; kw < 3; ++kw) {
+                const int hi = ho * g.stride + kh - g.pad, wi = wo * g.stride + kw - g.pad;
+                if ((unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W) {
+                    const uint32_t x = *(const uint32_t*)(a + (((int64_t)b * g.H + hi) * g.W + wi) * g.cpitch + c0);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[e] += (int)(int8_t)(x >> (8 * e)) * w[e][kh * 3 + kw];
+                }
+            }
+        *(int4*)(p.acc + z * p.st_acc + ((int64_t)b * hw + pix) * p.ldacc + c0) = make_int4(acc[0], acc[1], acc[2], acc[3]);
+        if (p.gsum) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                int y = acc[e];                   // channels beyond C read zero inputs and zero weights: y == 0
+                if (p.relu) y = max(y, 0);
+                const long long yl = (long long)y;
+                sq += ((unsigned long long)(yl * yl)) >> p.rshift;
+                vm = max(vm, y < 0 ? -y : y);
+            }
+        }
+    }
+    if (p.gsum) {
+        __shared__ unsigned long long rs[4];
+        __shared__ int rm[4];
+        sq = dw_wave_sum_u64(sq);
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) vm = max(vm, __shfl_xor(vm, d));
+        if ((threadIdx.x & 63) == 0) { rs[threadIdx.x >> 6] = sq; rm[threadIdx.x >> 6] = vm; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const unsigned long long t = rs[0] + rs[1] + rs[2] + rs[3];
+            const int m = max(max(rm[0], rm[1]), max(rm[2], rm[3]));
+            if (t) atomicAdd(p.gsum + z * p.st_g + b, t);
+            if (m) atomicMax(p.vmax + z * p.st_g + b, m);
+        }
+    }
+}
+
+hipError_t launch_dwconv_forward(const DwArgs& p, hipStream_t s)
+{
+    const ConvGeom& g = p.g;
+    if (p.B <= 0) return hipSuccess;
+    if (g.ks != 3 || p.B > 65535) return hipErrorInvalidValue;
+    const int64_t tv = (int64_t)g.Ho * g.Wo * ((g.Cin + 3) >> 2);
+    if (tv > (int64_t(1) << 28)) return hipErrorInvalidValue;
+    const unsigned bx = (unsigned)((tv + 256 * DW_VPT - 1) / (256 * DW_VPT));
+    hipLaunchKernelGGL(k_dwconv_forward, dim3(bx, (unsigned)p.B, (unsigned)p.nb), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+// Weight gradient of a depthwise convolution: dw[c][tap] = sum over output pixels of gy[m][c] * a[pixel(m) + tap][c].
+// A workgroup owns DW_ROWS output pixels (of the samples [b0, b1)) and a group of up to 64 channels; a thread owns four
+// channels and every (256 / quads)-th row, keeps 36 int32 partial sums, adds them to LDS accumulators with LDS atomics,
+// and the workgroup adds those to dw with integer atomics (exact and order-free; dw must be zero on entry).
+constexpr int DW_ROWS = 2048;
+
+__global__ __launch_bounds__(256) void k_dwconv_wgrad(DwArgs p)
+{
+    const ConvGeom& g = p.g;
+    const int z = blockIdx.z;
+    const int C = g.Cin;
+    const int cg0 = blockIdx.y * 64;
+    const int nq = min(16, (C - cg0 + 3) >> 2);          // channel quads of this workgroup
+    const int lanes = 256 / nq;                          // row lanes
+    const int q = threadIdx.x % nq, rl = threadIdx.x / nq;
+    const int c0 = cg0 + 4 * q;
+    const int hw = g.Ho * g.Wo;
+    const int64_t m0 = (int64_t)p.b0 * hw, m1 = (int64_t)p.b1 * hw;
+    const int8_t* __restrict__ a = p.a + z * p.st_a;
+    const int8_t* __restrict__ gy = p.gy + z * p.st_gy;
+    __shared__ int lacc[64 * 9];
+    for (int e = threadIdx.x; e < 64 * 9; e += 256) lacc[e] = 0;
+    __syncthreads();
+    int part[4][9];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int t = 0; t < 9; ++t) part[e][t] = 0;
+    if (rl < lanes) {
+        const int64_t r0 = m0 + (int64_t)blockIdx.x * DW_ROWS;
+        const int64_t r1 = min(m1, r0 + DW_ROWS);
+        for (int64_t m = r0 + rl; m < r1; m += lanes) {
+            const int b = (int)(m / hw), pix = (int)(m - (int64_t)b * hw);
+            const int ho = pix / g.Wo, wo = pix - ho * g.Wo;
+            const uint32_t gw = *(const uint32_t*)(gy + m * p.ldg + c0);
+            if (gw == 0u) continue;   // a rectified gradient is zero wherever the activity is
+            int gv[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) gv[e] = (int)(int8_t)(gw >> (8 * e));
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) {
+                    const int hi = ho * g.stride + kh - g.pad, wi = wo * g.stride + kw - g.pad;
+                    if ((unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W) {
+                        const uint32_t x = *(const uint32_t*)(a + (((int64_t)b * g.H + hi) * g.W + wi) * g.cpitch + c0);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) part[e][kh * 3 + kw] += gv[e] * (int)(int8_t)(x >> (8 * e));
+                    }
+                }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+                if (part[e][t]) atomicAdd(&lacc[(4 * q + e) * 9 + t], part[e][t]);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < 64 * 9; e += 256) {
+        const int c = cg0 + e / 9, t = e - (e / 9) * 9;
+        if (c < C && lacc[e]) atomicAdd(p.dw + z * p.st_dw + (int64_t)c * 12 + t, lacc[e]);
+    }
+}
+
+hipError_t launch_dwconv_wgrad(const DwArgs& p, hipStream_t s)
+{
+    const ConvGeom& g = p.g;
+    const int64_t rows = (int64_t)(p.b1 - p.b0) * g.Ho * g.Wo;
+    if (rows <= 0) return hipSuccess;
+    if (g.ks != 3) return hipErrorInvalidValue;
+    const int64_t bx = (rows + DW_ROWS - 1) / DW_ROWS;
+    if (bx > 0x7FFFFFFF || (g.Cin + 63) / 64 > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_dwconv_wgrad, dim3((unsigned)bx, (unsigned)((g.Cin + 63) / 64), (unsigned)p.nb), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
 }  // namespace ffi

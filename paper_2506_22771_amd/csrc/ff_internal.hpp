@@ -236,6 +236,31 @@ struct Im2colArgs {
     int32_t wtaps_only;
 };
 hipError_t launch_im2col(const Im2colArgs& p, bool transposed, hipStream_t s);
+// ---- depthwise convolution (conv.hip): one ks x ks filter per channel, HBM-bound -----------------------------
+struct DwArgs {
+    const int8_t* a;    // NHWC int8 [B, H, W, cpitch]
+    int64_t st_a;
+    const int8_t* w_q;  // [C, 16]: nine taps (kh, kw) per channel, zero pad bytes
+    ConvGeom g;         // Cin = C
+    int32_t B;
+    // forward
+    int32_t* acc;       // [B*Ho*Wo, ldacc]
+    int64_t ldacc, st_acc;
+    unsigned long long* gsum;  // [B] per pass (stride st_g), zeroed; may be null
+    int32_t* vmax;
+    int64_t st_g;
+    int32_t relu, rshift;
+    // weight gradient over the samples [b0, b1)
+    const int8_t* gy;   // row-major int8 local gradient [B*Ho*Wo, ldg]
+    int64_t ldg, st_gy;
+    int32_t* dw;        // [C, 12] int32, zeroed
+    int64_t st_dw;
+    int32_t b0, b1;
+    int32_t nb;
+};
+hipError_t launch_dwconv_forward(const DwArgs& p, hipStream_t s);
+hipError_t launch_dwconv_wgrad(const DwArgs& p, hipStream_t s);
+
 // true when launch_im2col can write the planes for this geometry (LDS slab fits, grid limits)
 bool im2col_planes_ok(const ConvGeom& g, int64_t nbatch_times_nb);
 

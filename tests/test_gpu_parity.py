@@ -267,6 +267,46 @@ def test_conv_forward_and_backward(ff, B, H, W, Cin, Cout, ks, stride):
     np.testing.assert_array_equal(dw.cpu().numpy()[:, :K], dw_ref.reshape(Cout, K))
 
 
+@pytest.mark.parametrize("B,H,W,C,stride", [(3, 8, 12, 16, 1), (5, 9, 7, 20, 2), (2, 32, 32, 96, 1), (4, 16, 16, 6, 2),
+                                              (1, 4, 4, 130, 1)])
+def test_depthwise_forward_and_backward(ff, B, H, W, C, stride):
+    """Depthwise 3x3 layers through the single-operation entry points: accumulators, integer goodness sums and
+    maxima, the row-major int8 local gradient and the [C, 9] weight gradient."""
+    rng = np.random.default_rng(B * 1000 + C)
+    layer = Layer("dwconv", H=H, W=W, C_in=C, C_out=C, ksize=3, stride=stride, pad=1)
+    desc = ff.layer_desc(layer, B)
+    a_q = rng.integers(-127, 128, (B, H, W, C)).astype(np.int8)
+    w = (rng.standard_normal((C, 3, 3)) * 0.2).astype(np.float32)
+    w_q, s_w = O.quantize(w, 0)
+    s_a = np.float32(0.0041)
+    M = B * layer.rows_per_sample
+    acc_ref = O.dwconv_forward(a_q, w_q, stride, 1)
+    r = O.goodness_shift(9, layer.terms_per_sample)
+    assert ff.ff_goodness_shift(desc) == r
+    g_ref = O.goodness(acc_ref, 1, r, s_a, s_w)
+    ws = workspace(ff.ff_layer_workspace_bytes(desc))
+    d_aq = dev(pad_nhwc(a_q))
+    acc = empty32(M, C)
+    gsum = torch.zeros((B,), dtype=torch.int64, device="cuda")
+    vmax = torch.zeros((B,), dtype=torch.int32, device="cuda")
+    ff.ff_layer_forward(desc, d_aq, dev(pad8(w_q.reshape(C, 9))), acc, gsum, vmax, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(acc.cpu().numpy()[:, :C], acc_ref.reshape(M, C))
+    np.testing.assert_array_equal(gsum.cpu().numpy().view(np.uint64), g_ref["g_int"])
+    np.testing.assert_array_equal(vmax.cpu().numpy(), g_ref["vmax"])
+    ct = (rng.standard_normal(B) * 0.3).astype(np.float32)
+    g = O.local_grad(acc_ref, 1, s_a, s_w, ct)
+    gq_ref, sg_ref = O.quantize(g, 1, 4, 55)
+    dw_ref = O.dwconv_wgrad(gq_ref, a_q, 3, stride, 1, 0, B)
+    gy, s_g, dw = empty8(M, C), scalar(), empty32(C, 9)
+    ff.ff_layer_backward_local(desc, dev(pad32(acc_ref.reshape(M, C))), dev(g_ref["vmax"]), dev(np.array([s_a])),
+                               dev(np.array([s_w])), dev(ct), 1, 4, 55, d_aq, gy, s_g, dw, ws)
+    torch.cuda.synchronize()
+    assert s_g.item() == sg_ref
+    check_q(gy, gq_ref.reshape(M, C), "depthwise gy_q (row-major)")
+    np.testing.assert_array_equal(dw.cpu().numpy()[:, :9], dw_ref.reshape(C, 9))
+
+
 def test_conv_weight_gradient_chunks(ff):
     """A reduction over more than 133144 output pixels is split into sample blocks with separate int32
     accumulators (here 128 + 12 images of 32x32), combined by ff_layer_update in chunk order."""
@@ -342,7 +382,7 @@ def _run_steps(ff, wl, n_steps, lam=None):
 
 
 @pytest.mark.parametrize("name,steps", [("tiny", 3), ("tiny_l2", 3), ("cfg1", 3), ("cfg2", 1), ("tiny_conv", 3),
-                                        ("tiny_conv16", 3), ("tiny_conv_s2", 3), ("tiny_res", 3)])
+                                        ("tiny_conv16", 3), ("tiny_conv_s2", 3), ("tiny_res", 3), ("tiny_dw", 3)])
 def test_train_step(ff, name, steps):
     _run_steps(ff, workload(name), steps)
 
@@ -369,6 +409,14 @@ def test_train_step_cfg4_full_size(ff):
     """The ResNet-18-shaped stack with its residual additions and the three 1x1 projections (20 convolutions,
     11.16 M weights, 256+256 images) at its full size."""
     _run_steps(ff, workload("cfg4"), 1)
+
+
+@pytest.mark.slow
+@pytest.mark.timeout(1500)
+def test_train_step_mbv2_like_full_size(ff):
+    """A 1x1-heavy stack with depthwise 3x3 convolutions (five inverted bottlenecks on 32x32 images, 256+256
+    samples): depthwise layers with two weight-gradient chunks, a stride-2 depthwise layer, 16 layers of look-ahead."""
+    _run_steps(ff, workload("mbv2_like"), 1)
 
 
 @pytest.mark.slow

@@ -220,7 +220,7 @@ hipError_t launch_im2col(const Im2colArgs& p, bool transposed, hipStream_t s)
 // store of the accumulators); blockIdx.y = sample, so the per-sample goodness sums / maxima are reduced in the
 // workgroup and leave as one atomic each.  HBM-bound on the int32 output (4 bytes written per input byte).
 // ------------------------------------------------------------------------------------------------------------
-constexpr int DW_VPT = 4;
+constexpr int DW_PIX = 8;   // output pixels per thread
 
 __device__ __forceinline__ unsigned long long dw_wave_sum_u64(unsigned long long v)
 {
@@ -232,52 +232,83 @@ __device__ __forceinline__ unsigned long long dw_wave_sum_u64(unsigned long long
     return v;
 }
 
-__global__ __launch_bounds__(256) void k_dwconv_forward(DwArgs p)
+// blockIdx.x = share of the sample's output pixels, blockIdx.y = sample, blockIdx.z = pass * channel groups + group.
+// A thread keeps the 36 weights of its four channels in registers and walks over DW_PIX pixels, 256 / quads apart.
+__global__ __launch_bounds__(256) void k_dwconv_forward(DwArgs p, int cgroups)
 {
     const ConvGeom& g = p.g;
-    const int z = blockIdx.z, b = blockIdx.y;
-    const int C = g.Cin, C4 = (C + 3) >> 2;
+    const int z = blockIdx.z / cgroups, cg0 = (blockIdx.z - z * cgroups) * 64;
+    const int b = blockIdx.y;
+    const int C = g.Cin;
+    const int nq = min(16, (C - cg0 + 3) >> 2);          // channel quads of this workgroup
+    const int lanes = 256 / nq;                          // pixel lanes
+    const int q = threadIdx.x % nq, pl = threadIdx.x / nq;
+    const int c0 = cg0 + 4 * q;
     const int hw = g.Ho * g.Wo;
-    const int tv = hw * C4;
     const int8_t* __restrict__ a = p.a + z * p.st_a;
     unsigned long long sq = 0;
     int vm = 0;
-#pragma unroll
-    for (int it = 0; it < DW_VPT; ++it) {
-        const int v = ((int)blockIdx.x * DW_VPT + it) * 256 + (int)threadIdx.x;
-        if (v >= tv) break;
-        const int pix = v / C4, c0 = (v - pix * C4) * 4;
-        const int ho = pix / g.Wo, wo = pix - ho * g.Wo;
-        int w[4][9];
+    if (pl < lanes) {
+        // the nine taps of a channel are nine consecutive bytes of its weight row: three packed words per channel
+        uint32_t w[4][3];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             uint4 wr = make_uint4(0u, 0u, 0u, 0u);
             if (c0 + e < C) wr = *(const uint4*)(p.w_q + (int64_t)(c0 + e) * 16);
-            const uint32_t ww[3] = {wr.x, wr.y, wr.z};
-#pragma unroll
-            for (int t = 0; t < 9; ++t) w[e][t] = (int)(int8_t)(ww[t >> 2] >> (8 * (t & 3)));
+            w[e][0] = wr.x; w[e][1] = wr.y; w[e][2] = wr.z;
         }
-        int acc[4] = {0, 0, 0, 0};
+        const int pix0 = (int)blockIdx.x * lanes * DW_PIX + pl;
+#pragma unroll 2
+        for (int it = 0; it < DW_PIX; ++it) {
+            const int pix = pix0 + it * lanes;
+            if (pix >= hw) break;
+            const int ho = pix / g.Wo, wo = pix - ho * g.Wo;
+            uint32_t x[9];   // tap words: byte e = channel c0 + e
 #pragma unroll
-        for (int kh = 0; kh < 3; ++kh)
+            for (int kh = 0; kh < 3; ++kh)
 #pragma unroll
-            for (int kw = 0; kw < 3; ++kw) {
-                const int hi = ho * g.stride + kh - g.pad, wi = wo * g.stride + kw - g.pad;
-                if ((unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W) {
-                    const uint32_t x = *(const uint32_t*)(a + (((int64_t)b * g.H + hi) * g.W + wi) * g.cpitch + c0);
+                for (int kw = 0; kw < 3; ++kw) {
+                    const int hi = ho * g.stride + kh - g.pad, wi = wo * g.stride + kw - g.pad;
+                    x[kh * 3 + kw] = ((unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W)
+                                         ? *(const uint32_t*)(a + (((int64_t)b * g.H + hi) * g.W + wi) * g.cpitch + c0)
+                                         : 0u;
+                }
+            // two 4x4 byte transposes turn (tap words x channel bytes) into (channel words x tap bytes), which is
+            // the operand order of the packed int8 dot product
+            int acc[4];
+            {
+                uint32_t lo[4], hi4[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[e] += (int)(int8_t)(x >> (8 * e)) * w[e][kh * 3 + kw];
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t* xs = x + 4 * h;
+                    const uint32_t t0 = __builtin_amdgcn_perm(xs[1], xs[0], 0x05010400u);
+                    const uint32_t t1 = __builtin_amdgcn_perm(xs[1], xs[0], 0x07030602u);
+                    const uint32_t t2 = __builtin_amdgcn_perm(xs[3], xs[2], 0x05010400u);
+                    const uint32_t t3 = __builtin_amdgcn_perm(xs[3], xs[2], 0x07030602u);
+                    uint32_t* o = h ? hi4 : lo;
+                    o[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
+                    o[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+                    o[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
+                    o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    int sacc = (int)(int8_t)(x[8] >> (8 * e)) * (int)(int8_t)(w[e][2] & 0xFFu);
+                    sacc = __builtin_amdgcn_sdot4((int)lo[e], (int)w[e][0], sacc, false);
+                    sacc = __builtin_amdgcn_sdot4((int)hi4[e], (int)w[e][1], sacc, false);
+                    acc[e] = sacc;
                 }
             }
-        *(int4*)(p.acc + z * p.st_acc + ((int64_t)b * hw + pix) * p.ldacc + c0) = make_int4(acc[0], acc[1], acc[2], acc[3]);
-        if (p.gsum) {
+            *(int4*)(p.acc + z * p.st_acc + ((int64_t)b * hw + pix) * p.ldacc + c0) = make_int4(acc[0], acc[1], acc[2], acc[3]);
+            if (p.gsum) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                int y = acc[e];                   // channels beyond C read zero inputs and zero weights: y == 0
-                if (p.relu) y = max(y, 0);
-                const long long yl = (long long)y;
-                sq += ((unsigned long long)(yl * yl)) >> p.rshift;
-                vm = max(vm, y < 0 ? -y : y);
+                for (int e = 0; e < 4; ++e) {
+                    int y = acc[e];                   // channels beyond C read zero inputs and zero weights: y == 0
+                    if (p.relu) y = max(y, 0);
+                    const long long yl = (long long)y;
+                    sq += ((unsigned long long)(yl * yl)) >> p.rshift;
+                    vm = max(vm, y < 0 ? -y : y);
+                }
             }
         }
     }
@@ -302,11 +333,13 @@ hipError_t launch_dwconv_forward(const DwArgs& p, hipStream_t s)
 {
     const ConvGeom& g = p.g;
     if (p.B <= 0) return hipSuccess;
-    if (g.ks != 3 || p.B > 65535) return hipErrorInvalidValue;
-    const int64_t tv = (int64_t)g.Ho * g.Wo * ((g.Cin + 3) >> 2);
-    if (tv > (int64_t(1) << 28)) return hipErrorInvalidValue;
-    const unsigned bx = (unsigned)((tv + 256 * DW_VPT - 1) / (256 * DW_VPT));
-    hipLaunchKernelGGL(k_dwconv_forward, dim3(bx, (unsigned)p.B, (unsigned)p.nb), dim3(256), 0, s, p);
+    const int cgroups = (g.Cin + 63) / 64;
+    if (g.ks != 3 || p.B > 65535 || (int64_t)cgroups * p.nb > 65535) return hipErrorInvalidValue;
+    // pixels per workgroup depend on the group's quad count; size the grid for full groups (16 quads, 16 lanes),
+    // narrower groups have more lanes and finish their share early
+    const int64_t hw = (int64_t)g.Ho * g.Wo;
+    const unsigned bx = (unsigned)((hw + 16 * DW_PIX - 1) / (16 * DW_PIX));
+    hipLaunchKernelGGL(k_dwconv_forward, dim3(bx, (unsigned)p.B, (unsigned)(cgroups * p.nb)), dim3(256), 0, s, p, cgroups);
     return hipGetLastError();
 }
 
@@ -314,7 +347,7 @@ hipError_t launch_dwconv_forward(const DwArgs& p, hipStream_t s)
 // A workgroup owns DW_ROWS output pixels (of the samples [b0, b1)) and a group of up to 64 channels; a thread owns four
 // channels and every (256 / quads)-th row, keeps 36 int32 partial sums, adds them to LDS accumulators with LDS atomics,
 // and the workgroup adds those to dw with integer atomics (exact and order-free; dw must be zero on entry).
-constexpr int DW_ROWS = 2048;
+constexpr int DW_ROWS = 512;
 
 __global__ __launch_bounds__(256) void k_dwconv_wgrad(DwArgs p)
 {

@@ -226,6 +226,9 @@ ff_status ff_lookahead(const float* coeff, int32_t n_layers, int64_t batch, floa
  *   dw_acc       int32 [N, ff_pitch32(K)]: dw_acc[n][k] = sum_m gy_q[m][n] * a_q[m][k]   (out)
  *   a_q_t        int8 [K, ff_pitch(M)]: the transposed copy ff_quantize / ff_layer_handoff wrote (in)
  *   dw_acc holds ff_layer_dw_chunks(layer) accumulators (1 unless M > 133144).
+ * Convolutions: a_q_t is the NHWC int8 layer input itself.  Depthwise layers (FF_DWCONV2D): gy_q_t receives the
+ * gradient ROW-MAJOR, int8 [M, ff_pitch(C)], and dw_acc is int32 [C, ff_pitch32(9)] with
+ * dw_acc[c][kh*3+kw] = sum over output pixels of gy_q[m][c] * a_q[pixel(m) + tap][c].
  * ws: >= ff_layer_workspace_bytes(layer).
  * ------------------------------------------------------------------------------------------- */
 ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc, const int32_t* vmax,

@@ -98,7 +98,10 @@ typedef struct {
 enum { FF_ROLE_LAYER = 0, FF_ROLE_PROJECTION = 1 };
 enum { FF_SKIP_NONE = 0, FF_SKIP_IDENTITY = 1, FF_SKIP_PROJECTION = 2 };
 
-/* A stack of layers trained together by ff_train_step. [host] */
+/* A stack of layers trained together by ff_train_step. [host]
+ * Consecutive layers must fit: dense K = previous N; convolution H, W, C_in = previous H_out, W_out, C_out; a dense
+ * layer after a convolution reads its NHWC output flattened (in_features = H_out * W_out * C_out, C_out % 4 == 0).
+ * A convolution after a dense layer is FF_ERR_UNSUPPORTED. */
 typedef struct {
     int32_t n_layers;
     int32_t batch;               /* samples per pass; must equal every layer's batch */

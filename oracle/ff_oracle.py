@@ -361,6 +361,8 @@ def train_step(layers, w_master: List[np.ndarray], x_pos: np.ndarray, x_neg: np.
         for i, layer in enumerate(layers):
             src = i - 1 - _layer_attr(layer, "input_back", 0)
             a = np.ascontiguousarray(x if src < 0 else outs[src], dtype=np.float32)
+            if layer.kind == "dense" and a.ndim > 2:
+                a = a.reshape(B, -1)     # flatten: NHWC order, the element order of the tensor itself
             tag = stream_tag(step, i, p, KIND_ACT)
             if role[i] == "proj":
                 a_q, s_a = quantize(a, ROUND_STOCHASTIC, seed, tag)

@@ -164,8 +164,15 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
         if (dd.src >= 0) {
             const Dims& p = w->d[dd.src];
             if (p.role == FF_ROLE_PROJECTION) return FF_ERR_SHAPE;   // a projection has no output of its own
-            if ((p.kind == FF_DENSE) != (d.kind == FF_DENSE)) return FF_ERR_UNSUPPORTED;  // no dense <-> conv transitions in this build
-            if (d.kind == FF_DENSE && d.K != p.N) return FF_ERR_SHAPE;
+            if (p.kind == FF_DENSE && d.kind != FF_DENSE) return FF_ERR_UNSUPPORTED;   // no dense -> conv transition
+            if (p.kind != FF_DENSE && d.kind == FF_DENSE) {
+                // flatten: the NHWC output [B, H_out, W_out, C] read as [B, H_out * W_out * C]; its int32 rows must be
+                // contiguous (C % 4 == 0)
+                if ((p.N & 3) != 0) return FF_ERR_UNSUPPORTED;
+                if (d.K != p.rps * p.N) return FF_ERR_SHAPE;
+            } else if (d.kind == FF_DENSE && d.K != p.N) {
+                return FF_ERR_SHAPE;
+            }
             if (d.kind != FF_DENSE && (d.g.Cin != p.N || d.g.H != p.g.Ho || d.g.W != p.g.Wo)) return FF_ERR_SHAPE;
         }
         if (L.role == FF_ROLE_PROJECTION) {
@@ -869,6 +876,10 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
             a.per_sample = goodness + (int64_t)j * 2 * B;
             a.st_per_sample = B;
             a.rows_per_sample = (int32_t)dp.rps;
+            if (dp.kind != FF_DENSE && dense) {   // flatten: one row of H_out * W_out * C contiguous accumulators per sample
+                a.ldacc = d.K;
+                a.rows_per_sample = 1;
+            }
             a.relu = Lp.relu ? 1 : 0;
             a.l2norm = Lp.l2norm_out ? 1 : 0;
         }

@@ -382,7 +382,7 @@ def _run_steps(ff, wl, n_steps, lam=None):
 
 
 @pytest.mark.parametrize("name,steps", [("tiny", 3), ("tiny_l2", 3), ("cfg1", 3), ("cfg2", 1), ("tiny_conv", 3),
-                                        ("tiny_conv16", 3), ("tiny_conv_s2", 3), ("tiny_res", 3), ("tiny_dw", 3)])
+                                        ("tiny_conv16", 3), ("tiny_conv_s2", 3), ("tiny_res", 3), ("tiny_dw", 3), ("tiny_cnn_head", 3)])
 def test_train_step(ff, name, steps):
     _run_steps(ff, workload(name), steps)
 

@@ -187,6 +187,10 @@ def workload(name: str) -> Workload:
                         256, "uniform_onehot", lam=0.05)
     if name == "tiny_dw":   # stem 3->16 at 8x12, two bottlenecks (the second with stride 2)
         return Workload("tiny_dw", bottleneck_stack(16, [(2, 16, 1), (3, 20, 2)], 8, 12), 5, "uniform_onehot", lam=0.05)
+    if name == "tiny_cnn_head":   # two 3x3 convolutions at 8x12, flatten, two dense layers (L2-normalised hand-off)
+        convs = conv_stack([3, 16, 16], 8, 12)
+        return Workload("tiny_cnn_head", convs + (Layer("dense", in_features=8 * 12 * 16, out_features=40, l2norm_out=1),
+                                                   Layer("dense", in_features=40, out_features=24)), 6, "uniform_onehot", lam=0.05)
     if name == "cfg5":   # large-GEMM stress
         return Workload("cfg5", mlp([4096, 4096, 4096], False), 8192, "normal", lam=0.05)
     if name == "tiny":   # ragged shapes spanning tile tails, for quick parity tests

@@ -429,17 +429,17 @@ __global__ __launch_bounds__(GL_THREADS) void k_goodness_loss(GoodnessArgs a)
         const float den = 1.0f + e;
         const float sig_big = 1.0f / den;
         const float sig_small = e / den;
-        float c;
-        double xd;
+        float c, xs;
         if (sign > 0) {
             c = -(x >= 0.0f ? sig_small : sig_big);
-            xd = -(double)x;
+            xs = -x;
         } else {
             c = (x >= 0.0f ? sig_big : sig_small);
-            xd = (double)x;
+            xs = x;
         }
         coeff[b] = c;
-        lsum += (xd > 0.0 ? xd : 0.0) + log1p(exp(-fabs(xd)));
+        // the reported loss (softplus) is not fed back into anything: fp32 terms, summed in fp64
+        lsum += (double)(fmaxf(xs, 0.0f) + log1pf(expf(-fabsf(xs))));
         if (a.next_amax_bits) {
             float ymax = (float)vmax[b] * s_y;
             if (a.l2norm) {

@@ -518,7 +518,7 @@ const char* ff_status_string(ff_status s)
     }
 }
 
-const char* ff_version(void) { return "ffint8 0.2 (gfx950)"; }
+const char* ff_version(void) { return "ffint8 0.3 (gfx950)"; }
 
 int32_t ff_goodness_shift(const ff_layer_desc* layer)
 {

@@ -288,7 +288,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
             for (int r = 0; r < 32 / RPI; ++r) {
                 const int row = r * RPI + rl;
                 const v4i v = *(const v4i*)(ebase + row * EROW + cc * 16);
-                *(v4i*)(ctile + (int64_t)row * a.ldc) = v;
+                __builtin_nontemporal_store(v, (v4i*)(ctile + (int64_t)row * a.ldc));
             }
             wave_lds_fence();
         }

@@ -134,6 +134,15 @@ hipError_t launch_absmax(const float* x, int64_t st_x, int nb, int64_t n, uint32
 // ------------------------------------------------------------------------------------------------
 // quantiser
 // ------------------------------------------------------------------------------------------------
+// 16-byte load of data that is not read again soon (source tensors of the quantisers): a streaming hint keeps it
+// from displacing what the next kernels will read
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld_stream16(const void* p)
+{
+    const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // one random word per element: two multiply / xor-shift stages over (low index word ^ key)
 __device__ __forceinline__ uint32_t sr_mix(uint32_t v)
 {
@@ -226,7 +235,7 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
                 const float* px = px0 + (int64_t)dr * a.cols;
                 if (VEC) {
                     if (in) {
-                        const uint4 f = *(const uint4*)px;
+                        const uint4 f = ld_stream16(px);
                         w0 = f.x; w1 = f.y; w2 = f.z; w3 = f.w;
                     }
                 } else if (in) {
@@ -236,7 +245,7 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
                     if (col + 3 < a.cols) w3 = __float_as_uint(px[3]);
                 }
             } else if (in) {
-                const uint4 f = *(const uint4*)(pa0 + (int64_t)dr * a.ldacc);  // pitch is a multiple of 4
+                const uint4 f = ld_stream16(pa0 + (int64_t)dr * a.ldacc);  // pitch is a multiple of 4
                 w0 = f.x; w1 = f.y; w2 = f.z; w3 = f.w;
                 if (ragged) {
                     if (col + 1 >= a.cols) w1 = 0;
@@ -720,7 +729,10 @@ __global__ __launch_bounds__(256) void k_update(UpdateArgs a)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             d[g][j] = make_int4(0, 0, 0, 0);
-            if (j < a.n_terms && cnt[g]) d[g][j] = *(const int4*)(a.dw[j] + n * a.lddw + k);
+            if (j < a.n_terms && cnt[g]) {   // last use of the accumulators: streaming hint
+                const uint4 v = ld_stream16(a.dw[j] + n * a.lddw + k);
+                d[g][j] = make_int4((int)v.x, (int)v.y, (int)v.z, (int)v.w);
+            }
         }
     }
     uint32_t m = 0;

@@ -288,7 +288,11 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
             for (int r = 0; r < 32 / RPI; ++r) {
                 const int row = r * RPI + rl;
                 const v4i v = *(const v4i*)(ebase + row * EROW + cc * 16);
-                __builtin_nontemporal_store(v, (v4i*)(ctile + (int64_t)row * a.ldc));
+                // forward accumulators are not read again until other kernels have streamed more than the caches
+                // hold: a non-temporal store keeps them from displacing what is needed next.  Weight gradients are
+                // read by the update right away: ordinary stores.
+                if (MODE == 1) __builtin_nontemporal_store(v, (v4i*)(ctile + (int64_t)row * a.ldc));
+                else *(v4i*)(ctile + (int64_t)row * a.ldc) = v;
             }
             wave_lds_fence();
         }

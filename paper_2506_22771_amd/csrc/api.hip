@@ -901,6 +901,7 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
             a.q_t = (int8_t*)(base + w.off_aqt[i]);
             a.st_qt = (int64_t)w.st_aqt[i];
             a.ldqt = pitch8(d.M);
+            a.qt_streaming = 1;   // read again only by this layer's weight gradient, after every forward pass
         }
         a.scale = s_a + 2 * i;
         a.st_scale = 1;

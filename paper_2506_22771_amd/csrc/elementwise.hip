@@ -335,7 +335,10 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
                 o.y = (int)tileT[cl * QT_LDW + 4 * ch + 1];
                 o.z = (int)tileT[cl * QT_LDW + 4 * ch + 2];
                 o.w = (int)tileT[cl * QT_LDW + 4 * ch + 3];
-                *(int4*)(q_t + oc * a.ldqt + orow) = o;
+                // the transposed copy of a layer input is read by the weight-gradient contraction much later
+                // (streaming store); that of a local gradient right away
+                if (a.qt_streaming) __builtin_nontemporal_store((u32x4){(uint32_t)o.x, (uint32_t)o.y, (uint32_t)o.z, (uint32_t)o.w}, (u32x4*)(q_t + oc * a.ldqt + orow));
+                else *(int4*)(q_t + oc * a.ldqt + orow) = o;
             }
         }
     }

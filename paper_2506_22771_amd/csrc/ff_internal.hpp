@@ -66,6 +66,7 @@ struct QuantArgs {
     int64_t ldq;
     int8_t* q_t;  // [cols, ldqt] or null
     int64_t ldqt;
+    int32_t qt_streaming;  // q_t is not read again soon: store it with a streaming hint
     float* scale;  // device scalar out
     // batching (second problem = first + strides, in elements of the respective type)
     int32_t nb;

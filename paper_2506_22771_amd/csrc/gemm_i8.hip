@@ -432,7 +432,7 @@ hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s)
     GemmPlan p = gemm_plan(a.I, a.J, a.R, a.nb, a.splits > 1);
     const int bm = p.bm, bn = p.bn;
     if (bn == 256) {
-        if (bm == 256) return launch_cfg<256, 256, 4, 4>(a, s);   // 16 waves of 64x64: four waves per SIMD to interleave
+        if (bm == 256) return launch_cfg<256, 256, 4, 2>(a, s);
         if (bm == 128) return launch_cfg<128, 256, 2, 2>(a, s);
         return launch_cfg<64, 256, 1, 4>(a, s);
     }

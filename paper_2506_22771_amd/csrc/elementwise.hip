@@ -96,6 +96,13 @@ __device__ __forceinline__ uint32_t absbits4(const float4 v)
     return max(a, b);
 }
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ldf4(const float4* p)   // streaming hint: the tensor is larger than the caches
+{
+    const f32x4 v = __builtin_nontemporal_load((const f32x4*)p);
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
 __global__ __launch_bounds__(256) void k_absmax_f32(const float* __restrict__ x0, int64_t st_x, int64_t n,
                                                     uint32_t* __restrict__ slot)
 {
@@ -111,10 +118,10 @@ __global__ __launch_bounds__(256) void k_absmax_f32(const float* __restrict__ x0
     uint32_t m = 0;
     int64_t i = gtid;
     for (; i + 3 * gstride < nvec; i += 4 * gstride) {
-        const float4 v0 = xv[i], v1 = xv[i + gstride], v2 = xv[i + 2 * gstride], v3 = xv[i + 3 * gstride];
+        const float4 v0 = ldf4(xv + i), v1 = ldf4(xv + i + gstride), v2 = ldf4(xv + i + 2 * gstride), v3 = ldf4(xv + i + 3 * gstride);
         m = max(m, max(max(absbits4(v0), absbits4(v1)), max(absbits4(v2), absbits4(v3))));
     }
-    for (; i < nvec; i += gstride) m = max(m, absbits4(xv[i]));
+    for (; i < nvec; i += gstride) m = max(m, absbits4(ldf4(xv + i)));
     if (gtid < head) m = max(m, __float_as_uint(x[gtid]) & 0x7FFFFFFFu);
     const int64_t tail0 = head + (nvec << 2);
     if (tail0 + gtid < n) m = max(m, __float_as_uint(x[tail0 + gtid]) & 0x7FFFFFFFu);

@@ -299,7 +299,11 @@ __global__ __launch_bounds__(256) void k_dwconv_forward(DwArgs p, int cgroups)
                     acc[e] = sacc;
                 }
             }
-            *(int4*)(p.acc + z * p.st_acc + ((int64_t)b * hw + pix) * p.ldacc + c0) = make_int4(acc[0], acc[1], acc[2], acc[3]);
+            {   // like the contraction's forward output: not read again soon, non-temporal store
+                typedef int i32x4 __attribute__((ext_vector_type(4)));
+                __builtin_nontemporal_store((i32x4){acc[0], acc[1], acc[2], acc[3]},
+                                            (i32x4*)(p.acc + z * p.st_acc + ((int64_t)b * hw + pix) * p.ldacc + c0));
+            }
             if (p.gsum) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {

@@ -536,7 +536,9 @@ __global__ __launch_bounds__(256) void k_residual_act(ResidualArgs a)
         const int e = v * 4;
         const int r = e / N, col = e - r * N;
         const int64_t row = row0 + r;
-        const int4 c = *(const int4*)(a.acc + z * a.st_acc + row * a.ldacc + col);
+        // the accumulators of a residual layer are not read again (everything downstream uses y): streaming hint
+        const uint4 cw = ld_stream16(a.acc + z * a.st_acc + row * a.ldacc + col);
+        const int4 c = make_int4((int)cw.x, (int)cw.y, (int)cw.z, (int)cw.w);
         float u[4];
         if (a.skip == FF_SKIP_IDENTITY) {
             const uint32_t xw = *(const uint32_t*)(a.xq + z * a.st_xq + row * a.ldx + col);

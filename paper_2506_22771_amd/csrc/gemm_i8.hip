@@ -240,6 +240,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     // after the main loop; each wave uses a private slice, no barrier needed): 16-byte writes row by row,
     // then reads that give every store instruction whole contiguous row segments of WTN*4 bytes.
     const bool staged = FF_STAGED_EPI && i0 + BM <= a.I && j0 + BN <= a.J;
+    const bool fast_sq = a.relu && a.rshift == 0;
     int8_t* const ebase = lds + wave * ESLICE;
 #pragma unroll
     for (int ti = 0; ti < TI; ++ti) {
@@ -267,13 +268,23 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
                 }
                 if (EPI) {
                     const int cc[4] = {c0, c1, c2, c3};
+                    if (fast_sq) {
+                        // ReLU and no pre-shift (every dense layer): one 32x32+64-bit multiply-add per element
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        int v = cc[e];
-                        if (a.relu) v = max(v, 0);
-                        const long long vl = (long long)v;
-                        sq += ((unsigned long long)(vl * vl)) >> a.rshift;
-                        vm = max(vm, v < 0 ? -v : v);
+                        for (int e = 0; e < 4; ++e) {
+                            const unsigned v = (unsigned)max(cc[e], 0);
+                            sq += (unsigned long long)v * v;
+                            vm = max(vm, (int)v);
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            int v = cc[e];
+                            if (a.relu) v = max(v, 0);
+                            const long long vl = (long long)v;
+                            sq += ((unsigned long long)(vl * vl)) >> a.rshift;
+                            vm = max(vm, v < 0 ? -v : v);
+                        }
                     }
                 }
             }

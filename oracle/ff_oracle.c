@@ -28,7 +28,11 @@
  * the residual-block functions: zero skip == plain layer, zero weights ==
  * dequantised input, exact goodness of power-of-two activities, order
  * independence and agreement with the fp64 sum of squares; depthwise
- * convolution == full convolution with channel-diagonal weights.
+ * convolution == full convolution with channel-diagonal weights; for the
+ * exact-derivative look-ahead: brute-force input-gradient contraction, a hand
+ * example and the lambda = 0 / top-layer reductions of the combination, and
+ * finite differences of L_new on an fp64 model of a three-layer stack within
+ * the int8 quantisation error.
  * The look-ahead *semantics* (which reading of Eq. (4) is meant) has no pin in
  * the paper: parity unpinned for that choice; its arithmetic is pinned.
  */
@@ -500,6 +504,62 @@ int ffo_dense_wgrad(const int8_t *gy_q, const int8_t *a_q, int64_t M, int64_t K,
     }
     if (bad & 2) return FFO_ERR_ARG;
     return bad ? FFO_ERR_OVERFLOW : FFO_OK;
+}
+
+/* ------------------------------------------------------------------------
+ * Exact-derivative variant of the look-ahead (Eq. (4) read literally: the
+ * derivative of the later layers' losses with respect to this layer's weights
+ * is taken through those layers).  Dense ReLU stacks without normalisation.
+ * With z_i the pre-activation in activity units, y_i = act(z_i), and
+ * E_i = d(L_{i+1} + ... + L_k)/dy_i:
+ *     H_i = d(L_i + ... + L_k)/dz_i = (2 c_i y_i + E_i) * act'(z_i)
+ *     E_{i-1} = H_i W_i                          (a_i = y_{i-1})
+ *     g^Y_i = dL_new_i/dz_i = (2 c_i y_i + lambda E_i) * act'(z_i)
+ * c_i = dL_i/dG_i per sample (NOT the combined coefficient of the default
+ * reading).  H_i and g^Y_i are each quantised to int8 (a reading: the paper
+ * gives no int8 form of this chain and states that FF avoids it).
+ *
+ * Input-gradient contraction: e[m][k] = sum_n h_q[m][n] * w_q[n][k].
+ * ---------------------------------------------------------------------- */
+int ffo_dense_input_grad(const int8_t *h_q, const int8_t *w_q, int64_t M, int64_t K, int64_t N,
+                         int32_t *e)
+{
+    if (!h_q || !w_q || !e) return FFO_ERR_ARG;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t sum = 0;
+            for (int64_t n = 0; n < N; ++n) sum += (int32_t)h_q[m * N + n] * (int32_t)w_q[n * K + k];
+            if (sum > INT32_MAX || sum < INT32_MIN) bad |= 1;
+            e[m * K + k] = (int32_t)sum;
+        }
+    }
+    return bad ? FFO_ERR_OVERFLOW : FFO_OK;
+}
+
+/* The two gradients of one layer and one pass, before quantisation:
+ *   y = act(fp32(acc) * (s_a * s_w));  t = (2 c[b]) * y;  E = fp32(e_acc) * s_e  (0 when e_acc is NULL)
+ *   h = (t + E) * mask;   g = fma(lambda, E, t) * mask;   mask = acc > 0 (ReLU) or 1 (identity). */
+int ffo_chain_combine(const int32_t *acc, int64_t B, int64_t terms, int relu, float s_a, float s_w,
+                      const float *c, const int32_t *e_acc, float s_e, float lambda, float *h, float *g)
+{
+    if (!acc || !c || !h || !g) return FFO_ERR_ARG;
+    const float s_y = s_a * s_w;
+    for (int64_t b = 0; b < B; ++b) {
+        const float d = 2.0f * c[b];
+        for (int64_t j = 0; j < terms; ++j) {
+            const int64_t i = b * terms + j;
+            float y = (float)acc[i] * s_y;
+            if (relu && y < 0.0f) y = 0.0f;
+            const float t = d * y;
+            const float E = e_acc ? (float)e_acc[i] * s_e : 0.0f;
+            const int live = !relu || acc[i] > 0;
+            h[i] = live ? t + E : 0.0f;
+            g[i] = live ? fmaf(lambda, E, t) : 0.0f;
+        }
+    }
+    return FFO_OK;
 }
 
 /* Convolution: dw[co][kh][kw][ci] = sum over samples b0 <= b < b1 and output

@@ -24,6 +24,7 @@ PASS_POS = +1
 PASS_NEG = -1
 KIND_ACT = 0   # stochastic-rounding stream of an activation tensor
 KIND_GRAD = 1  # stochastic-rounding stream of a local-gradient tensor
+KIND_CHAIN = 2  # stochastic-rounding stream of the gradient handed down the chain (exact-derivative variant)
 INT32_SAFE_ROWS = (2**31 - 1) // (127 * 127)   # longest reduction that cannot overflow int32
 
 _lib = None
@@ -64,6 +65,8 @@ def lib() -> C.CDLL:
         L.ffo_local_grad_f32.argtypes = [P, i64, i64, P, P]
         L.ffo_conv_wgrad.argtypes = [P, P, i64, i64, i64, i64, i64, i64, i64, i64, i64, P]
         L.ffo_update.argtypes = [P, i64, P, P, P, i32, f32, i32]
+        L.ffo_dense_input_grad.argtypes = [P, P, i64, i64, i64, P]
+        L.ffo_chain_combine.argtypes = [P, i64, i64, i32, f32, f32, P, P, f32, f32, P, P]
         _lib = L
     return _lib
 
@@ -280,6 +283,34 @@ def conv_wgrad(gy_q: np.ndarray, a_q: np.ndarray, ks: int, stride: int, pad: int
     return dw
 
 
+def dense_input_grad(h_q: np.ndarray, w_q: np.ndarray) -> np.ndarray:
+    """e[m][k] = sum_n h_q[m][n] * w_q[n][k] (int32): the gradient handed to the layer below."""
+    M, N = h_q.shape
+    N2, K = w_q.shape
+    assert N == N2
+    e = np.empty((M, K), dtype=np.int32)
+    _chk(lib().ffo_dense_input_grad(_p(h_q), _p(w_q), M, K, N, _p(e)), "dense_input_grad")
+    return e
+
+
+def chain_combine(acc: np.ndarray, relu: int, s_a, s_w, c: np.ndarray, e_acc, s_e, lam: float):
+    """(h, g) of ffo_chain_combine; e_acc None = the top layer (no later losses)."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    B = acc.shape[0]
+    terms = acc.size // B if B else 0
+    c = np.ascontiguousarray(c, dtype=np.float32)
+    h = np.empty(acc.shape, dtype=np.float32)
+    g = np.empty(acc.shape, dtype=np.float32)
+    ep = None
+    if e_acc is not None:
+        e_acc = np.ascontiguousarray(e_acc, dtype=np.int32)
+        assert e_acc.shape == acc.shape
+        ep = _p(e_acc)
+    _chk(lib().ffo_chain_combine(_p(acc), B, terms, relu, np.float32(s_a), np.float32(s_w), _p(c), ep,
+                                 np.float32(s_e), np.float32(lam), _p(h), _p(g)), "chain_combine")
+    return h, g
+
+
 def update(w: np.ndarray, dws: Sequence[np.ndarray], s_g: Sequence[float], s_a: Sequence[float],
            lr: float, total_samples: int) -> np.ndarray:
     """Returns the updated fp32 master weights (w itself is left untouched)."""
@@ -437,6 +468,57 @@ def train_step(layers, w_master: List[np.ndarray], x_pos: np.ndarray, x_neg: np.
         if skip[i] == "projection":
             finish(i - 2, pdws, sgs, psas)
         grads[i] = per_pass
+    out = dict(w_master=new_w, w_q=new_wq, s_w=new_sw,
+               loss=np.array([[fwd[i][p]["loss_mean"] for p in range(2)] for i in range(k)]),
+               goodness=np.stack([np.stack([fwd[i][p]["G"] for p in range(2)]) for i in range(k)]))
+    if keep:
+        out.update(fwd=fwd, grads=grads, w_q_in=[q for q, _ in wq], s_w_in=[s for _, s in wq])
+    return out
+
+
+def train_step_chain(layers, w_master: List[np.ndarray], x_pos: np.ndarray, x_neg: np.ndarray,
+                     theta: float, lam: float, lr: float, seed: int, step: int, keep: bool = True,
+                     train_mask=None) -> Dict:
+    """One iteration with Eq. (4) read as an exact derivative (see ffo_dense_input_grad): the same
+    forward pass as train_step, then per pass a sweep from the last layer to the first that hands
+    the int8 gradient H_i down through the pre-step weights.  Dense layers without normalisation."""
+    k = len(layers)
+    for l in layers:
+        if l.kind != "dense" or l.l2norm_out or _layer_attr(l, "skip", "none") != "none" \
+                or _layer_attr(l, "role", "ff") != "ff" or _layer_attr(l, "input_back", 0):
+            raise OracleError("the exact-derivative look-ahead is defined for plain dense stacks only")
+    wq = [quantize(w, ROUND_NEAREST) for w in w_master]
+    B = x_pos.shape[0]
+    fwd: List[List[Dict]] = [[None, None] for _ in range(k)]
+    for p, (x, sign) in enumerate(((x_pos, PASS_POS), (x_neg, PASS_NEG))):
+        a = np.ascontiguousarray(x, dtype=np.float32)
+        for i, layer in enumerate(layers):
+            f = forward_layer(layer, a, wq[i][0], wq[i][1], sign, theta, seed, stream_tag(step, i, p, KIND_ACT))
+            a = f.pop("a_next")
+            fwd[i][p] = f
+    grads: List[List[Dict]] = [[None, None] for _ in range(k)]
+    for p in range(2):
+        e_acc, s_e = None, np.float32(0)
+        for i in range(k - 1, -1, -1):
+            f, layer = fwd[i][p], layers[i]
+            h, g = chain_combine(f["acc"], layer.relu, f["s_a"], wq[i][1], f["c"], e_acc, s_e, lam)
+            gy_q, s_g = quantize(g, ROUND_STOCHASTIC, seed, stream_tag(step, i, p, KIND_GRAD))
+            rec = dict(gy_q=gy_q, s_g=s_g, dw=[dense_wgrad(gy_q, f["a_q"]).reshape(-1)], h=h, g=g, e_acc=e_acc, s_e=s_e)
+            if i > 0:
+                h_q, s_h = quantize(h, ROUND_STOCHASTIC, seed, stream_tag(step, i, p, KIND_CHAIN))
+                e_acc = dense_input_grad(h_q, wq[i][0])
+                s_e = np.float32(s_h) * np.float32(wq[i][1])
+                rec.update(h_q=h_q, s_h=s_h)
+            grads[i][p] = rec
+    new_w, new_wq, new_sw = [None] * k, [None] * k, [None] * k
+    for i in range(k):
+        if train_mask is not None and not train_mask[i]:
+            new_w[i], new_wq[i], new_sw[i] = w_master[i], wq[i][0], wq[i][1]
+            continue
+        w_new = update(w_master[i], [grads[i][p]["dw"][0] for p in range(2)], [grads[i][p]["s_g"] for p in range(2)],
+                       [fwd[i][p]["s_a"] for p in range(2)], lr, 2 * B)
+        new_w[i] = w_new
+        new_wq[i], new_sw[i] = quantize(w_new, ROUND_NEAREST)
     out = dict(w_master=new_w, w_q=new_wq, s_w=new_sw,
                loss=np.array([[fwd[i][p]["loss_mean"] for p in range(2)] for i in range(k)]),
                goodness=np.stack([np.stack([fwd[i][p]["G"] for p in range(2)]) for i in range(k)]))

@@ -58,7 +58,7 @@ enum { FF_PASS_POS = +1, FF_PASS_NEG = -1 };
 enum { FF_DENSE = 0, FF_CONV2D = 1, FF_DWCONV2D = 2 };
 
 /* Stochastic-rounding stream kinds used by ff_train_step (see ff_stream_tag). */
-enum { FF_KIND_ACT = 0, FF_KIND_GRAD = 1 };
+enum { FF_KIND_ACT = 0, FF_KIND_GRAD = 1, FF_KIND_CHAIN = 2 };
 
 /* Smallest workspace accepted by the single-operation entry points. */
 #define FF_WS_MIN_BYTES 1024u
@@ -110,7 +110,21 @@ typedef struct {
                                     is 0 takes part in the forward pass and in the look-ahead sums of the layers
                                     before it, but its weights are left as they are (the greedy layer-by-layer
                                     schedule of Section III trains layer i with layers < i frozen). */
+    int32_t lookahead;           /* FF_LOOKAHEAD_COEFF (0, the default reading) or FF_LOOKAHEAD_CHAIN, see below */
 } ff_net_desc;
+
+/* How the later layers' losses enter a layer's update (Eq. (3), Eq. (4)).
+ * FF_LOOKAHEAD_COEFF: through their per-sample loss derivatives only (ff_lookahead); no gradient crosses a layer
+ *   boundary, as Section IV-C describes the cost of the method.
+ * FF_LOOKAHEAD_CHAIN: Eq. (4) taken literally as a derivative through the later layers, in int8 (a variant; the
+ *   paper gives no int8 form of it).  Dense layers with l2norm_out = 0 only, else FF_ERR_UNSUPPORTED.  Per pass,
+ *   from the last layer down, with c_i = dL_i/dG_i, y_i the activities and E_k = 0:
+ *     h_i = (2 c_i y_i + E_i) * act'          quantised (stochastic, stream kind FF_KIND_CHAIN) -> h_q, s_h
+ *     E_{i-1} = s_h s_W (h_q W_q)             ff_layer_input_grad, pre-step weights
+ *     g_i = (2 c_i y_i + lambda E_i) * act'   quantised (stream kind FF_KIND_GRAD), then the weight gradient and
+ *                                             the update as in the default reading.
+ *   lambda = 0 gives the default step bit for bit; the last layer's update is the same for every lambda. */
+enum { FF_LOOKAHEAD_COEFF = 0, FF_LOOKAHEAD_CHAIN = 1 };
 
 /* Trainable state. [host] arrays of n_layers DEVICE pointers.
  * w_master[i]: fp32 [N_i, K_i] contiguous (conv: [C_out][k][k][C_in]).
@@ -241,6 +255,25 @@ ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc
                                   void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * ff_chain_gradients, ff_layer_input_grad — the two operations FF_LOOKAHEAD_CHAIN adds (Eq. (4) as an exact
+ * derivative; dense layers).
+ * ff_chain_gradients, one layer and pass:  y = act(s_a s_w acc);  E = (s_h s_w_up) e_acc, or 0 if e_acc == NULL
+ *   h[m][n] = (2 coeff[m] y + E) * mask          fp32 [M, N] contiguous (out, may be NULL with h_amax)
+ *   g[m][n] = fma(lambda, E, 2 coeff[m] y) * mask fp32 [M, N] contiguous (out)
+ *   mask = acc > 0 under ReLU, 1 otherwise;  h_amax, g_amax: absmax of the two tensors (one fp32 each, out).
+ *   acc int32 [M, ff_pitch32(N)], e_acc int32 [M, ff_pitch32(N)], coeff fp32 [M]; s_a, s_w, s_h, s_w_up device
+ *   scalars (s_h, s_w_up unused without e_acc).  h and g are then quantised with ff_quantize.
+ * ff_layer_input_grad:  e_acc[m][k] = sum_n h_q[m][n] * w_q_t[k][n]   (int32 [M, ff_pitch32(K)])
+ *   h_q int8 [M, ff_pitch(N)]; w_q_t int8 [K, ff_pitch(N)] is the TRANSPOSED int8 weight matrix (ff_quantize's q_t
+ *   output for the [N, K] master weights).  FF_ERR_OVERFLOW_BOUND if N * 127^2 could exceed int32.
+ * ------------------------------------------------------------------------------------------- */
+ff_status ff_chain_gradients(const ff_layer_desc* layer, const int32_t* acc, const float* s_a, const float* s_w,
+                             const float* coeff, const int32_t* e_acc, const float* s_h, const float* s_w_up,
+                             float lambda, float* h, float* g, float* h_amax, float* g_amax, void* stream);
+ff_status ff_layer_input_grad(const ff_layer_desc* layer, const int8_t* h_q, const int8_t* w_q_t, int32_t* e_acc,
+                              void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * ff_layer_update — SGD step on the fp32 master weights from both passes' integer accumulators
  * and requantisation (Algorithm 1: "update weights using gradients in INT8 precision"):
  *   g = fp32(dw_pos) * (s_g_pos * s_a_pos);  g = fma(fp32(dw_neg), s_g_neg * s_a_neg, g)
@@ -312,7 +345,8 @@ enum {
     FF_K_IM2COL = 8,     /* patch matrices of convolution layers              */
     FF_K_RESIDUAL = 9,   /* block output and its goodness (residual layers)   */
     FF_K_DWCONV = 10,    /* depthwise convolution: forward and weight gradient */
-    FF_K_COUNT = 11
+    FF_K_CHAIN = 11,     /* FF_LOOKAHEAD_CHAIN: gradient combination, its quantisation, input-gradient contraction */
+    FF_K_COUNT = 12
 };
 #define FF_TIMING_MAX_RECORDS 16384
 ff_status ff_timing_enable(int32_t class_mask);

@@ -13,7 +13,7 @@ import torch
 
 ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
 PASS_POS, PASS_NEG = 1, -1
-KIND_ACT, KIND_GRAD = 0, 1
+KIND_ACT, KIND_GRAD, KIND_CHAIN = 0, 1, 2
 WS_MIN_BYTES = 1024
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libffint8.so")
@@ -33,7 +33,7 @@ class LayerDesc(C.Structure):
 
 class NetDesc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("batch", C.c_int32), ("layers", C.POINTER(LayerDesc)),
-                ("train_layer", C.POINTER(C.c_int32))]
+                ("train_layer", C.POINTER(C.c_int32)), ("lookahead", C.c_int32)]
 
 
 class NetState(C.Structure):
@@ -76,6 +76,10 @@ def lib() -> C.CDLL:
         L.ff_lookahead.argtypes = [P, i32, i64, f32, P, P]
         L.ff_layer_backward_local.restype = i32
         L.ff_layer_backward_local.argtypes = [LD, P, P, P, P, P, i32, u64, u64, P, P, P, P, P, sz, P]
+        L.ff_chain_gradients.restype = i32
+        L.ff_chain_gradients.argtypes = [LD, P, P, P, P, P, P, P, f32, P, P, P, P, P]
+        L.ff_layer_input_grad.restype = i32
+        L.ff_layer_input_grad.argtypes = [LD, P, P, P, P, sz, P]
         L.ff_layer_update.restype = i32
         L.ff_layer_update.argtypes = [LD, P, P, P, P, P, P, P, f32, i32, P, P, P, sz, P]
         L.ff_train_step.restype = i32
@@ -188,6 +192,18 @@ def ff_layer_backward_local(desc, acc, vmax, s_a, s_w, coeff_total, round_mode, 
          "ff_layer_backward_local")
 
 
+def ff_chain_gradients(desc, acc, s_a, s_w, coeff, e_acc, s_h, s_w_up, lam, h, g, h_amax, g_amax) -> None:
+    _chk(lib().ff_chain_gradients(C.byref(desc), _ptr(acc), _ptr(s_a), _ptr(s_w), _ptr(coeff), _ptr(e_acc), _ptr(s_h),
+                                  _ptr(s_w_up), lam, _ptr(h), _ptr(g), _ptr(h_amax), _ptr(g_amax), _stream()),
+         "ff_chain_gradients")
+
+
+def ff_layer_input_grad(desc, h_q, w_q_t, e_acc, ws) -> None:
+    _chk(lib().ff_layer_input_grad(C.byref(desc), _ptr(h_q), _ptr(w_q_t), _ptr(e_acc), _ptr(ws),
+                                   ws.numel() * ws.element_size() if ws is not None else 0, _stream()),
+         "ff_layer_input_grad")
+
+
 def ff_layer_update(desc, w_master, dw_pos, s_g_pos, s_a_pos, dw_neg, s_g_neg, s_a_neg, lr, total_samples, w_q, s_w,
                     ws) -> None:
     _chk(lib().ff_layer_update(C.byref(desc), _ptr(w_master), _ptr(dw_pos), _ptr(s_g_pos), _ptr(s_a_pos), _ptr(dw_neg),
@@ -200,12 +216,12 @@ class Net:
     Holds references to the tensors so that the pointer arrays stay valid."""
 
     def __init__(self, layers: Sequence, batch: int, w_master: List[torch.Tensor], w_q: List[torch.Tensor],
-                 s_w: List[torch.Tensor], train_layer: Optional[Sequence[int]] = None):
+                 s_w: List[torch.Tensor], train_layer: Optional[Sequence[int]] = None, lookahead: str = "coeff"):
         self.k = len(layers)
         self.batch = batch
         self._descs = (LayerDesc * self.k)(*[layer_desc(l, batch) for l in layers])
         self._mask = (C.c_int32 * self.k)(*[int(bool(f)) for f in train_layer]) if train_layer is not None else None
-        self.desc = NetDesc(self.k, batch, self._descs, self._mask)
+        self.desc = NetDesc(self.k, batch, self._descs, self._mask, {"coeff": 0, "chain": 1}[lookahead])
         self.w_master, self.w_q, self.s_w = list(w_master), list(w_q), list(s_w)
         self._pm = (C.c_void_p * self.k)(*[t.data_ptr() for t in self.w_master])
         self._pq = (C.c_void_p * self.k)(*[t.data_ptr() for t in self.w_q])
@@ -233,7 +249,7 @@ def ff_train_step_at(net: Net, x_pos, x_neg, theta, lam, lr, seed, step_dev, adv
 
 
 KERNEL_CLASSES = ("gemm_fwd", "gemm_dw", "quant_act", "quant_grad", "quant_w", "update", "absmax", "small", "im2col",
-                  "residual", "dwconv")
+                  "residual", "dwconv", "chain")
 
 
 def ff_timing_enable(on, classes: Optional[Sequence[str]] = None) -> None:

@@ -135,6 +135,12 @@ struct WsLayout {
     size_t off_aqt[MAX_LAYERS], st_aqt[MAX_LAYERS];  // dense only: transposed quantised input [2][st], retained
     size_t off_acc[MAX_LAYERS], st_acc[MAX_LAYERS];  // int32 accumulators [2][st] (bytes), retained
     size_t off_y[MAX_LAYERS], st_y[MAX_LAYERS];      // residual layers: fp32 block output [2][st] (bytes), retained
+    // exact-derivative look-ahead only (all sizes 0 otherwise)
+    int chain;
+    size_t off_hf, off_gf, st_f;   // fp32 scratch [2][st_f] each: the two gradients of a layer before quantisation
+    size_t off_hq, st_hq;          // int8 scratch [2][st_hq]: the gradient handed down, row-major
+    size_t off_e, st_e;            // int32 scratch [2][st_e] (bytes): input-gradient accumulators
+    size_t off_wqt;                // int8 scratch: transposed int8 weights of one layer
     size_t total;
 };
 
@@ -203,14 +209,15 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
     size_t off = 0;
     const size_t k = (size_t)w->k, B = (size_t)w->B;
     w->off_slots = off;
-    off = align_up(off + sizeof(uint32_t) * (k * 5 + 2), A);
+    // + h_amax[k][2], wt_amax[k] (exact-derivative look-ahead)
+    off = align_up(off + sizeof(uint32_t) * (k * 8 + 2), A);
     w->off_gsum = off;
     off = align_up(off + sizeof(uint64_t) * k * 2 * B, A);
     w->off_vmax = off;
     off = align_up(off + sizeof(int32_t) * k * 2 * B, A);
     w->zero_bytes = off;
     w->off_scales = off;
-    off = align_up(off + sizeof(float) * k * 4, A);
+    off = align_up(off + sizeof(float) * (k * 4 + 4), A);   // + s_h[2], the scale of the transposed weight copy
     w->off_c = off;
     off = align_up(off + sizeof(float) * k * 2 * B, A);
     w->off_ct = off;
@@ -261,6 +268,39 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
         w->st_y[i] = d.skip != FF_SKIP_NONE ? align_up((size_t)(d.M * d.N) * sizeof(float), A) : 0;
         w->off_y[i] = off;
         off += 2 * w->st_y[i];
+    }
+    w->chain = net->lookahead == FF_LOOKAHEAD_CHAIN;
+    w->st_f = w->st_hq = w->st_e = 0;
+    w->off_hf = w->off_gf = w->off_hq = w->off_e = w->off_wqt = off;
+    if (net->lookahead != FF_LOOKAHEAD_COEFF && net->lookahead != FF_LOOKAHEAD_CHAIN) return FF_ERR_INVALID_ARG;
+    if (w->chain) {
+        size_t f = 0, hq = 0, e = 0, wqt = 0;
+        for (int i = 0; i < w->k; ++i) {
+            const Dims& d = w->d[i];
+            const ff_layer_desc& L = net->layers[i];
+            if (d.kind != FF_DENSE || L.l2norm_out || L.role != FF_ROLE_LAYER || L.skip != FF_SKIP_NONE || L.input_back)
+                return FF_ERR_UNSUPPORTED;
+            if (d.N > INT32_SAFE_LEN) return FF_ERR_OVERFLOW_BOUND;   // reduction length of the input gradient
+            f = max(f, (size_t)(d.M * d.N) * sizeof(float));
+            if (i > 0) {
+                hq = max(hq, (size_t)(d.M * pitch8(d.N)));
+                e = max(e, (size_t)(d.M * pitch32(d.K)) * sizeof(int32_t));
+                wqt = max(wqt, (size_t)(d.K * pitch8(d.N)));
+            }
+        }
+        w->st_f = align_up(f, A);
+        w->off_hf = off;
+        off += 2 * w->st_f;
+        w->off_gf = off;
+        off += 2 * w->st_f;
+        w->st_hq = align_up(hq, A);
+        w->off_hq = off;
+        off += 2 * w->st_hq;
+        w->st_e = align_up(e, A);
+        w->off_e = off;
+        off += 2 * w->st_e;
+        w->off_wqt = off;
+        off += align_up(wqt, A);
     }
     w->total = off;
     return FF_OK;
@@ -518,7 +558,7 @@ const char* ff_status_string(ff_status s)
     }
 }
 
-const char* ff_version(void) { return "ffint8 0.3 (gfx950)"; }
+const char* ff_version(void) { return "ffint8 0.4 (gfx950)"; }
 
 int32_t ff_goodness_shift(const ff_layer_desc* layer)
 {
@@ -739,6 +779,76 @@ ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc
     const int64_t dw_elems = d.N * pitch32(d.K);
     int8_t* colT = (int8_t*)ws + FF_WS_MIN_BYTES;
     return run_wgrad(d, gy_q_t, 0, a_q_t, 0, colT, 0, (int32_t*)(colT + layer_col_bytes(d)), 0, dw_acc, 0, dw_elems, 1, s);
+}
+
+ff_status ff_chain_gradients(const ff_layer_desc* layer, const int32_t* acc, const float* s_a, const float* s_w,
+                             const float* coeff, const int32_t* e_acc, const float* s_h, const float* s_w_up,
+                             float lambda, float* h, float* g, float* h_amax, float* g_amax, void* stream)
+{
+    Dims d;
+    const ff_status st = layer_dims(layer, &d);
+    if (st != FF_OK) return st;
+    if (d.kind != FF_DENSE) return FF_ERR_UNSUPPORTED;
+    if (!acc || !s_a || !s_w || !coeff || !g || !g_amax) return FF_ERR_INVALID_ARG;
+    if (e_acc && (!s_h || !s_w_up)) return FF_ERR_INVALID_ARG;
+    if ((h == nullptr) != (h_amax == nullptr)) return FF_ERR_INVALID_ARG;
+    if (!aligned16(acc) || (e_acc && !aligned16(e_acc)) || !aligned4(g) || (h && !aligned4(h)) || !aligned4(g_amax) ||
+        (h_amax && !aligned4(h_amax)))
+        return FF_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)g_amax, 1, 0u, s));
+    if (h_amax) HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)h_amax, 1, 0u, s));
+    ChainArgs ca;
+    memset(&ca, 0, sizeof(ca));
+    ca.acc = acc;
+    ca.ldacc = pitch32(d.N);
+    ca.s_a = s_a;
+    ca.s_w = s_w;
+    ca.coeff = coeff;
+    ca.e_acc = e_acc;
+    ca.lde = pitch32(d.N);
+    ca.s_h = s_h;
+    ca.s_w_up = s_w_up;
+    ca.lambda = lambda;
+    ca.relu = layer->relu ? 1 : 0;
+    ca.M = d.M;
+    ca.N = d.N;
+    ca.h = h;
+    ca.g = g;
+    ca.h_amax_bits = (uint32_t*)h_amax;   // the bit pattern of a non-negative fp32 is the value itself
+    ca.g_amax_bits = (uint32_t*)g_amax;
+    ca.nb = 1;
+    HIPCHK_T(FF_K_CHAIN, launch_chain_combine(ca, s));
+    return FF_OK;
+}
+
+ff_status ff_layer_input_grad(const ff_layer_desc* layer, const int8_t* h_q, const int8_t* w_q_t, int32_t* e_acc,
+                              void* ws, size_t ws_bytes, void* stream)
+{
+    Dims d;
+    const ff_status st = layer_dims(layer, &d);
+    if (st != FF_OK) return st;
+    if (d.kind != FF_DENSE) return FF_ERR_UNSUPPORTED;
+    if (!h_q || !w_q_t || !e_acc || !ws) return FF_ERR_INVALID_ARG;
+    if (ws_bytes < FF_WS_MIN_BYTES) return FF_ERR_WORKSPACE;
+    if (!aligned16(h_q) || !aligned16(w_q_t) || !aligned16(e_acc)) return FF_ERR_ALIGN;
+    if (d.N > INT32_SAFE_LEN) return FF_ERR_OVERFLOW_BOUND;
+    hipStream_t s = (hipStream_t)stream;
+    GemmArgs ga;
+    memset(&ga, 0, sizeof(ga));
+    ga.P = h_q;
+    ga.Q = w_q_t;
+    ga.C = e_acc;
+    ga.I = (int32_t)d.M;
+    ga.J = (int32_t)d.K;
+    ga.R = (int32_t)d.N;
+    ga.ldp = pitch8(d.N);
+    ga.ldq = pitch8(d.N);
+    ga.ldc = pitch32(d.K);
+    ga.nb = 1;
+    ga.splits = 1;
+    HIPCHK_T(FF_K_CHAIN, launch_gemm_nt_i8(ga, s));
+    return FF_OK;
 }
 
 ff_status ff_layer_update(const ff_layer_desc* layer, float* w_master, const int32_t* dw_acc_pos,
@@ -996,7 +1106,7 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
     }
 
     // ---- look-ahead coefficients of every layer (Eq. (3)/(4)) and the absmax of every local gradient
-    {
+    if (!w.chain) {
         LookaheadArgs la;
         memset(&la, 0, sizeof(la));
         la.coeff = c;
@@ -1066,6 +1176,137 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         return FF_OK;
     };
     auto trained = [&](int t) { return !net->train_layer || net->train_layer[t]; };
+
+    if (w.chain) {
+        // ---- Eq. (4) as an exact derivative: from the last layer down, the int8 gradient h_i is handed through the
+        // pre-step weights of layer i to the layer below (dense layers only, checked by make_layout)
+        uint32_t* h_amax = w_amax + k;        // [k][2]
+        uint32_t* wt_amax = h_amax + 2 * k;   // [k]
+        float* s_h = s_g + 2 * k;             // [2]
+        float* s_wt = s_h + 2;                // scale of the transposed weight copy (equals s_w of the layer)
+        float* hf = (float*)(base + w.off_hf);
+        float* gf = (float*)(base + w.off_gf);
+        const int64_t st_f = (int64_t)(w.st_f / sizeof(float));
+        int8_t* hq = (int8_t*)(base + w.off_hq);
+        int32_t* eacc = (int32_t*)(base + w.off_e);
+        int8_t* wqt = (int8_t*)(base + w.off_wqt);
+        for (int i = k - 1; i >= 0; --i) {
+            const Dims& d = w.d[i];
+            const ff_layer_desc& L = net->layers[i];
+            ChainArgs ca;
+            memset(&ca, 0, sizeof(ca));
+            ca.acc = (const int32_t*)(base + w.off_acc[i]);
+            ca.ldacc = pitch32(d.N);
+            ca.st_acc = (int64_t)(w.st_acc[i] / sizeof(int32_t));
+            ca.s_a = s_a + 2 * i;
+            ca.st_s_a = 1;
+            ca.s_w = state->s_w[i];
+            ca.coeff = c + (int64_t)i * 2 * B;
+            ca.st_coeff = B;
+            if (i < k - 1) {
+                ca.e_acc = eacc;
+                ca.lde = pitch32(d.N);
+                ca.st_e = (int64_t)(w.st_e / sizeof(int32_t));
+                ca.s_h = s_h;
+                ca.st_s_h = 1;
+                ca.s_w_up = s_wt;   // pre-step weight scale of layer i + 1 (state->s_w[i + 1] already holds the updated one)
+            }
+            ca.lambda = lambda;
+            ca.relu = L.relu ? 1 : 0;
+            ca.M = d.M;
+            ca.N = d.N;
+            ca.h = i > 0 ? hf : nullptr;
+            ca.g = gf;
+            ca.st_out = st_f;
+            ca.h_amax_bits = h_amax + 2 * i;
+            ca.g_amax_bits = g_amax + 2 * i;
+            ca.st_amax = 1;
+            ca.nb = 2;
+            HIPCHK_T(FF_K_CHAIN, launch_chain_combine(ca, s));
+
+            QuantArgs a;
+            memset(&a, 0, sizeof(a));
+            a.x = gf;
+            a.st_x = st_f;
+            a.rows_per_sample = 1;
+            a.amax_bits = g_amax + 2 * i;
+            a.st_amax = 1;
+            a.round_mode = FF_ROUND_STOCHASTIC;
+            a.key = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 0, FF_KIND_GRAD));
+            a.key2 = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 1, FF_KIND_GRAD));
+            a.step_dev = step_dev;
+            a.seed = seed;
+            a.tag_layer = (uint32_t)i;
+            a.tag_kind = FF_KIND_GRAD;
+            a.rows = d.M;
+            a.cols = d.N;
+            a.q_t = (int8_t*)(base + w.off_gy);
+            a.st_qt = (int64_t)w.st_gy;
+            a.ldqt = pitch8(d.M);
+            a.scale = s_g + 2 * i;
+            a.st_scale = 1;
+            a.nb = 2;
+            if (trained(i)) HIPCHK_T(FF_K_QUANT_GRAD, launch_quantize(QSRC_F32, a, s));
+
+            if (i > 0) {
+                QuantArgs hqa = a;
+                hqa.x = hf;
+                hqa.amax_bits = h_amax + 2 * i;
+                hqa.key = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 0, FF_KIND_CHAIN));
+                hqa.key2 = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 1, FF_KIND_CHAIN));
+                hqa.tag_kind = FF_KIND_CHAIN;
+                hqa.q_t = nullptr;
+                hqa.st_qt = 0;
+                hqa.ldqt = 0;
+                hqa.q = hq;
+                hqa.st_q = (int64_t)w.st_hq;
+                hqa.ldq = pitch8(d.N);
+                hqa.scale = s_h;
+                HIPCHK_T(FF_K_CHAIN, launch_quantize(QSRC_F32, hqa, s));
+
+                // transposed int8 copy of the pre-step weights: the same codes as w_q, [K, pitch(N)]
+                const int64_t nw = d.N * d.K;
+                HIPCHK_T(FF_K_CHAIN, launch_absmax(state->w_master[i], 0, 1, nw, wt_amax + i, s));
+                QuantArgs wa;
+                memset(&wa, 0, sizeof(wa));
+                wa.x = state->w_master[i];
+                wa.amax_bits = wt_amax + i;
+                wa.round_mode = FF_ROUND_NEAREST_EVEN;
+                wa.rows = d.N;
+                wa.cols = d.K;
+                wa.q_t = wqt;
+                wa.ldqt = pitch8(d.N);
+                wa.scale = s_wt;
+                wa.nb = 1;
+                wa.rows_per_sample = 1;
+                HIPCHK_T(FF_K_CHAIN, launch_quantize(QSRC_F32, wa, s));
+
+                GemmArgs ga;
+                memset(&ga, 0, sizeof(ga));
+                ga.P = hq;
+                ga.Q = wqt;
+                ga.C = eacc;
+                ga.I = (int32_t)d.M;
+                ga.J = (int32_t)d.K;
+                ga.R = (int32_t)d.N;
+                ga.ldp = pitch8(d.N);
+                ga.ldq = pitch8(d.N);
+                ga.ldc = pitch32(d.K);
+                ga.nb = 2;
+                ga.st_p = (int64_t)w.st_hq;
+                ga.st_q = 0;
+                ga.st_c = (int64_t)(w.st_e / sizeof(int32_t));
+                ga.splits = 1;
+                HIPCHK_T(FF_K_CHAIN, launch_gemm_nt_i8(ga, s));
+            }
+            if (trained(i)) {
+                const ff_status us = wgrad_update(i, i);
+                if (us != FF_OK) return us;
+            }
+        }
+        if (step_dev && advance) HIPCHK_T(FF_K_SMALL, launch_advance_u64(step_dev, s));
+        return FF_OK;
+    }
 
     for (int i = 0; i < k; ++i) {
         const Dims& d = w.d[i];

@@ -709,6 +709,76 @@ hipError_t launch_grad_amax(const float* ct, const int32_t* vmax, const float* s
 }
 
 // ------------------------------------------------------------------------------------------------
+// Exact-derivative look-ahead: the two gradients of a dense layer (see ChainArgs).  A thread owns four
+// consecutive columns of one row; HBM-bound (two int32 tensors read, two fp32 tensors written).
+// ------------------------------------------------------------------------------------------------
+template <bool VEC>
+__global__ __launch_bounds__(256) void k_chain_combine(ChainArgs a)
+{
+    const int z = blockIdx.y;
+    const int64_t ngroups = (a.N + 3) >> 2;
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    uint32_t mh = 0, mg = 0;
+    if (e < a.M * ngroups) {
+        const int64_t m = e / ngroups;
+        const int64_t j0 = (e - m * ngroups) << 2;
+        const float s_y = a.s_a[z * a.st_s_a] * a.s_w[0];
+        const float s_e = a.e_acc ? a.s_h[z * a.st_s_h] * a.s_w_up[0] : 0.0f;
+        const float d = 2.0f * a.coeff[z * a.st_coeff + m];
+        const uint4 av = ld_stream16(a.acc + z * a.st_acc + m * a.ldacc + j0);
+        uint4 ev = make_uint4(0u, 0u, 0u, 0u);
+        if (a.e_acc) ev = ld_stream16(a.e_acc + z * a.st_e + m * a.lde + j0);
+        const int ai[4] = {(int)av.x, (int)av.y, (int)av.z, (int)av.w};
+        const int ei[4] = {(int)ev.x, (int)ev.y, (int)ev.z, (int)ev.w};
+        float hv[4], gv[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float y = (float)ai[c] * s_y;
+            if (a.relu && y < 0.0f) y = 0.0f;
+            const float t = d * y;
+            const float E = a.e_acc ? (float)ei[c] * s_e : 0.0f;
+            const bool live = (!a.relu || ai[c] > 0) && j0 + c < a.N;
+            hv[c] = live ? t + E : 0.0f;
+            gv[c] = live ? __builtin_fmaf(a.lambda, E, t) : 0.0f;
+            mh = max(mh, __float_as_uint(hv[c]) & 0x7FFFFFFFu);
+            mg = max(mg, __float_as_uint(gv[c]) & 0x7FFFFFFFu);
+        }
+        float* gp = a.g + z * a.st_out + m * a.N + j0;
+        float* hp = a.h ? a.h + z * a.st_out + m * a.N + j0 : nullptr;
+        if (VEC) {
+            *(float4*)gp = make_float4(gv[0], gv[1], gv[2], gv[3]);
+            if (hp) *(float4*)hp = make_float4(hv[0], hv[1], hv[2], hv[3]);
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (j0 + c < a.N) {
+                    gp[c] = gv[c];
+                    if (hp) hp[c] = hv[c];
+                }
+        }
+    }
+    block_atomic_max_bits<256>(mg, a.g_amax_bits + z * a.st_amax);
+    if (a.h) {
+        __syncthreads();   // the reduction buffer of the first call is read by thread 0 until here
+        block_atomic_max_bits<256>(mh, a.h_amax_bits + z * a.st_amax);
+    }
+}
+
+hipError_t launch_chain_combine(const ChainArgs& a, hipStream_t s)
+{
+    if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    const int64_t total = a.M * ((a.N + 3) >> 2);
+    const int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks, (unsigned)a.nb);
+    const bool vec = (a.N & 3) == 0 && ((((uintptr_t)a.g) & 15) == 0) && (!a.h || (((uintptr_t)a.h) & 15) == 0) &&
+                     (a.st_out & 3) == 0;
+    if (vec) hipLaunchKernelGGL(k_chain_combine<true>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(k_chain_combine<false>, grid, dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // weight update (HBM-bound: 4 B x (1 + n_terms) read + 4 B written per weight) with fused absmax.
 // One workgroup per (row, 4096-column segment); a thread owns four groups of four columns, 256 groups
 // apart, and issues all of its loads before the arithmetic.

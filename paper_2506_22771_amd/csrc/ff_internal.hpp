@@ -169,6 +169,38 @@ struct GoodnessFxArgs {
 };
 hipError_t launch_goodness_fx(const GoodnessFxArgs& a, hipStream_t s);
 
+// ---- exact-derivative look-ahead (Eq. (4) taken literally; dense ReLU stacks) -----------------------------------
+// Per element of one layer and pass: y = act(fp32(acc) * (s_a*s_w)), t = (2 c[b]) * y, E = fp32(e_acc) * (s_h*s_w_up)
+// (0 without e_acc: the last layer), mask = acc > 0 under ReLU:
+//   h = (t + E) * mask          -- handed down to the layer below (null h: not needed, first layer)
+//   g = fma(lambda, E, t) * mask -- this layer's own local gradient
+// and the absmax of both tensors (bit patterns, atomic max into zeroed slots).
+struct ChainArgs {
+    const int32_t* acc;  // [M, ldacc]
+    int64_t ldacc, st_acc;
+    const float* s_a;    // [z * st_s_a]
+    int32_t st_s_a;
+    const float* s_w;
+    const float* coeff;  // [B] per pass (stride st_coeff): dL/dG of THIS layer
+    int64_t st_coeff;
+    const int32_t* e_acc;  // [M, lde] or null
+    int64_t lde, st_e;
+    const float* s_h;      // [z * st_s_h]: scale of the int8 gradient handed down by the layer above
+    int32_t st_s_h;
+    const float* s_w_up;   // weight scale of the layer above
+    float lambda;
+    int32_t relu;
+    int64_t M, N;
+    float* h;  // [M, N] contiguous per pass (stride st_out), may be null
+    float* g;  // [M, N] contiguous per pass
+    int64_t st_out;
+    uint32_t* h_amax_bits;  // [z * st_amax], zeroed; may be null with h
+    uint32_t* g_amax_bits;
+    int32_t st_amax;
+    int32_t nb;
+};
+hipError_t launch_chain_combine(const ChainArgs& a, hipStream_t s);
+
 // absmax of the local gradient for one layer / pass: max_b |2 c[b]| * (float(vmax[b]) * s_y) -> slot bits.
 hipError_t launch_grad_amax(const float* coeff_total, const int32_t* vmax, const float* s_a,
                             const float* s_w, int64_t B, uint32_t* slot, hipStream_t s);

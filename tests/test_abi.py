@@ -124,3 +124,20 @@ def test_residual_topology_validation(ff):
     assert bad(1, input_back=2) == 0               # only the previous layer or the one before it
     assert bad(2, l2norm_out=1) == 0               # no normalised hand-off from a block output
     assert ws_bytes(L[:4], wl.batch) == 0          # stack ends in a projection
+
+
+def test_chain_lookahead_validation(ff):
+    """FF_LOOKAHEAD_CHAIN: plain dense stacks only; it needs more workspace than the default reading; an unknown mode
+    is an argument error (workspace 0)."""
+    import ctypes as C
+    from workloads import workload
+
+    def nbytes(name, mode):
+        wl = workload(name)
+        descs = (ff.binding.LayerDesc * len(wl.layers))(*[ff.layer_desc(l, wl.batch) for l in wl.layers])
+        return ff.lib().ff_workspace_bytes(C.byref(ff.binding.NetDesc(len(wl.layers), wl.batch, descs, None, mode)))
+
+    assert nbytes("tiny", 1) > nbytes("tiny", 0) > 0
+    assert nbytes("cfg5", 1) > nbytes("cfg5", 0)
+    assert nbytes("tiny_l2", 1) == 0 and nbytes("tiny_conv", 1) == 0 and nbytes("tiny_res", 1) == 0
+    assert nbytes("tiny", 2) == 0 and nbytes("tiny", -1) == 0

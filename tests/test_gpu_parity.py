@@ -347,8 +347,10 @@ def test_conv_weight_gradient_chunks(ff):
 
 
 # ------------------------------------------------------------------------------------------- whole step
-def _run_steps(ff, wl, n_steps, lam=None):
+def _run_steps(ff, wl, n_steps, lam=None, lookahead="coeff", theta=None):
     lam = wl.lam if lam is None else lam
+    theta = wl.theta if theta is None else theta
+    oracle_step = O.train_step if lookahead == "coeff" else O.train_step_chain
     W = make_weights(wl)
     xp, xn = make_inputs(wl)
     k, B = len(wl.layers), wl.batch
@@ -358,7 +360,7 @@ def _run_steps(ff, wl, n_steps, lam=None):
     ws1 = workspace()
     for i, l in enumerate(wl.layers):
         ff.ff_quantize(d_w[i], l.N, l.K, 0, 0, 0, d_wq[i], None, d_sw[i], ws1)
-    net = ff.Net(wl.layers, B, d_w, d_wq, d_sw)
+    net = ff.Net(wl.layers, B, d_w, d_wq, d_sw, lookahead=lookahead)
     nbytes = net.workspace_bytes()
     assert nbytes > 0
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
@@ -367,9 +369,9 @@ def _run_steps(ff, wl, n_steps, lam=None):
     d_xp, d_xn = dev(xp), dev(xn)
     Wref = W
     for step in range(n_steps):
-        ff.ff_train_step(net, d_xp, d_xn, wl.theta, lam, wl.lr, wl.sr_seed, step, loss, good, ws)
+        ff.ff_train_step(net, d_xp, d_xn, theta, lam, wl.lr, wl.sr_seed, step, loss, good, ws)
         torch.cuda.synchronize()
-        ref = O.train_step(wl.layers, Wref, xp, xn, wl.theta, lam, wl.lr, wl.sr_seed, step, keep=False)
+        ref = oracle_step(wl.layers, Wref, xp, xn, theta, lam, wl.lr, wl.sr_seed, step, keep=False)
         Wref = ref["w_master"]
         assert rel_close(good.cpu().numpy(), ref["goodness"], TOL), f"goodness step {step}"
         assert rel_close(loss.cpu().numpy(), ref["loss"], TOL), f"loss step {step}"
@@ -434,3 +436,76 @@ def test_train_step_lambda_zero_and_reproducible(ff):
     b = _run_steps(ff, wl, 2, lam=0.0)
     for x, y in zip(a, b):
         np.testing.assert_array_equal(x, y)
+
+
+# ------------------------------------------------------------------- exact-derivative look-ahead (Eq. (4) literally)
+@pytest.mark.parametrize("B,K,N,relu", [(5, 20, 12, 1), (33, 100, 72, 1), (64, 500, 500, 1), (7, 36, 10, 0), (130, 300, 258, 1)])
+def test_chain_gradients_and_input_gradient(ff, B, K, N, relu):
+    """The two operations of the variant, each against the oracle: the fp32 gradients h and g with their absmax
+    (bit-exact: a fixed sequence of fp32 operations), their int8 codes through ff_quantize, and the int32
+    input-gradient contraction e = h_q W_q through the transposed int8 weights."""
+    rng = np.random.default_rng(B + N)
+    layer = _dense(B, K, N, relu=relu)
+    desc = ff.layer_desc(layer, B)
+    acc = rng.integers(-40000, 40000, (B, N)).astype(np.int32)
+    e_in = rng.integers(-9000, 9000, (B, N)).astype(np.int32)
+    c = (rng.standard_normal(B) * 0.4).astype(np.float32)
+    s_a, s_w, s_h, s_wu, lam = np.float32(0.0021), np.float32(0.0007), np.float32(0.004), np.float32(0.0009), 0.35
+    for e_acc in (e_in, None):
+        h_ref, g_ref = O.chain_combine(acc, relu, s_a, s_w, c, e_acc, np.float32(s_h) * np.float32(s_wu), lam)
+        h = torch.full((B, N), float("nan"), device="cuda")
+        g = torch.full((B, N), float("nan"), device="cuda")
+        h_amax, g_amax = scalar(), scalar()
+        ff.ff_chain_gradients(desc, dev(pad32(acc)), dev(np.array([s_a])), dev(np.array([s_w])), dev(c),
+                              None if e_acc is None else dev(pad32(e_acc)), dev(np.array([s_h])), dev(np.array([s_wu])),
+                              lam, h, g, h_amax, g_amax)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(h.cpu().numpy(), h_ref)
+        np.testing.assert_array_equal(g.cpu().numpy(), g_ref)
+        assert h_amax.item() == np.abs(h_ref).max() and g_amax.item() == np.abs(g_ref).max()
+    # quantise h as the step does and contract it with the transposed weights
+    w = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    w_q, _ = O.quantize(w, 0)
+    hq_ref, sh_ref = O.quantize(h_ref, 1, 9, 77)
+    e_ref = O.dense_input_grad(hq_ref, w_q)
+    hq, sh, wqt, swt = empty8(B, N), scalar(), empty8(K, N), scalar()
+    ff.ff_quantize(h, B, N, 1, 9, 77, hq, None, sh, workspace())
+    ff.ff_quantize(dev(w), N, K, 0, 0, 0, None, wqt, swt, workspace())
+    e = empty32(B, K)
+    ff.ff_layer_input_grad(desc, hq, wqt, e, workspace())
+    torch.cuda.synchronize()
+    assert sh.item() == sh_ref
+    check_q(hq, hq_ref, "h_q")
+    check_q(wqt, np.ascontiguousarray(w_q.T), "w_q_t")
+    np.testing.assert_array_equal(e.cpu().numpy()[:, :K], e_ref)
+
+
+@pytest.mark.parametrize("name,steps,lam,theta", [("tiny", 3, 0.25, 19.0), ("tiny", 2, 0.0, 2.0), ("cfg1", 2, 0.5, 158.0),
+                                                  ("cfg2_plain", 1, 0.05, 2.0)])
+def test_train_step_chain(ff, name, steps, lam, theta):
+    """Whole steps of the variant against the oracle: ragged widths (100-72-52), the MNIST-shaped stack, and a
+    deeper one (784-2000^4 without the normalisation the variant does not cover)."""
+    if name == "cfg2_plain":
+        from workloads import Workload, mlp
+        wl = Workload("cfg2_plain", mlp([784, 2000, 2000, 2000, 2000], False), 256, "uniform_onehot", lam=lam)
+    else:
+        wl = workload(name)
+    _run_steps(ff, wl, steps, lam=lam, lookahead="chain", theta=theta)
+
+
+def test_train_step_chain_rejects_what_it_does_not_cover(ff):
+    for name in ("tiny_l2", "tiny_conv"):
+        wl = workload(name)
+        W = make_weights(wl)
+        d_w = [dev(w.reshape(w.shape[0], -1)) for w in W]
+        net = ff.Net(wl.layers, wl.batch, d_w, [empty8(l.N, l.K) for l in wl.layers], [scalar() for _ in wl.layers],
+                     lookahead="chain")
+        assert net.workspace_bytes() == 0
+
+
+@pytest.mark.slow
+@pytest.mark.timeout(1200)
+def test_train_step_chain_cfg5_full_size(ff):
+    """The variant at the large-GEMM configuration (8192+8192 samples, 4096->4096->4096): the input-gradient
+    contraction runs at the forward contraction's shape."""
+    _run_steps(ff, workload("cfg5"), 1, lookahead="chain")

@@ -30,7 +30,7 @@ INT8_MFMA_PEAK_TOPS = 256 * 2.4e9 * 8192 / 1e12   # 256 CUs x 2.4 GHz x 8192 int
 HBM_PEAK_GBS = 8000.0
 
 
-def setup(ff, torch, wl):
+def setup(ff, torch, wl, lookahead="coeff"):
     from workloads import make_inputs, make_weights
     W = make_weights(wl)
     xp, xn = make_inputs(wl)
@@ -41,7 +41,9 @@ def setup(ff, torch, wl):
     ws1 = torch.empty(ff.WS_MIN_BYTES, dtype=torch.uint8, device="cuda")
     for i, l in enumerate(wl.layers):
         ff.ff_quantize(d_w[i], l.N, l.K, ff.ROUND_NEAREST, 0, 0, d_wq[i], None, d_sw[i], ws1)
-    net = ff.Net(wl.layers, B, d_w, d_wq, d_sw)
+    net = ff.Net(wl.layers, B, d_w, d_wq, d_sw, lookahead=lookahead)
+    if net.workspace_bytes() == 0:
+        raise SystemExit(f"bench.py: workload {wl.name} is not covered by --lookahead {lookahead}")
     ws = torch.empty(net.workspace_bytes(), dtype=torch.uint8, device="cuda")
     loss = torch.empty((k, 2), device="cuda")
     good = torch.empty((k, 2, B), device="cuda")
@@ -50,7 +52,7 @@ def setup(ff, torch, wl):
     return net, d_xp, d_xn, loss, good, ws
 
 
-def cpu_baseline(wl, sample_batch: int):
+def cpu_baseline(wl, sample_batch: int, lookahead: str = "coeff"):
     """The CPU oracle as it stands, timed on this host, on a smaller batch of the same network."""
     from oracle import ff_oracle as O
     from workloads import make_inputs, make_weights, scaled
@@ -59,7 +61,8 @@ def cpu_baseline(wl, sample_batch: int):
     xp, xn = make_inputs(small)
     O.lib()
     t0 = time.perf_counter()
-    O.train_step(small.layers, W, xp, xn, small.theta, small.lam, small.lr, small.sr_seed, 0, keep=False)
+    step = O.train_step if lookahead == "coeff" else O.train_step_chain
+    step(small.layers, W, xp, xn, small.theta, small.lam, small.lr, small.sr_seed, 0, keep=False)
     dt = time.perf_counter() - t0
     try:
         cores = len(os.sched_getaffinity(0))
@@ -132,6 +135,8 @@ def main() -> int:
                     help="also run one plain 1 GiB-read / 1 GiB-write elementwise kernel (torch.add) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against known traffic")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph-replay timing")
+    ap.add_argument("--lookahead", choices=("coeff", "chain"), default="coeff",
+                    help="chain: the exact-derivative variant of the look-ahead (dense stacks; one more contraction per layer)")
     ap.add_argument("--gemm-data-probe", action="store_true",
                     help="instead of the train step, time the forward contraction of the first layer on Gaussian, "
                          "constant and zero int8 operands (same kernel and traffic; shows the clock/power effect)")
@@ -154,7 +159,7 @@ def main() -> int:
     if args.gemm_data_probe:
         print(json.dumps(gemm_data_probe(ff, torch, wl)))
         return 0
-    net, d_xp, d_xn, loss, good, ws = setup(ff, torch, wl)
+    net, d_xp, d_xn, loss, good, ws = setup(ff, torch, wl, args.lookahead)
     k, B = len(wl.layers), wl.batch
 
     if args.pmc_calibration:
@@ -267,7 +272,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8 (int32 accumulate; fp32 scales, goodness, master weights)", "data": "synthetic",
         "config": {"workload": wl.name, "layers": [f"{l.K}->{l.N}" for l in wl.layers],
-                   "batch_pos": B, "batch_neg": B, "lambda": wl.lam, "theta": wl.theta, "lr": wl.lr,
+                   "batch_pos": B, "batch_neg": B, "lookahead": args.lookahead, "lambda": wl.lam, "theta": wl.theta, "lr": wl.lr,
                    "layer_steps_per_step": k, "whole_step_samples_per_s": samples / (ms_per_step * 1e-3),
                    "int8_TOPs_whole_step": ops_per_step / (ms_per_step * 1e-3) / 1e12},
         "int8_mfma_pct_of_peak": 100.0 * achieved / INT8_MFMA_PEAK_TOPS,
@@ -280,7 +285,7 @@ def main() -> int:
     }
     if not args.no_cpu_baseline:
         sb = args.cpu_sample_batch or {"cfg5": 8192, "cfg2": 1024, "cfg1": 64, "cfg3": 64, "cfg4_plain": 32}.get(wl.name, min(B, 256))
-        out["cpu_baseline"] = cpu_baseline(wl, min(sb, B))
+        out["cpu_baseline"] = cpu_baseline(wl, min(sb, B), args.lookahead)
     print(json.dumps(out))
     return 0
 

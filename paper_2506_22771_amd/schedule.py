@@ -41,9 +41,10 @@ class TrainState:
             ff.ff_quantize(w_master[i], l.N, l.K, ff.ROUND_NEAREST, 0, 0, w_q[i], None, s_w[i], ws)
         return TrainState(layers, batch, w_master, w_q, s_w)
 
-    def net(self, n_layers: Optional[int] = None, train_layer: Optional[Sequence[int]] = None) -> ff.Net:
+    def net(self, n_layers: Optional[int] = None, train_layer: Optional[Sequence[int]] = None,
+            lookahead: str = "coeff") -> ff.Net:
         k = len(self.layers) if n_layers is None else n_layers
-        return ff.Net(self.layers[:k], self.batch, self.w_master[:k], self.w_q[:k], self.s_w[:k], train_layer)
+        return ff.Net(self.layers[:k], self.batch, self.w_master[:k], self.w_q[:k], self.s_w[:k], train_layer, lookahead)
 
 
 @dataclass
@@ -81,10 +82,11 @@ def _run(net: ff.Net, batches, n_iter_epochs: int, theta: float, lr: float, seed
 
 def train_lookahead(state: TrainState, batches: Sequence[Tuple[torch.Tensor, torch.Tensor]], epochs: int,
                     theta: float, lr: float, seed: int, lam0: float = 0.0, dlam: float = 0.001, step0: int = 0,
-                    log_every: int = 1) -> History:
-    """Algorithm 1 for `epochs` passes over `batches`; lambda = lam0 + epoch * dlam (Section V-A)."""
+                    log_every: int = 1, lookahead: str = "coeff") -> History:
+    """Algorithm 1 for `epochs` passes over `batches`; lambda = lam0 + epoch * dlam (Section V-A).
+    lookahead = "chain": Eq. (4) as an exact derivative through the later layers (dense stacks only)."""
     hist = History()
-    _run(state.net(), batches, epochs, theta, lr, seed, step0, lam0, dlam, hist, log_every)
+    _run(state.net(lookahead=lookahead), batches, epochs, theta, lr, seed, step0, lam0, dlam, hist, log_every)
     return hist
 
 

@@ -21,13 +21,13 @@ def ff():
     return m
 
 
-def _setup(ff, wl):
+def _setup(ff, wl, lookahead="coeff"):
     from paper_2506_22771_amd import schedule
     W = make_weights(wl)
     xp, xn = make_inputs(wl)
     B, k = wl.batch, len(wl.layers)
     st = schedule.TrainState.from_weights(wl.layers, B, W)
-    net = st.net()
+    net = st.net(lookahead=lookahead)
     ws = torch.empty(net.workspace_bytes(), dtype=torch.uint8, device="cuda")
     loss = torch.empty((k, 2), device="cuda")
     good = torch.empty((k, 2, B), device="cuda")
@@ -63,10 +63,11 @@ def test_step_at_equals_step(ff, name):
     assert int(step_dev.item()) == 8
 
 
-@pytest.mark.parametrize("name", ["tiny_l2", "cfg1", "tiny_conv16"])
+@pytest.mark.parametrize("name", ["tiny_l2", "cfg1", "tiny_conv16", "tiny/chain"])
 def test_captured_graph_replays_match_eager_steps(ff, name):
+    name, _, mode = name.partition("/")
     wl = workload(name)
-    a, b = _setup(ff, wl), _setup(ff, wl)
+    a, b = _setup(ff, wl, mode or "coeff"), _setup(ff, wl, mode or "coeff")
     step_dev = torch.zeros(1, dtype=torch.int64, device="cuda")
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):

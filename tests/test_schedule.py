@@ -135,6 +135,35 @@ def test_masked_step_matches_oracle(ff, name):
 
 
 @pytest.mark.gpu
+def test_masked_chain_step_and_lambda_ramp_match_oracle(ff):
+    """The exact-derivative look-ahead with a frozen middle layer (its gradient still reaches the layer below), then
+    the lambda ramp over it, bit for bit against the oracle's loop."""
+    from workloads import Workload, mlp
+    wl = Workload("tiny3", mlp([60, 44, 36, 28], False), 20, "uniform_onehot", theta=12.0, lam=0.3)
+    schedule, st, W, xp, xn, batch = _state(ff, wl)
+    k = 3
+    mask = [1, 0, 1]
+    net = st.net(k, mask, lookahead="chain")
+    ws = torch.empty(net.workspace_bytes(), dtype=torch.uint8, device="cuda")
+    loss = torch.empty((k, 2), device="cuda")
+    good = torch.empty((k, 2, wl.batch), device="cuda")
+    ff.ff_train_step(net, batch[0], batch[1], wl.theta, wl.lam, wl.lr, wl.sr_seed, 5, loss, good, ws)
+    torch.cuda.synchronize()
+    ref = O.train_step_chain(wl.layers, W, xp, xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, 5, keep=False, train_mask=mask)
+    for i in range(k):
+        np.testing.assert_array_equal(st.w_master[i].cpu().numpy().reshape(-1), ref["w_master"][i].reshape(-1))
+        assert st.s_w[i].item() == ref["s_w"][i]
+    assert not np.array_equal(ref["w_master"][0], W[0]) and np.array_equal(ref["w_master"][1], W[1])
+    Wref = ref["w_master"]
+    schedule.train_lookahead(st, [batch], 3, wl.theta, wl.lr, wl.sr_seed, lam0=0.1, dlam=0.2, step0=6, lookahead="chain")
+    torch.cuda.synchronize()
+    for e in range(3):
+        Wref = O.train_step_chain(wl.layers, Wref, xp, xn, wl.theta, 0.1 + 0.2 * e, wl.lr, wl.sr_seed, 6 + e, keep=False)["w_master"]
+    for i in range(k):
+        np.testing.assert_array_equal(st.w_master[i].cpu().numpy().reshape(-1), Wref[i].reshape(-1))
+
+
+@pytest.mark.gpu
 def test_greedy_schedule_matches_oracle(ff):
     wl = workload("tiny_l2")
     schedule, st, W, xp, xn, batch = _state(ff, wl)

@@ -1222,12 +1222,31 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
             ca.g_amax_bits = g_amax + 2 * i;
             ca.st_amax = 1;
             ca.nb = 2;
-            HIPCHK_T(FF_K_CHAIN, launch_chain_combine(ca, s));
-
+            // The last layer has nothing ahead of it: h = g = 2 c y, which the quantiser forms straight from the
+            // accumulators (absmax by monotonicity, as in the default step); no fp32 tensors are written.
+            const bool top = i == k - 1;
+            int qsrc = QSRC_F32;
             QuantArgs a;
             memset(&a, 0, sizeof(a));
-            a.x = gf;
-            a.st_x = st_f;
+            if (top) {
+                for (int p = 0; p < 2; ++p)
+                    HIPCHK_T(FF_K_SMALL, launch_grad_amax(c + ((int64_t)i * 2 + p) * B, vmax + ((int64_t)i * 2 + p) * B,
+                                                          s_a + 2 * i + p, state->s_w[i], B, g_amax + 2 * i + p, s));
+                qsrc = QSRC_GRAD;
+                a.acc = ca.acc;
+                a.st_acc = ca.st_acc;
+                a.ldacc = ca.ldacc;
+                a.s_a = ca.s_a;
+                a.st_s_a = 1;
+                a.s_w = ca.s_w;
+                a.per_sample = ca.coeff;
+                a.st_per_sample = B;
+                a.relu = ca.relu;
+            } else {
+                HIPCHK_T(FF_K_CHAIN, launch_chain_combine(ca, s));
+                a.x = gf;
+                a.st_x = st_f;
+            }
             a.rows_per_sample = 1;
             a.amax_bits = g_amax + 2 * i;
             a.st_amax = 1;
@@ -1246,12 +1265,14 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
             a.scale = s_g + 2 * i;
             a.st_scale = 1;
             a.nb = 2;
-            if (trained(i)) HIPCHK_T(FF_K_QUANT_GRAD, launch_quantize(QSRC_F32, a, s));
+            if (trained(i)) HIPCHK_T(FF_K_QUANT_GRAD, launch_quantize(qsrc, a, s));
 
             if (i > 0) {
                 QuantArgs hqa = a;
-                hqa.x = hf;
-                hqa.amax_bits = h_amax + 2 * i;
+                if (!top) {
+                    hqa.x = hf;
+                    hqa.amax_bits = h_amax + 2 * i;
+                }
                 hqa.key = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 0, FF_KIND_CHAIN));
                 hqa.key2 = make_sr_key(seed, ff_stream_tag(step, (uint32_t)i, 1, FF_KIND_CHAIN));
                 hqa.tag_kind = FF_KIND_CHAIN;
@@ -1262,7 +1283,7 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
                 hqa.st_q = (int64_t)w.st_hq;
                 hqa.ldq = pitch8(d.N);
                 hqa.scale = s_h;
-                HIPCHK_T(FF_K_CHAIN, launch_quantize(QSRC_F32, hqa, s));
+                HIPCHK_T(FF_K_CHAIN, launch_quantize(qsrc, hqa, s));
 
                 // transposed int8 copy of the pre-step weights: the same codes as w_q, [K, pitch(N)]
                 const int64_t nw = d.N * d.K;

@@ -296,6 +296,7 @@ ff_status ff_layer_update(const ff_layer_desc* layer, float* w_master, const int
  *   goodness      fp32 [n_layers, 2, batch]                                           (out)
  *   ws            >= ff_workspace_bytes(net) bytes
  * Stochastic rounding streams: ff_stream_tag(step, layer, pass, kind) under `seed`.
+ * net->lookahead selects how the later layers' losses enter (see FF_LOOKAHEAD_COEFF / FF_LOOKAHEAD_CHAIN above).
  * ------------------------------------------------------------------------------------------- */
 ff_status ff_train_step(const ff_net_desc* net, const ff_net_state* state, const float* x_pos,
                         const float* x_neg, float theta, float lambda, float lr, uint64_t seed,

@@ -16,6 +16,7 @@ struct Dims {
     int64_t B, M, K, N, rps;   // M rows per pass (dense: B; conv: B*Ho*Wo), rps rows per sample
     int64_t in_rows, in_cols;  // 2-D view of the layer input: dense [B, K]; conv [B*H*W, C_in]
     bool implicit;             // conv whose forward runs as an implicit GEMM (C_in % 16 == 0)
+    bool pointwise;            // 1x1 stride-1 convolution: its transposed patch matrix is the transposed input itself
     ConvGeom g;                // conv only
     int n_chunks;              // weight-gradient accumulators per pass
     int64_t chunk_b;           // samples per accumulator
@@ -60,6 +61,7 @@ static ff_status layer_dims(const ff_layer_desc* L, Dims* d)
         d->in_rows = d->B * L->H * L->W;
         d->in_cols = L->C_in;
         d->implicit = L->kind == FF_CONV2D && (L->C_in & 15) == 0;
+        d->pointwise = L->kind == FF_CONV2D && L->ksize == 1 && L->stride == 1;
         if (d->in_rows * g.cpitch >= (int64_t(1) << 31) || d->M >= (int64_t(1) << 31)) return FF_ERR_UNSUPPORTED;
     } else {
         return FF_ERR_INVALID_ARG;
@@ -98,11 +100,12 @@ static int32_t goodness_shift(int64_t K, int64_t terms)
 // Scratch one layer needs per pass beyond FF_WS_MIN_BYTES.
 // `col`: the row-major patch matrix of an explicit-im2col forward or the transposed patch matrix of one
 // weight-gradient chunk (conv only).  `part`: partial accumulators of a split weight-gradient reduction.
-static size_t layer_col_bytes(const Dims& d)
+// have_aqt: the caller keeps a transposed copy of a pointwise layer's input, which serves as its patch matrix.
+static size_t layer_col_bytes(const Dims& d, bool have_aqt = false)
 {
     if (d.kind != FF_CONV2D) return 0;   // dense and depthwise layers need no patch matrix
     const size_t fwd = d.implicit ? 0 : (size_t)(d.M * pitch8(d.K));
-    const size_t bwd = (size_t)(d.K * pitch8(d.chunk_b * d.rps));
+    const size_t bwd = have_aqt && d.pointwise ? 0 : (size_t)(d.K * pitch8(d.chunk_b * d.rps));
     return align_up(fwd > bwd ? fwd : bwd, 256);
 }
 static size_t layer_part_bytes(const Dims& d, int nb)
@@ -132,7 +135,7 @@ struct WsLayout {
     size_t off_col, st_col;          // int8 scratch [2][st_col]: patch matrices of conv layers
     size_t off_part, st_part;        // int32 scratch [2][st_part] (bytes): partial sums of split weight gradients
     size_t off_aq[MAX_LAYERS], st_aq[MAX_LAYERS];    // quantised layer input [2][st]: dense layers share one scratch
-    size_t off_aqt[MAX_LAYERS], st_aqt[MAX_LAYERS];  // dense only: transposed quantised input [2][st], retained
+    size_t off_aqt[MAX_LAYERS], st_aqt[MAX_LAYERS];  // dense and 1x1 stride-1 conv: transposed quantised input [2][st], retained
     size_t off_acc[MAX_LAYERS], st_acc[MAX_LAYERS];  // int32 accumulators [2][st] (bytes), retained
     size_t off_y[MAX_LAYERS], st_y[MAX_LAYERS];      // residual layers: fp32 block output [2][st] (bytes), retained
     // exact-derivative look-ahead only (all sizes 0 otherwise)
@@ -228,7 +231,7 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
         if (d.kind == FF_DENSE) aq_dense = max(aq_dense, (size_t)(d.in_rows * pitch8(d.in_cols)));
         gy = max(gy, d.kind == FF_DWCONV2D ? (size_t)(d.M * pitch8(d.N)) : (size_t)(d.N * pitch8(d.M)));
         dw = max(dw, (size_t)(d.N * pitch32(d.K)) * sizeof(int32_t));
-        col = max(col, layer_col_bytes(d));
+        col = max(col, layer_col_bytes(d, true));
         part = max(part, layer_part_bytes(d, 2));
     }
     aq_dense = align_up(aq_dense, A);
@@ -259,8 +262,9 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
             w->st_aq[i] = align_up((size_t)(d.in_rows * pitch8(d.in_cols)), A);
             w->off_aq[i] = off;
             off += 2 * w->st_aq[i];
-            w->st_aqt[i] = 0;
-            w->off_aqt[i] = 0;
+            w->st_aqt[i] = d.pointwise ? align_up((size_t)(d.K * pitch8(d.M)), A) : 0;
+            w->off_aqt[i] = d.pointwise ? off : 0;
+            off += 2 * w->st_aqt[i];
         }
         w->st_acc[i] = align_up((size_t)(d.M * pitch32(d.N)) * sizeof(int32_t), A);
         w->off_acc[i] = off;
@@ -434,11 +438,11 @@ static bool wgrad_uses_planes(const Dims& d, int64_t nbatch, int nb)
 }
 
 // Weight gradient: dw[z][c] = gy_q_t[z][:, chunk c] x (patches of chunk c)^T for every chunk c.
-// `aqt` is the transposed quantised input (dense) or the NHWC quantised input (conv; patches are materialised
-// chunk by chunk into `colT`).  dw accumulators of one pass are dw_elems apart.
+// `aqt` is the transposed quantised input (dense; also a 1x1 stride-1 convolution when aqt_transposed is set) or the
+// NHWC quantised input (conv; patches are materialised chunk by chunk into `colT`).  dw accumulators of one pass are dw_elems apart.
 static ff_status run_wgrad(const Dims& d, const int8_t* gy_t, int64_t st_gy, const int8_t* aqt, int64_t st_aqt,
                            int8_t* colT, int64_t st_colT, int32_t* part, int64_t st_part, int32_t* dw, int64_t st_dw,
-                           int64_t dw_elems, int nb, hipStream_t s)
+                           int64_t dw_elems, int nb, hipStream_t s, bool aqt_transposed = false)
 {
     for (int c = 0; c < d.n_chunks; ++c) {
         const int64_t b0 = c * d.chunk_b, b1 = min(d.B, b0 + d.chunk_b);
@@ -477,7 +481,7 @@ static ff_status run_wgrad(const Dims& d, const int8_t* gy_t, int64_t st_gy, con
         g.ldc = pitch32(d.K);
         g.rows_per_sample = 1;
         g.nb = nb;
-        if (d.kind == FF_DENSE) {
+        if (d.kind == FF_DENSE || aqt_transposed) {   // a 1x1 stride-1 convolution is a dense layer over its pixels
             g.Q = aqt + m0;
             g.st_q = st_aqt;
             g.ldq = pitch8(d.M);
@@ -1007,7 +1011,7 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         a.q = (int8_t*)(base + w.off_aq[i]);
         a.st_q = (int64_t)w.st_aq[i];
         a.ldq = pitch8(d.in_cols);
-        if (dense) {
+        if (dense || d.pointwise) {
             a.q_t = (int8_t*)(base + w.off_aqt[i]);
             a.st_qt = (int64_t)w.st_aqt[i];
             a.ldqt = pitch8(d.M);
@@ -1131,14 +1135,14 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
     // contraction per pass and chunk, combined update, requantisation
     auto wgrad_update = [&](int t, int gl) -> ff_status {
         const Dims& d = w.d[t];
-        const bool dense = d.kind == FF_DENSE;
+        const bool dense = d.kind == FF_DENSE || d.pointwise;   // layers that keep a transposed copy of their input
         const int64_t dw_elems = (int64_t)(w.dw_bytes / sizeof(int32_t));
         const ff_status ws_ = run_wgrad(d, (const int8_t*)(base + w.off_gy), (int64_t)w.st_gy,
                                         dense ? (const int8_t*)(base + w.off_aqt[t]) : (const int8_t*)(base + w.off_aq[t]),
                                         dense ? (int64_t)w.st_aqt[t] : (int64_t)w.st_aq[t], (int8_t*)(base + w.off_col),
                                         (int64_t)w.st_col, (int32_t*)(base + w.off_part),
                                         (int64_t)(w.st_part / sizeof(int32_t)), (int32_t*)(base + w.off_dw),
-                                        (int64_t)(w.st_dw / sizeof(int32_t)), dw_elems, 2, s);
+                                        (int64_t)(w.st_dw / sizeof(int32_t)), dw_elems, 2, s, d.pointwise);
         if (ws_ != FF_OK) return ws_;
 
         UpdateArgs u;

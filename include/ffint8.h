@@ -183,8 +183,8 @@ ff_status ff_layer_forward(const ff_layer_desc* layer, const int8_t* a_q, const 
  *   - M = batch * H_out * W_out rows (one per output pixel, NHWC order), K = ksize^2 * C_in with the reduction
  *     index ordered (kh, kw, ci), N = C_out.  a_q is the NHWC int8 input [batch, H, W, ff_pitch(C_in)]
  *     (what ff_quantize writes for rows = batch*H*W, cols = C_in); w_q is [C_out, ff_pitch(K)].
- *   - ff_layer_forward runs an implicit GEMM when C_in % 16 == 0; otherwise it first writes the patch matrix
- *     into ws.  ff_layer_backward_local takes the SAME NHWC a_q in its a_q_t argument and materialises the
+ *   - ff_layer_forward runs an implicit GEMM when C_in % 16 == 0 (a 1x1 stride-1 convolution reads a_q as the
+ *     dense operand it is, for any C_in); otherwise it first writes the patch matrix into ws.  ff_layer_backward_local takes the SAME NHWC a_q in its a_q_t argument and materialises the
  *     transposed patches of one weight-gradient chunk at a time in ws.  Both need
  *     ws_bytes >= ff_layer_workspace_bytes(layer).
  *   - A weight-gradient reduction over more than 133144 rows (M * 127^2 would not fit int32) is split into

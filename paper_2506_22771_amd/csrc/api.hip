@@ -104,7 +104,7 @@ static int32_t goodness_shift(int64_t K, int64_t terms)
 static size_t layer_col_bytes(const Dims& d, bool have_aqt = false)
 {
     if (d.kind != FF_CONV2D) return 0;   // dense and depthwise layers need no patch matrix
-    const size_t fwd = d.implicit ? 0 : (size_t)(d.M * pitch8(d.K));
+    const size_t fwd = d.implicit || d.pointwise ? 0 : (size_t)(d.M * pitch8(d.K));
     const size_t bwd = have_aqt && d.pointwise ? 0 : (size_t)(d.K * pitch8(d.chunk_b * d.rps));
     return align_up(fwd > bwd ? fwd : bwd, 256);
 }
@@ -350,7 +350,7 @@ struct Timed {
 
 // ---- the two contractions of a layer, for nb passes at once ------------------------------------------
 // Forward: acc[z] = A_q[z] x W_q^T (+ per-sample sums).  `aq` is the quantised layer input (dense: [M, pitch(K)];
-// conv: NHWC), `col` scratch for an explicit patch matrix (conv with C_in % 16 != 0).
+// conv: NHWC), `col` scratch for an explicit patch matrix (3x3 or strided conv with C_in % 16 != 0).
 static ff_status run_forward(const Dims& d, int relu, const int8_t* aq, int64_t st_aq, const int8_t* w_q, int32_t* acc,
                              int64_t st_acc, unsigned long long* gsum, int32_t* vmax, int64_t st_g, int8_t* col,
                              int64_t st_col, int nb, hipStream_t s)
@@ -394,7 +394,8 @@ static ff_status run_forward(const Dims& d, int relu, const int8_t* aq, int64_t 
     g.rshift = goodness_shift(d.K, d.rps * d.N);
     g.nb = nb;
     g.splits = 1;
-    if (d.kind == FF_DENSE) {
+    if (d.kind == FF_DENSE || d.pointwise) {
+        // (a 1x1 stride-1 convolution: the NHWC input [B*H*W, pitch(C_in)] is its own patch matrix)
         g.P = aq;
         g.st_p = st_aq;
         g.ldp = pitch8(d.K);

@@ -305,13 +305,23 @@ __global__ __launch_bounds__(256) void k_dwconv_forward(DwArgs p, int cgroups)
                                             (i32x4*)(p.acc + z * p.st_acc + ((int64_t)b * hw + pix) * p.ldacc + c0));
             }
             if (p.gsum) {
+                // channels beyond C read zero inputs and zero weights: their y is 0
+                if (p.relu && p.rshift == 0) {        // the usual case: one 32x32+64-bit multiply-add per activity
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    int y = acc[e];                   // channels beyond C read zero inputs and zero weights: y == 0
-                    if (p.relu) y = max(y, 0);
-                    const long long yl = (long long)y;
-                    sq += ((unsigned long long)(yl * yl)) >> p.rshift;
-                    vm = max(vm, y < 0 ? -y : y);
+                    for (int e = 0; e < 4; ++e) {
+                        const unsigned y = (unsigned)max(acc[e], 0);
+                        sq += (unsigned long long)y * y;
+                        vm = max(vm, (int)y);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        int y = acc[e];
+                        if (p.relu) y = max(y, 0);
+                        const long long yl = (long long)y;
+                        sq += ((unsigned long long)(yl * yl)) >> p.rshift;
+                        vm = max(vm, y < 0 ? -y : y);
+                    }
                 }
             }
         }

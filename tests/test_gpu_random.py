@@ -1,0 +1,95 @@
+"""Seeded sweeps over random small shapes: the same comparisons as tests/test_gpu_parity.py (HIP library against the
+CPU oracle, int8 / int32 bit-exact, fp32 within 1e-5), on shapes nobody picked by hand — odd sizes, single rows and
+columns, widths just past a tile or a 16-byte boundary."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+
+import test_gpu_parity as P  # noqa: E402
+from test_gpu_parity import ff  # noqa: E402,F401  (fixture)
+from workloads import Workload, conv_stack, mlp  # noqa: E402
+
+
+def _dims(rng, n, lo, hi):
+    """n sizes in [lo, hi], biased towards the edges of 16 / 64 / 256 blocks"""
+    out = []
+    for _ in range(n):
+        if rng.random() < 0.4:
+            base = int(rng.choice([16, 32, 64, 128, 256]))
+            v = base * int(rng.integers(1, max(2, hi // base + 1))) + int(rng.integers(-2, 3))
+        else:
+            v = int(rng.integers(lo, hi + 1))
+        out.append(int(min(max(v, lo), hi)))
+    return out
+
+
+def test_random_quantize_shapes(ff):
+    rng = np.random.default_rng(101)
+    for _ in range(24):
+        rows, cols = _dims(rng, 2, 1, 700)
+        P.test_quantize(ff, rows, cols, int(rng.integers(0, 2)))
+
+
+def test_random_dense_layers(ff):
+    rng = np.random.default_rng(202)
+    for _ in range(16):
+        B, K, N = _dims(rng, 3, 1, 600)
+        P.test_layer_forward(ff, B, K, N, int(rng.integers(0, 2)))
+        P.test_backward_local_and_update(ff, B, K, N)
+        P.test_chain_gradients_and_input_gradient(ff, B, K, N, int(rng.integers(0, 2)))
+
+
+def test_random_conv_layers(ff):
+    rng = np.random.default_rng(303)
+    for _ in range(16):
+        ks = int(rng.choice([1, 3]))
+        stride = int(rng.choice([1, 2]))
+        H, W = (int(v) for v in rng.integers(3, 21, 2))
+        if rng.random() < 0.4:            # maps the fast transposed-patch paths accept
+            H, W = int(rng.choice([4, 8, 16])), int(rng.choice([8, 16, 32]))
+        Cin = int(rng.choice([3, 5, 16, 24, 32, 40, 64, 70]))
+        Cout = int(rng.choice([4, 8, 20, 32, 64, 72]))
+        B = int(rng.integers(1, 7))
+        P.test_conv_forward_and_backward(ff, B, H, W, Cin, Cout, ks, stride)
+
+
+def test_random_depthwise_layers(ff):
+    rng = np.random.default_rng(404)
+    for _ in range(10):
+        H, W = (int(v) for v in rng.integers(3, 25, 2))
+        C = int(rng.choice([4, 6, 16, 20, 64, 68, 130]))
+        P.test_depthwise_forward_and_backward(ff, int(rng.integers(1, 6)), H, W, C, int(rng.choice([1, 2])))
+
+
+def test_random_dense_stacks(ff):
+    """Whole steps of random dense stacks, both readings of the look-ahead; theta near the goodness of the first
+    layer so that both passes carry a live gradient."""
+    rng = np.random.default_rng(505)
+    for case in range(6):
+        depth = int(rng.integers(2, 5))
+        widths = _dims(rng, depth + 1, 12, 300)     # the label overlay needs ten input features
+        widths = [w + (-w) % 4 for w in widths]    # activity widths: multiples of 4 like every configured network
+        B = int(rng.integers(2, 90))
+        norm = bool(rng.integers(0, 2))
+        wl = Workload(f"rand{case}", mlp(widths, norm), B, "uniform_onehot", lam=float(rng.choice([0.0, 0.1, 0.7])),
+                      theta=float(rng.choice([2.0, 10.0, 40.0])))
+        P._run_steps(ff, wl, 2)
+        if not norm:
+            P._run_steps(ff, wl, 2, lookahead="chain")
+
+
+def test_random_conv_stacks(ff):
+    rng = np.random.default_rng(606)
+    for case in range(4):
+        chans = [3] + [int(rng.choice([8, 16, 24, 32])) for _ in range(int(rng.integers(1, 4)))]
+        h, w = int(rng.choice([4, 6, 8, 12])), int(rng.choice([10, 11, 16]))   # the label overlay needs ten columns
+        wl = Workload(f"randc{case}", conv_stack(chans, h, w), int(rng.integers(2, 9)), "uniform_onehot",
+                      lam=float(rng.choice([0.0, 0.25])))
+        P._run_steps(ff, wl, 2)

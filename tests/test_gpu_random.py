@@ -14,7 +14,7 @@ sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 import test_gpu_parity as P  # noqa: E402
 from test_gpu_parity import ff  # noqa: E402,F401  (fixture)
-from workloads import Workload, conv_stack, mlp  # noqa: E402
+from workloads import Workload, bottleneck_stack, conv_stack, mlp, res_stack  # noqa: E402
 
 
 def _dims(rng, n, lo, hi):
@@ -32,14 +32,14 @@ def _dims(rng, n, lo, hi):
 
 def test_random_quantize_shapes(ff):
     rng = np.random.default_rng(101)
-    for _ in range(24):
+    for _ in range(60):
         rows, cols = _dims(rng, 2, 1, 700)
         P.test_quantize(ff, rows, cols, int(rng.integers(0, 2)))
 
 
 def test_random_dense_layers(ff):
     rng = np.random.default_rng(202)
-    for _ in range(16):
+    for _ in range(40):
         B, K, N = _dims(rng, 3, 1, 600)
         P.test_layer_forward(ff, B, K, N, int(rng.integers(0, 2)))
         P.test_backward_local_and_update(ff, B, K, N)
@@ -48,7 +48,7 @@ def test_random_dense_layers(ff):
 
 def test_random_conv_layers(ff):
     rng = np.random.default_rng(303)
-    for _ in range(16):
+    for _ in range(40):
         ks = int(rng.choice([1, 3]))
         stride = int(rng.choice([1, 2]))
         H, W = (int(v) for v in rng.integers(3, 21, 2))
@@ -62,7 +62,7 @@ def test_random_conv_layers(ff):
 
 def test_random_depthwise_layers(ff):
     rng = np.random.default_rng(404)
-    for _ in range(10):
+    for _ in range(25):
         H, W = (int(v) for v in rng.integers(3, 25, 2))
         C = int(rng.choice([4, 6, 16, 20, 64, 68, 130]))
         P.test_depthwise_forward_and_backward(ff, int(rng.integers(1, 6)), H, W, C, int(rng.choice([1, 2])))
@@ -72,7 +72,7 @@ def test_random_dense_stacks(ff):
     """Whole steps of random dense stacks, both readings of the look-ahead; theta near the goodness of the first
     layer so that both passes carry a live gradient."""
     rng = np.random.default_rng(505)
-    for case in range(6):
+    for case in range(16):
         depth = int(rng.integers(2, 5))
         widths = _dims(rng, depth + 1, 12, 300)     # the label overlay needs ten input features
         widths = [w + (-w) % 4 for w in widths]    # activity widths: multiples of 4 like every configured network
@@ -87,9 +87,28 @@ def test_random_dense_stacks(ff):
 
 def test_random_conv_stacks(ff):
     rng = np.random.default_rng(606)
-    for case in range(4):
+    for case in range(10):
         chans = [3] + [int(rng.choice([8, 16, 24, 32])) for _ in range(int(rng.integers(1, 4)))]
         h, w = int(rng.choice([4, 6, 8, 12])), int(rng.choice([10, 11, 16]))   # the label overlay needs ten columns
         wl = Workload(f"randc{case}", conv_stack(chans, h, w), int(rng.integers(2, 9)), "uniform_onehot",
                       lam=float(rng.choice([0.0, 0.25])))
+        P._run_steps(ff, wl, 2)
+
+
+def test_random_residual_and_bottleneck_stacks(ff):
+    """Basic residual blocks (identity and projection skips) and inverted bottlenecks (1x1, depthwise 3x3, 1x1) with
+    random widths, strides and map sizes."""
+    rng = np.random.default_rng(707)
+    for case in range(8):
+        h, w = int(rng.choice([4, 8, 12])), int(rng.choice([12, 16]))
+        stem = int(rng.choice([8, 16]))
+        if case % 2 == 0:
+            stages = [(stem, 1, 1)] + [(int(rng.choice([16, 24, 32])), int(rng.choice([1, 2])), int(rng.integers(1, 3)))
+                                       for _ in range(int(rng.integers(1, 3)))]
+            layers = res_stack(stem, stages, h, w)
+        else:
+            blocks = [(int(rng.integers(1, 5)), int(rng.choice([8, 16, 20, 24])), int(rng.choice([1, 2])))
+                      for _ in range(int(rng.integers(1, 3)))]
+            layers = bottleneck_stack(stem, blocks, h, w)
+        wl = Workload(f"randr{case}", layers, int(rng.integers(2, 7)), "uniform_onehot", lam=float(rng.choice([0.0, 0.05])))
         P._run_steps(ff, wl, 2)

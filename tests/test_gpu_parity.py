@@ -192,7 +192,7 @@ def test_backward_local_and_update(ff, B, K, N):
         gy_t, s_g, dw = empty8(N, B), scalar(), empty32(N, K)
         ff.ff_layer_backward_local(desc, dev(pad32(acc)), dev(gd["vmax"]), dev(np.array([s_a])), dev(np.array([s_w])),
                                    dev(ct), 1, 4, 100 + p, dev(pad8(np.ascontiguousarray(a_q.T))), gy_t, s_g, dw,
-                                   workspace())
+                                   workspace(max(ff.WS_MIN_BYTES, ff.ff_layer_workspace_bytes(desc))))
         torch.cuda.synchronize()
         assert s_g.item() == sg_ref
         check_q(gy_t, gq_ref.T, "gy_q_t")

@@ -46,6 +46,17 @@ def test_random_dense_layers(ff):
         P.test_chain_gradients_and_input_gradient(ff, B, K, N, int(rng.integers(0, 2)))
 
 
+def test_random_larger_dense_layers(ff):
+    """Several tiles of every tile shape with ragged edges, and reductions long enough for a split weight gradient."""
+    rng = np.random.default_rng(212)
+    for _ in range(6):
+        B, K, N = _dims(rng, 3, 200, 1500)
+        P.test_layer_forward(ff, B, K, N, 1)
+        P.test_backward_local_and_update(ff, B, K, N)
+    for (B, K, N) in ((5000, 40, 24), (3000, 272, 130)):     # few outputs, a long reduction: split weight gradient
+        P.test_backward_local_and_update(ff, B, K, N)
+
+
 def test_random_conv_layers(ff):
     rng = np.random.default_rng(303)
     for _ in range(40):

@@ -417,11 +417,46 @@ __global__ __launch_bounds__(256) void k_reduce_splits(const int32_t* __restrict
     }
 }
 
+// Many splits of a small output (convolutions with few channels): a thread of the kernel above would walk the splits
+// one dependent load after the other.  Here 16 lanes share the splits of each 16-byte group and meet in LDS.
+__global__ __launch_bounds__(256) void k_reduce_splits_wide(const int32_t* __restrict__ part, int splits, int64_t st_split,
+                                                            int64_t st_part_z, int32_t* __restrict__ out, int64_t st_out_z,
+                                                            int64_t n4)
+{
+    const int4* __restrict__ p = (const int4*)(part + blockIdx.y * st_part_z);
+    int4* __restrict__ o = (int4*)(out + blockIdx.y * st_out_z);
+    const int64_t s4 = st_split >> 2;
+    const int el = threadIdx.x & 15, sl = threadIdx.x >> 4;
+    const int64_t e = (int64_t)blockIdx.x * 16 + el;
+    int4 acc = make_int4(0, 0, 0, 0);
+    if (e < n4)
+        for (int sp = sl; sp < splits; sp += 16) {
+            const int4 v = p[e + sp * s4];
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+    __shared__ int4 red[16][16];
+    red[sl][el] = acc;
+    __syncthreads();
+    if (sl == 0 && e < n4) {
+#pragma unroll
+        for (int r = 1; r < 16; ++r) {
+            const int4 v = red[r][el];
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        o[e] = acc;
+    }
+}
+
 hipError_t launch_reduce_splits(const int32_t* part, int splits, int64_t st_split, int64_t st_part_z, int32_t* out,
                                 int64_t st_out_z, int64_t n, int nb, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
     const int64_t n4 = n >> 2;
+    if (splits >= 32 && n4 <= (int64_t(1) << 20)) {
+        hipLaunchKernelGGL(k_reduce_splits_wide, dim3((unsigned)((n4 + 15) / 16), (unsigned)nb), dim3(256), 0, s, part,
+                           splits, st_split, st_part_z, out, st_out_z, n4);
+        return hipGetLastError();
+    }
     int64_t blocks = (n4 + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(k_reduce_splits, dim3((unsigned)blocks, (unsigned)nb), dim3(256), 0, s, part, splits, st_split,

@@ -90,13 +90,15 @@ __global__ __launch_bounds__(256) void k_im2col(Im2colArgs p)
 // channel-major in LDS ([channel][row][padded column], zero borders), so that the global gathers become one
 // pass of 16-byte loads, and every colT row receives RH * W_out contiguous bytes per workgroup in 16-byte
 // stores (lanes run over the chunks of one colT row first).
-// FAST (stride 1, W_out % 16 == 0): the 16 reduction bytes of an output chunk -- 16 consecutive output pixels
+// FAST (MODE 1: stride 1, W_out % 16 == 0): the 16 reduction bytes of an output chunk -- 16 consecutive output pixels
 // of one row, one tap, one channel -- are 16 consecutive LDS bytes at the tap's column offset: five aligned
 // words and a byte alignment.  Otherwise (stride 2, or maps narrower than 16) each byte is gathered from LDS.
 // Requires H_out * W_out % 16 == 0 (chunks do not straddle samples) and RH * W_out % 16 == 0.
 constexpr int FT_CT = 32;
 
-template <bool FAST>
+// MODE 0: byte gathers; 1: FAST; 2 / 3: stride 1 on maps 8 / 4 pixels wide -- a chunk is two (four) output rows of
+// eight (four) consecutive LDS bytes each, fetched as aligned words and a byte alignment like FAST.
+template <int MODE>
 __global__ __launch_bounds__(256) void k_im2col_t_slab(Im2colArgs p, int RH)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t slab[];
@@ -139,7 +141,24 @@ __global__ __launch_bounds__(256) void k_im2col_t_slab(Im2colArgs p, int RH)
         const int ci = r % nct, tap = r / nct;
         const int kh = tap / g.ks, kw = tap - kh * g.ks;
         uint4 o;
-        if (FAST) {
+        if (MODE == 2 || MODE == 3) {
+            constexpr int PPC = MODE == 2 ? 2 : 4;     // output rows per chunk
+            uint32_t ow[4];
+#pragma unroll
+            for (int r = 0; r < PPC; ++r) {
+                const int off = (ci * NR + ch * PPC + r + kh) * WP + kw;
+                const uint32_t* wp = (const uint32_t*)(slab + (off & ~3));
+                const uint32_t sh = (uint32_t)(off & 3);
+                if (MODE == 2) {
+                    const uint32_t w0 = wp[0], w1 = wp[1], w2 = wp[2];
+                    ow[2 * r] = __builtin_amdgcn_alignbyte(w1, w0, sh);
+                    ow[2 * r + 1] = __builtin_amdgcn_alignbyte(w2, w1, sh);
+                } else {
+                    ow[r] = __builtin_amdgcn_alignbyte(wp[1], wp[0], sh);
+                }
+            }
+            o = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+        } else if (MODE == 1) {
             const int cpr = g.Wo >> 4;              // chunks per output row
             const int hl = ch / cpr, w16 = ch - hl * cpr;
             const int off = (ci * NR + hl + kh) * WP + w16 * 16 + kw;
@@ -201,8 +220,10 @@ hipError_t launch_im2col(const Im2colArgs& p, bool transposed, hipStream_t s)
         if (RH > 0) {
             const int HoE = p.wtaps_only ? g.H : g.Ho;
             const dim3 grid((unsigned)(HoE / RH), (unsigned)((g.Cin + FT_CT - 1) / FT_CT), (unsigned)(p.nb * (p.b1 - p.b0)));
-            if (g.stride == 1 && (g.Wo & 15) == 0) hipLaunchKernelGGL(k_im2col_t_slab<true>, grid, dim3(256), lds, s, p, RH);
-            else hipLaunchKernelGGL(k_im2col_t_slab<false>, grid, dim3(256), lds, s, p, RH);
+            if (g.stride == 1 && (g.Wo & 15) == 0) hipLaunchKernelGGL(k_im2col_t_slab<1>, grid, dim3(256), lds, s, p, RH);
+            else if (g.stride == 1 && g.Wo == 8) hipLaunchKernelGGL(k_im2col_t_slab<2>, grid, dim3(256), lds, s, p, RH);
+            else if (g.stride == 1 && g.Wo == 4) hipLaunchKernelGGL(k_im2col_t_slab<3>, grid, dim3(256), lds, s, p, RH);
+            else hipLaunchKernelGGL(k_im2col_t_slab<0>, grid, dim3(256), lds, s, p, RH);
             return hipGetLastError();
         }
         if (p.wtaps_only) return hipErrorInvalidValue;   // the generic kernel below writes full patches only

@@ -239,7 +239,10 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     // instruction writes 32-byte pieces of 32 different rows.  Interior tiles therefore go through LDS (free
     // after the main loop; each wave uses a private slice, no barrier needed): 16-byte writes row by row,
     // then reads that give every store instruction whole contiguous row segments of WTN*4 bytes.
-    const bool staged = FF_STAGED_EPI && i0 + BM <= a.I && j0 + BN <= a.J;
+    // Edge tiles take the same route when J is a multiple of 4 (a lane's 16 bytes then never straddle the last
+    // column): rows and column groups beyond the matrix are simply not stored.
+    const bool interior = i0 + BM <= a.I && j0 + BN <= a.J;
+    const bool staged = FF_STAGED_EPI && (interior || (a.J & 3) == 0);
     const bool fast_sq = a.relu && a.rshift == 0;
     int8_t* const ebase = lds + wave * ESLICE;
 #pragma unroll
@@ -299,6 +302,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
             for (int r = 0; r < 32 / RPI; ++r) {
                 const int row = r * RPI + rl;
                 const v4i v = *(const v4i*)(ebase + row * EROW + cc * 16);
+                if (!interior && (i0 + wm * WTM + ti * 32 + row >= a.I || j0 + wn * WTN + cc * 4 >= a.J)) continue;
                 // forward accumulators are not read again until other kernels have streamed more than the caches
                 // hold: a non-temporal store keeps them from displacing what is needed next.  Weight gradients are
                 // read by the update right away: ordinary stores.

@@ -85,9 +85,8 @@ def test_random_dense_stacks(ff):
     rng = np.random.default_rng(505)
     for case in range(16):
         depth = int(rng.integers(2, 5))
-        widths = _dims(rng, depth + 1, 12, 300)     # the label overlay needs ten input features
-        widths = [w + (-w) % 4 for w in widths]    # activity widths: multiples of 4 like every configured network
-        B = int(rng.integers(2, 90))
+        widths = [_dims(rng, 1, 12, 300)[0]] + _dims(rng, depth, 1, 300)   # the label overlay needs ten input features
+        B = int(rng.integers(1, 90))
         norm = bool(rng.integers(0, 2))
         wl = Workload(f"rand{case}", mlp(widths, norm), B, "uniform_onehot", lam=float(rng.choice([0.0, 0.1, 0.7])),
                       theta=float(rng.choice([2.0, 10.0, 40.0])))
@@ -99,7 +98,7 @@ def test_random_dense_stacks(ff):
 def test_random_conv_stacks(ff):
     rng = np.random.default_rng(606)
     for case in range(10):
-        chans = [3] + [int(rng.choice([8, 16, 24, 32])) for _ in range(int(rng.integers(1, 4)))]
+        chans = [3] + [int(rng.choice([5, 8, 16, 17, 24, 32])) for _ in range(int(rng.integers(1, 4)))]
         h, w = int(rng.choice([4, 6, 8, 12])), int(rng.choice([10, 11, 16]))   # the label overlay needs ten columns
         wl = Workload(f"randc{case}", conv_stack(chans, h, w), int(rng.integers(2, 9)), "uniform_onehot",
                       lam=float(rng.choice([0.0, 0.25])))

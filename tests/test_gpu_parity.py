@@ -172,7 +172,7 @@ def test_lookahead(ff):
 
 
 # ------------------------------------------------------------------------------------------- backward / update
-@pytest.mark.parametrize("B,K,N", [(24, 100, 72), (200, 130, 300), (1024, 260, 96)])
+@pytest.mark.parametrize("B,K,N", [(24, 100, 72), (200, 130, 300), (1024, 260, 96), (40, 300, 2003), (8, 5000, 1030)])
 def test_backward_local_and_update(ff, B, K, N):
     rng = np.random.default_rng(B)
     a_q = rng.integers(-127, 128, (B, K)).astype(np.int8)

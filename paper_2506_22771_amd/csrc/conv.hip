@@ -253,6 +253,19 @@ __device__ __forceinline__ unsigned long long dw_wave_sum_u64(unsigned long long
     return v;
 }
 
+// 4x4 byte transpose: word j of x holds bytes (channels) 0..3 of item j; word e of o holds byte e of items 0..3.
+__device__ __forceinline__ void dw_transpose4x4(const uint32_t x[4], uint32_t o[4])
+{
+    const uint32_t t0 = __builtin_amdgcn_perm(x[1], x[0], 0x05010400u);
+    const uint32_t t1 = __builtin_amdgcn_perm(x[1], x[0], 0x07030602u);
+    const uint32_t t2 = __builtin_amdgcn_perm(x[3], x[2], 0x05010400u);
+    const uint32_t t3 = __builtin_amdgcn_perm(x[3], x[2], 0x07030602u);
+    o[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
+    o[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+    o[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
+    o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
+}
+
 // blockIdx.x = share of the sample's output pixels, blockIdx.y = sample, blockIdx.z = pass * channel groups + group.
 // A thread keeps the 36 weights of its four channels in registers and walks over DW_PIX pixels, 256 / quads apart.
 __global__ __launch_bounds__(256) void k_dwconv_forward(DwArgs p, int cgroups)
@@ -406,7 +419,54 @@ __global__ __launch_bounds__(256) void k_dwconv_wgrad(DwArgs p)
     for (int e = 0; e < 4; ++e)
 #pragma unroll
         for (int t = 0; t < 9; ++t) part[e][t] = 0;
-    if (rl < lanes) {
+    if (rl < lanes && g.stride == 1 && (g.Wo & 3) == 0) {
+        // Stride 1, rows of whole 4-pixel groups: four consecutive output pixels at a time.  The gradient words and
+        // the six input columns they touch are transposed to (channel word x pixel bytes), a horizontal tap is then
+        // a byte alignment of two such words, and every (channel, tap) takes one packed dot product over the four
+        // pixels: 116 ALU operations per group against 288 for the pixel-by-pixel loop below.
+        const int64_t r0 = m0 + (int64_t)blockIdx.x * DW_ROWS;
+        const int64_t r1 = min(m1, r0 + DW_ROWS);
+        for (int64_t m = r0 + 4 * rl; m < r1; m += 4 * lanes) {
+            const int b = (int)(m / hw), pix = (int)(m - (int64_t)b * hw);
+            const int ho = pix / g.Wo, wo = pix - ho * g.Wo;
+            uint32_t gq[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) gq[j] = *(const uint32_t*)(gy + (m + j) * p.ldg + c0);
+            if ((gq[0] | gq[1] | gq[2] | gq[3]) == 0u) continue;   // a rectified gradient is zero wherever the activity is
+            uint32_t G[4];
+            dw_transpose4x4(gq, G);
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh) {
+                const int hi = ho + kh - g.pad;
+                if ((unsigned)hi >= (unsigned)g.H) continue;
+                const int8_t* arow = a + (((int64_t)b * g.H + hi) * g.W) * g.cpitch + c0;
+                uint32_t X[8];
+#pragma unroll
+                for (int j = 0; j < 6; ++j) {
+                    const int wi = wo - g.pad + j;
+                    X[j] = (unsigned)wi < (unsigned)g.W ? *(const uint32_t*)(arow + (int64_t)wi * g.cpitch) : 0u;
+                }
+                X[6] = 0u;
+                X[7] = 0u;
+                uint32_t TA[4], TB[4];
+                dw_transpose4x4(X, TA);
+                dw_transpose4x4(X + 4, TB);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    part[e][kh * 3 + 0] = __builtin_amdgcn_sdot4((int)G[e], (int)TA[e], part[e][kh * 3 + 0], false);
+                    part[e][kh * 3 + 1] = __builtin_amdgcn_sdot4((int)G[e], (int)__builtin_amdgcn_alignbyte(TB[e], TA[e], 1u),
+                                                                 part[e][kh * 3 + 1], false);
+                    part[e][kh * 3 + 2] = __builtin_amdgcn_sdot4((int)G[e], (int)__builtin_amdgcn_alignbyte(TB[e], TA[e], 2u),
+                                                                 part[e][kh * 3 + 2], false);
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+                if (part[e][t]) atomicAdd(&lacc[(4 * q + e) * 9 + t], part[e][t]);
+    } else if (rl < lanes) {
         const int64_t r0 = m0 + (int64_t)blockIdx.x * DW_ROWS;
         const int64_t r1 = min(m1, r0 + DW_ROWS);
         for (int64_t m = r0 + rl; m < r1; m += lanes) {

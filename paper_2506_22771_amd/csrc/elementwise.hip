@@ -181,19 +181,27 @@ __device__ __forceinline__ int quant_code(float v, float inv, uint32_t word_in)
     return min(max(code, -127), 127);
 }
 
-constexpr int QT_ROWS = 128;  // tile rows
-constexpr int QT_COLS = 64;   // tile cols
 constexpr int QT_THREADS = 256;
-constexpr int QT_LDW = QT_ROWS / 4 + 1;  // words per column in the transposed LDS tile (+1: bank spread)
+// Tile of one workgroup: CB column blocks of four columns, 2 x (256 / CB) row blocks of four rows: 128 x 64 elements
+// for CB = 16, 256 x 32 for CB = 8 (matrices of at most 32 columns: no idle column lanes, and with a row pitch of
+// 32 columns or fewer the tile is one contiguous span of memory).
+template <int CB> struct QTile {
+    static constexpr int COLS = 4 * CB;
+    static constexpr int RH = 4 * (QT_THREADS / CB);   // rows of one half tile (u = 0 / 1)
+    static constexpr int ROWS = 2 * RH;
+    static constexpr int LDW = ROWS / 4 + 1;           // words per column in the transposed LDS tile (+1: bank spread)
+    static constexpr int CHUNKS = ROWS / 16;           // 16-byte pieces of one transposed column
+};
 
 // Each thread owns two 4x4 element blocks (rows 4*rb+j, cols 4*cb+c).  Codes are packed four columns
 // to a word for q, byte-transposed in registers for q_t and regrouped through LDS so that q_t is
 // written in 16-byte pieces.  All eight 16-byte loads of a thread are issued before any arithmetic.
 // VEC: 16-byte loads are legal (always for the int32 sources; for fp32 when cols % 4 == 0 and the base
 // is 16-byte aligned).  BIG: the tensor has 2^32 elements or more (64-bit element index).
-template <int SRC, bool STOCH, bool VEC, bool BIG>
+template <int SRC, bool STOCH, bool VEC, bool BIG, int CB = 16>
 __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
 {
+    constexpr int QT_ROWS = QTile<CB>::ROWS, QT_COLS = QTile<CB>::COLS, QT_LDW = QTile<CB>::LDW, QT_RH = QTile<CB>::RH;
     const int z = blockIdx.z;
     const float* __restrict__ x = a.x ? a.x + z * a.st_x : nullptr;
     const int32_t* __restrict__ acc = a.acc ? a.acc + z * a.st_acc : nullptr;
@@ -217,15 +225,15 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
     const int64_t r0 = (int64_t)blockIdx.y * QT_ROWS;
     const int64_t c0 = (int64_t)blockIdx.x * QT_COLS;
     const int t = threadIdx.x;
-    const int cb = t & 15;
+    const int cb = t & (CB - 1);
     const int64_t col = c0 + 4 * cb;
     const bool col_in = col < a.cols;
 
     __shared__ uint32_t tileT[QT_COLS * QT_LDW];
 
-    // ---- loads: 2 blocks x 4 rows x 16 bytes, raw bits.  Row (u, j) of this thread is rowb + 64*u + j:
+    // ---- loads: 2 blocks x 4 rows x 16 bytes, raw bits.  Row (u, j) of this thread is rowb + QT_RH*u + j:
     // all per-row offsets are (compile-time constant) x (uniform pitch), i.e. scalar-unit work.
-    const int64_t rowb = r0 + 4 * (t >> 4);
+    const int64_t rowb = r0 + 4 * (t / CB);
     const float* __restrict__ px0 = F32SRC ? x + rowb * a.cols + col : nullptr;
     const int32_t* __restrict__ pa0 = !F32SRC ? acc + rowb * a.ldacc + col : nullptr;
     int8_t* __restrict__ pq0 = q ? q + rowb * a.ldq + col : nullptr;
@@ -236,7 +244,7 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
     for (int u = 0; u < 2; ++u) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int dr = 64 * u + j;
+            const int dr = QT_RH * u + j;
             const int64_t row = rowb + dr;
             const bool in = row < a.rows && col_in;
             uint32_t w0 = 0, w1 = 0, w2 = 0, w3 = 0;
@@ -279,11 +287,11 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
     const uint64_t idx0 = (uint64_t)rowb * (uint64_t)a.cols + (uint64_t)col;   // element index of (row rowb, col)
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-        const int rb = (t >> 4) + 16 * u;
+        const int rb = (t / CB) + (QT_THREADS / CB) * u;
         uint32_t rowpack[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int dr = 64 * u + j;
+            const int dr = QT_RH * u + j;
             const int64_t row = rowb + dr;
             uint32_t base_lo;
             uint32_t kk = key.k0;
@@ -335,7 +343,7 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int e = t + QT_THREADS * u;
-            const int cl = e >> 3, ch = e & 7;
+            const int cl = e / QTile<CB>::CHUNKS, ch = e % QTile<CB>::CHUNKS;
             const int64_t oc = c0 + cl;
             const int64_t orow = r0 + 16 * ch;
             if (oc < a.cols && orow < a.ldqt) {
@@ -354,13 +362,21 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
 }
 
 template <int SRC, bool STOCH>
-static void launch_quantize_t(const QuantArgs& a, dim3 grid, dim3 block, hipStream_t s)
+static void launch_quantize_t(const QuantArgs& a, hipStream_t s)
 {
+    const dim3 block(QT_THREADS);
     const bool big = (uint64_t)a.rows * (uint64_t)a.cols >= (uint64_t(1) << 32);
     bool vec = true;
     if (SRC == QSRC_F32 || SRC == QSRC_F32_GRAD) {
         vec = (a.cols & 3) == 0 && (((uintptr_t)a.x) & 15) == 0 && ((a.st_x & 3) == 0 || a.nb == 1);
     }
+    if (a.cols <= QTile<8>::COLS && vec && !big) {
+        const dim3 grid(1, (unsigned)((a.rows + QTile<8>::ROWS - 1) / QTile<8>::ROWS), (unsigned)a.nb);
+        hipLaunchKernelGGL((k_quantize<SRC, STOCH, true, false, 8>), grid, block, 0, s, a);
+        return;
+    }
+    const dim3 grid((unsigned)((a.cols + QTile<16>::COLS - 1) / QTile<16>::COLS),
+                    (unsigned)((a.rows + QTile<16>::ROWS - 1) / QTile<16>::ROWS), (unsigned)a.nb);
     if (big) {
         if (vec) hipLaunchKernelGGL((k_quantize<SRC, STOCH, true, true>), grid, block, 0, s, a);
         else hipLaunchKernelGGL((k_quantize<SRC, STOCH, SRC != QSRC_F32 && SRC != QSRC_F32_GRAD, true>), grid, block, 0, s, a);
@@ -372,27 +388,24 @@ static void launch_quantize_t(const QuantArgs& a, dim3 grid, dim3 block, hipStre
 
 hipError_t launch_quantize(int src, const QuantArgs& a, hipStream_t s)
 {
-    const dim3 block(QT_THREADS);
-    const dim3 grid((unsigned)((a.cols + QT_COLS - 1) / QT_COLS), (unsigned)((a.rows + QT_ROWS - 1) / QT_ROWS),
-                    (unsigned)a.nb);
     if (a.rows <= 0 || a.cols <= 0) return hipSuccess;
     const bool st = a.round_mode == FF_ROUND_STOCHASTIC;
     switch (src) {
         case QSRC_F32:
-            if (st) launch_quantize_t<QSRC_F32, true>(a, grid, block, s);
-            else launch_quantize_t<QSRC_F32, false>(a, grid, block, s);
+            if (st) launch_quantize_t<QSRC_F32, true>(a, s);
+            else launch_quantize_t<QSRC_F32, false>(a, s);
             break;
         case QSRC_HANDOFF:
-            if (st) launch_quantize_t<QSRC_HANDOFF, true>(a, grid, block, s);
-            else launch_quantize_t<QSRC_HANDOFF, false>(a, grid, block, s);
+            if (st) launch_quantize_t<QSRC_HANDOFF, true>(a, s);
+            else launch_quantize_t<QSRC_HANDOFF, false>(a, s);
             break;
         case QSRC_F32_GRAD:
-            if (st) launch_quantize_t<QSRC_F32_GRAD, true>(a, grid, block, s);
-            else launch_quantize_t<QSRC_F32_GRAD, false>(a, grid, block, s);
+            if (st) launch_quantize_t<QSRC_F32_GRAD, true>(a, s);
+            else launch_quantize_t<QSRC_F32_GRAD, false>(a, s);
             break;
         default:
-            if (st) launch_quantize_t<QSRC_GRAD, true>(a, grid, block, s);
-            else launch_quantize_t<QSRC_GRAD, false>(a, grid, block, s);
+            if (st) launch_quantize_t<QSRC_GRAD, true>(a, s);
+            else launch_quantize_t<QSRC_GRAD, false>(a, s);
             break;
     }
     return hipGetLastError();

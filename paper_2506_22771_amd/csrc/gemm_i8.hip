@@ -393,7 +393,9 @@ GemmPlan gemm_plan(int64_t I, int64_t J, int64_t R, int nb, bool allow_split)
         // would idle most of the chip), at least 16 reduction steps per split.
         p.bm = edge(I);
         int64_t sp = 512 / tiles(p.bm, p.bn);
-        if (sp > nk / 16) sp = nk / 16;
+        // ... (8 where one partial result is small, at most 256 KB: writing and adding up the partials then costs little)
+        const int64_t min_steps = I * J * 4 <= (256 << 10) ? 8 : 16;
+        if (sp > nk / min_steps) sp = nk / min_steps;
         if (sp < 1) sp = 1;
         const int64_t per = (nk + sp - 1) / sp;
         p.splits = (int)((nk + per - 1) / per);   // no split without reduction steps

@@ -127,6 +127,7 @@ struct WsLayout {
                            // g_amax[k][2], w_amax[k]
     size_t off_gsum;       // uint64 [k][2][B]
     size_t off_vmax;       // int32  [k][2][B]
+    size_t off_gl;         // scratch of the goodness / loss kernel (see GoodnessArgs::loss_part)
     size_t zero_bytes;     // the region [0, zero_bytes) is cleared at the start of a step
     size_t off_scales;     // fp32: s_a[k][2], s_g[k][2]
     size_t off_c, off_ct;  // fp32 [k][2][B]
@@ -218,6 +219,8 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
     off = align_up(off + sizeof(uint64_t) * k * 2 * B, A);
     w->off_vmax = off;
     off = align_up(off + sizeof(int32_t) * k * 2 * B, A);
+    w->off_gl = off;   // goodness / loss kernel with several workgroups: uint64 partial sums [2][GL_MAX_WG], uint32 counters [2]
+    off = align_up(off + sizeof(uint64_t) * 2 * GL_MAX_WG + sizeof(uint32_t) * 2, A);
     w->zero_bytes = off;
     w->off_scales = off;
     off = align_up(off + sizeof(float) * (k * 4 + 4), A);   // + s_h[2], the scale of the transposed weight copy
@@ -1107,6 +1110,8 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         ga.nb = 2;
         ga.st_b = B;
         ga.st_scalar = 1;
+        ga.loss_part = (unsigned long long*)(base + w.off_gl);
+        ga.wg_counter = (uint32_t*)(base + w.off_gl + sizeof(uint64_t) * 2 * GL_MAX_WG);
         HIPCHK_T(FF_K_SMALL, launch_goodness_loss(ga, s));
     }
 

@@ -451,7 +451,8 @@ __global__ __launch_bounds__(GL_THREADS) void k_goodness_loss(GoodnessArgs a)
 
     double lsum = 0.0;
     uint32_t amax_bits = 0;
-    for (int64_t b = threadIdx.x; b < a.B; b += GL_THREADS) {
+    const int wg = blockIdx.y, nwg = gridDim.y;
+    for (int64_t b = (int64_t)wg * GL_THREADS + threadIdx.x; b < a.B; b += (int64_t)nwg * GL_THREADS) {
         double g = (double)gsum[b];
         g = g * pow2r;
         g = g * s_yd;
@@ -496,14 +497,34 @@ __global__ __launch_bounds__(GL_THREADS) void k_goodness_loss(GoodnessArgs a)
         __syncthreads();
     }
     if (threadIdx.x == 0) {
-        a.loss_mean[z * a.st_scalar] = a.B > 0 ? (float)(red[0] / (double)a.B) : 0.0f;
-        if (a.next_amax_bits) a.next_amax_bits[z * a.st_scalar] = redm[0];
+        if (nwg == 1) {
+            a.loss_mean[z * a.st_scalar] = a.B > 0 ? (float)(red[0] / (double)a.B) : 0.0f;
+            if (a.next_amax_bits) a.next_amax_bits[z * a.st_scalar] = redm[0];
+        } else {
+            if (a.next_amax_bits && redm[0]) atomicMax(a.next_amax_bits + z * a.st_scalar, redm[0]);
+            unsigned long long* part = a.loss_part + z * GL_MAX_WG;
+            __hip_atomic_store(part + wg, (unsigned long long)__double_as_longlong(red[0]), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+            __threadfence();
+            if (atomicAdd(a.wg_counter + z, 1u) == (unsigned)(nwg - 1)) {
+                // last workgroup of this pass: every partial sum has been published; add them in index order
+                __threadfence();
+                double t = 0.0;
+                for (int i = 0; i < nwg; ++i)
+                    t += __longlong_as_double((long long)__hip_atomic_load(part + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                a.loss_mean[z * a.st_scalar] = (float)(t / (double)a.B);
+                __hip_atomic_store(a.wg_counter + z, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
     }
 }
 
 hipError_t launch_goodness_loss(const GoodnessArgs& a, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_goodness_loss, dim3((unsigned)a.nb), dim3(GL_THREADS), 0, s, a);
+    // one workgroup of 1024 threads per pass, or (large batches, scratch given) one per 1024 samples
+    int nwg = 1;
+    if (a.loss_part && a.wg_counter && a.B >= 2 * GL_THREADS) nwg = (int)min((int64_t)GL_MAX_WG, (a.B + GL_THREADS - 1) / GL_THREADS);
+    hipLaunchKernelGGL(k_goodness_loss, dim3((unsigned)a.nb, (unsigned)nwg), dim3(GL_THREADS), 0, s, a);
     return hipGetLastError();
 }
 

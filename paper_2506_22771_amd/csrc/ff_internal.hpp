@@ -107,7 +107,13 @@ struct GoodnessArgs {
     int32_t nb;
     int64_t st_b;  // stride between problems for the [B] arrays
     int32_t st_scalar;  // stride for s_a / loss_mean / next_amax (s_w is shared)
+    // Optional (large batches): several workgroups per pass.  loss_part: [nb][GL_MAX_WG] partial loss sums, wg_counter:
+    // [nb]; the counters and the next_amax slots must be zero on entry, and the kernel leaves the counters zero.  The
+    // workgroup that finishes last adds the partial sums in index order, so the mean does not depend on timing.
+    unsigned long long* loss_part;
+    uint32_t* wg_counter;
 };
+constexpr int GL_MAX_WG = 32;
 hipError_t launch_goodness_loss(const GoodnessArgs& a, hipStream_t s);
 
 // coeff / coeff_total: [k][np][B] with strides; also (optionally) the absmax of each layer's local gradient.

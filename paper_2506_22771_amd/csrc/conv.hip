@@ -92,12 +92,12 @@ __global__ __launch_bounds__(256) void k_im2col(Im2colArgs p)
 // stores (lanes run over the chunks of one colT row first).
 // FAST (MODE 1: stride 1, W_out % 16 == 0): the 16 reduction bytes of an output chunk -- 16 consecutive output pixels
 // of one row, one tap, one channel -- are 16 consecutive LDS bytes at the tap's column offset: five aligned
-// words and a byte alignment.  Otherwise (stride 2, or maps narrower than 16) each byte is gathered from LDS.
+// words and a byte alignment.  Maps 8 or 4 pixels wide at stride 1 do the same per output row (MODE 2 / 3); otherwise
+// (stride 2, other widths) each byte is gathered from LDS (MODE 0).
 // Requires H_out * W_out % 16 == 0 (chunks do not straddle samples) and RH * W_out % 16 == 0.
 constexpr int FT_CT = 32;
 
-// MODE 0: byte gathers; 1: FAST; 2 / 3: stride 1 on maps 8 / 4 pixels wide -- a chunk is two (four) output rows of
-// eight (four) consecutive LDS bytes each, fetched as aligned words and a byte alignment like FAST.
+// MODE 2 / 3: a chunk is two (four) output rows of eight (four) consecutive LDS bytes each.
 template <int MODE>
 __global__ __launch_bounds__(256) void k_im2col_t_slab(Im2colArgs p, int RH)
 {

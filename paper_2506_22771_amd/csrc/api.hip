@@ -130,6 +130,7 @@ struct WsLayout {
     size_t off_gl;         // scratch of the goodness / loss kernel (see GoodnessArgs::loss_part)
     size_t zero_bytes;     // the region [0, zero_bytes) is cleared at the start of a step
     size_t off_scales;     // fp32: s_a[k][2], s_g[k][2]
+    size_t off_wbmax;      // uint32 [UPDATE_MAX_BLOCKS]
     size_t off_c, off_ct;  // fp32 [k][2][B]
     size_t off_gy, st_gy;  // int8 scratch [2][st_gy]: transposed quantised local gradient
     size_t off_dw, st_dw, dw_bytes;  // int32 scratch [2][MAX_CHUNKS][dw_bytes]; st_dw = pass stride (bytes)
@@ -224,6 +225,8 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
     w->zero_bytes = off;
     w->off_scales = off;
     off = align_up(off + sizeof(float) * (k * 4 + 4), A);   // + s_h[2], the scale of the transposed weight copy
+    w->off_wbmax = off;   // per-workgroup maxima of a small weight update (UpdateArgs::block_max)
+    off = align_up(off + sizeof(uint32_t) * UPDATE_MAX_BLOCKS, A);
     w->off_c = off;
     off = align_up(off + sizeof(float) * k * 2 * B, A);
     w->off_ct = off;
@@ -1168,12 +1171,18 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         u.lr = lr;
         u.total_samples = (int32_t)(2 * B);
         u.w_amax_bits = w_amax + t;
+        // small tensors: one maximum per workgroup, reduced by the quantiser below, instead of atomics on one word
+        const int64_t nblk = update_blocks(d.N, d.K);
+        uint32_t* wbmax = (uint32_t*)(base + w.off_wbmax);
+        const bool per_block = nblk <= UPDATE_MAX_BLOCKS;
+        if (per_block) u.block_max = wbmax;
         HIPCHK_T(FF_K_UPDATE, launch_update(u, s));
 
         QuantArgs qa;
         memset(&qa, 0, sizeof(qa));
         qa.x = state->w_master[t];
-        qa.amax_bits = w_amax + t;
+        qa.amax_bits = per_block ? wbmax : w_amax + t;
+        qa.amax_n = per_block ? (int32_t)nblk : 0;
         qa.round_mode = FF_ROUND_NEAREST_EVEN;
         qa.rows = d.N;
         qa.cols = d.K;

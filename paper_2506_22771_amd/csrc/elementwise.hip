@@ -212,7 +212,17 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
     if (a.step_dev) key = make_sr_key(a.seed, stream_tag_of(a.step_dev[0], a.tag_layer, (uint32_t)z, a.tag_kind));
 
     // a vanishing range (absmax < 2^-100, all-zero tensor included) quantises to zero codes with scale 1
-    const float amax = __uint_as_float(a.amax_bits[z * a.st_amax]);
+    uint32_t amax_word = a.amax_bits[z * a.st_amax];
+    if (a.amax_n > 1) {   // (uniform) the producer left one candidate per workgroup
+        __shared__ uint32_t amx[QT_THREADS / 64];
+        uint32_t mm = 0;
+        for (int i = threadIdx.x; i < a.amax_n; i += QT_THREADS) mm = max(mm, a.amax_bits[z * a.st_amax + i]);
+        mm = wave_max_u32(mm);
+        if ((threadIdx.x & 63) == 0) amx[threadIdx.x >> 6] = mm;
+        __syncthreads();
+        amax_word = max(max(amx[0], amx[1]), max(amx[2], amx[3]));
+    }
+    const float amax = __uint_as_float(amax_word);
     const bool live = amax >= 0x1p-100f;
     const float inv = live ? 127.0f / amax : 0.0f;
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
@@ -887,16 +897,37 @@ __global__ __launch_bounds__(256) void k_update(UpdateArgs a)
         }
     }
     }
-    block_atomic_max_bits<256>(m, a.w_amax_bits);
+    if (a.block_max) {
+        m = wave_max_u32(m);
+        __shared__ uint32_t bm[4];
+        if ((threadIdx.x & 63) == 0) bm[threadIdx.x >> 6] = m;
+        __syncthreads();
+        if (threadIdx.x == 0) a.block_max[blockIdx.y * gridDim.x + blockIdx.x] = max(max(bm[0], bm[1]), max(bm[2], bm[3]));
+    } else {
+        block_atomic_max_bits<256>(m, a.w_amax_bits);
+    }
+}
+
+static dim3 update_grid(int64_t N, int64_t K)
+{
+    // Mid-sized tensors (thousands of short rows): a workgroup takes four rows in turn, so that fewer workgroups meet
+    // at the absmax word (cfg2: 21 -> 17 us per launch).  Few rows: one each, the chain of dependent loads stays short.
+    const int64_t rows_y = N >= 1024 && N * K <= (int64_t(8) << 20) ? (N + 3) / 4 : N;
+    return dim3((unsigned)((K + UP_SEG - 1) / UP_SEG), (unsigned)rows_y);
+}
+
+int64_t update_blocks(int64_t N, int64_t K)
+{
+    if (N <= 0 || K <= 0) return 0;
+    const dim3 g = update_grid(N, K);
+    return (int64_t)g.x * g.y;
 }
 
 hipError_t launch_update(const UpdateArgs& a, hipStream_t s)
 {
     if (a.N <= 0 || a.K <= 0) return hipSuccess;
-    // Mid-sized tensors (thousands of short rows): a workgroup takes four rows in turn, so that fewer workgroups meet
-    // at the absmax word (cfg2: 21 -> 17 us per launch).  Few rows: one each, the chain of dependent loads stays short.
-    const int64_t rows_y = a.N >= 1024 && a.N * a.K <= (int64_t(8) << 20) ? (a.N + 3) / 4 : a.N;
-    const dim3 grid((unsigned)((a.K + UP_SEG - 1) / UP_SEG), (unsigned)rows_y);
+    const dim3 grid = update_grid(a.N, a.K);
+    if (a.block_max && (int64_t)grid.x * grid.y > UPDATE_MAX_BLOCKS) return hipErrorInvalidValue;
     const bool vec = (a.K & 3) == 0 && ((((uintptr_t)a.w) & 15) == 0);
     if (vec) hipLaunchKernelGGL(k_update<true>, grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL(k_update<false>, grid, dim3(256), 0, s, a);

@@ -58,6 +58,7 @@ struct QuantArgs {
     int32_t relu, l2norm;
     // quantiser
     const uint32_t* amax_bits;  // device: bit pattern of the non-negative fp32 absmax
+    int32_t amax_n;             // > 1: amax_bits is an array of that many candidates, the absmax is their maximum
     int32_t round_mode;
     SrKey key;
     // destination
@@ -221,7 +222,14 @@ struct UpdateArgs {
     float lr;
     int32_t total_samples;
     uint32_t* w_amax_bits;  // zeroed slot
+    // Optional, for tensors of at most UPDATE_MAX_BLOCKS workgroups (update_blocks() below): every workgroup stores its
+    // maximum here instead of meeting the others at w_amax_bits (hundreds of simultaneous atomics on one word cost
+    // more than the rest of a small update); the quantiser that follows takes the maximum of the array
+    // (QuantArgs::amax_n).
+    uint32_t* block_max;
 };
+constexpr int UPDATE_MAX_BLOCKS = 1024;
+int64_t update_blocks(int64_t N, int64_t K);   // workgroups launch_update starts for an [N, K] tensor
 hipError_t launch_update(const UpdateArgs& a, hipStream_t s);
 
 // ---- int8 contraction (gemm_i8.hip):  C[i][j] = sum_r P[i][r] * Q[j][r] -----------------------

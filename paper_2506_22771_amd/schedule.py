@@ -61,15 +61,36 @@ class History:
 
 
 def _run(net: ff.Net, batches, n_iter_epochs: int, theta: float, lr: float, seed: int, step: int,
-         lam0: float, dlam: float, hist: History, log_every: int) -> int:
+         lam0: float, dlam: float, hist: History, log_every: int, use_graph: bool = False) -> int:
     k, B = net.k, net.batch
     ws = torch.empty(net.workspace_bytes(), dtype=torch.uint8, device="cuda")
     loss = torch.empty((k, 2), device="cuda")
     good = torch.empty((k, 2, B), device="cuda")
     lam = lam0
+    if use_graph and batches:
+        # One captured step per epoch (lambda is a launch argument), replayed for every batch of the epoch: the batch is
+        # copied into fixed input buffers and the step number lives in device memory (ff_train_step_at), so that
+        # launch latency, which dominates small networks, is paid once per epoch.
+        x_pos_s = torch.empty_like(batches[0][0])
+        x_neg_s = torch.empty_like(batches[0][1])
+        step_dev = torch.tensor([step], dtype=torch.int64, device="cuda")
     for _ in range(n_iter_epochs):
+        graph = None
+        if use_graph and batches:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    ff.ff_train_step_at(net, x_pos_s, x_neg_s, theta, lam, lr, seed, step_dev, 1, loss, good, ws)
+            torch.cuda.current_stream().wait_stream(side)
         for (x_pos, x_neg) in batches:
-            ff.ff_train_step(net, x_pos, x_neg, theta, lam, lr, seed, step, loss, good, ws)
+            if graph is not None:
+                x_pos_s.copy_(x_pos)
+                x_neg_s.copy_(x_neg)
+                graph.replay()
+            else:
+                ff.ff_train_step(net, x_pos, x_neg, theta, lam, lr, seed, step, loss, good, ws)
             if log_every and step % log_every == 0:
                 hist.step.append(step)
                 hist.lam.append(lam)
@@ -82,11 +103,12 @@ def _run(net: ff.Net, batches, n_iter_epochs: int, theta: float, lr: float, seed
 
 def train_lookahead(state: TrainState, batches: Sequence[Tuple[torch.Tensor, torch.Tensor]], epochs: int,
                     theta: float, lr: float, seed: int, lam0: float = 0.0, dlam: float = 0.001, step0: int = 0,
-                    log_every: int = 1, lookahead: str = "coeff") -> History:
+                    log_every: int = 1, lookahead: str = "coeff", use_graph: bool = False) -> History:
     """Algorithm 1 for `epochs` passes over `batches`; lambda = lam0 + epoch * dlam (Section V-A).
-    lookahead = "chain": Eq. (4) as an exact derivative through the later layers (dense stacks only)."""
+    lookahead = "chain": Eq. (4) as an exact derivative through the later layers (dense stacks only).
+    use_graph: replay one captured HIP graph per epoch instead of launching every step eagerly (same results)."""
     hist = History()
-    _run(state.net(lookahead=lookahead), batches, epochs, theta, lr, seed, step0, lam0, dlam, hist, log_every)
+    _run(state.net(lookahead=lookahead), batches, epochs, theta, lr, seed, step0, lam0, dlam, hist, log_every, use_graph)
     return hist
 
 

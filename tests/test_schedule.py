@@ -186,3 +186,20 @@ def test_lookahead_schedule_with_lambda_ramp_matches_oracle(ff):
         np.testing.assert_array_equal(st.w_master[i].cpu().numpy().reshape(-1), Wref[i].reshape(-1))
     np.testing.assert_allclose(np.array(hist.loss[-1]), last["loss"], rtol=1e-5)
     assert hist.lam == pytest.approx([0.0, 0.05, 0.10, 0.15])
+
+
+@pytest.mark.gpu
+def test_lookahead_schedule_as_replayed_graphs_equals_eager(ff):
+    """Two batches, three epochs with a lambda ramp: one captured graph per epoch, replayed per batch, gives the same
+    weights bit for bit and the same logged losses as eagerly launched steps."""
+    wl = workload("tiny_l2")
+    schedule, st_a, W, xp, xn, batch = _state(ff, wl)
+    _, st_b, _, _, _, _ = _state(ff, wl)
+    batch2 = (batch[1].clone(), batch[0].clone())
+    ha = schedule.train_lookahead(st_a, [batch, batch2], 3, wl.theta, wl.lr, wl.sr_seed, lam0=0.0, dlam=0.1)
+    hb = schedule.train_lookahead(st_b, [batch, batch2], 3, wl.theta, wl.lr, wl.sr_seed, lam0=0.0, dlam=0.1, use_graph=True)
+    torch.cuda.synchronize()
+    for i in range(len(wl.layers)):
+        assert torch.equal(st_a.w_master[i], st_b.w_master[i]) and torch.equal(st_a.w_q[i], st_b.w_q[i])
+    assert ha.step == hb.step == list(range(6))
+    np.testing.assert_allclose(np.array(ha.loss), np.array(hb.loss), rtol=1e-5)

@@ -839,63 +839,63 @@ __global__ __launch_bounds__(256) void k_update(UpdateArgs a)
     const int64_t kbase = (int64_t)blockIdx.x * UP_SEG + 4 * threadIdx.x;
     uint32_t m = 0;
     for (int64_t n = blockIdx.y; n < a.N; n += gridDim.y) {
-    float* __restrict__ wrow = a.w + n * a.K;
-    float w[4][4];
-    int4 d[4][4];
-    int cnt[4];
+        float* __restrict__ wrow = a.w + n * a.K;
+        float w[4][4];
+        int4 d[4][4];
+        int cnt[4];
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const int64_t k = kbase + g * 1024;
-        cnt[g] = (int)max((int64_t)0, min((int64_t)4, a.K - k));
-        if (VEC) {
-            float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (cnt[g]) f = *(const float4*)(wrow + k);
-            w[g][0] = f.x; w[g][1] = f.y; w[g][2] = f.z; w[g][3] = f.w;
-        } else {
+        for (int g = 0; g < 4; ++g) {
+            const int64_t k = kbase + g * 1024;
+            cnt[g] = (int)max((int64_t)0, min((int64_t)4, a.K - k));
+            if (VEC) {
+                float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (cnt[g]) f = *(const float4*)(wrow + k);
+                w[g][0] = f.x; w[g][1] = f.y; w[g][2] = f.z; w[g][3] = f.w;
+            } else {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) w[g][c] = c < cnt[g] ? wrow[k + c] : 0.0f;
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            d[g][j] = make_int4(0, 0, 0, 0);
-            if (j < a.n_terms && cnt[g]) {   // last use of the accumulators: streaming hint
-                const uint4 v = ld_stream16(a.dw[j] + n * a.lddw + k);
-                d[g][j] = make_int4((int)v.x, (int)v.y, (int)v.z, (int)v.w);
+                for (int c = 0; c < 4; ++c) w[g][c] = c < cnt[g] ? wrow[k + c] : 0.0f;
             }
-        }
-    }
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const int64_t k = kbase + g * 1024;
-        float gr[4];
-        gr[0] = (float)d[g][0].x * sc[0]; gr[1] = (float)d[g][0].y * sc[0];
-        gr[2] = (float)d[g][0].z * sc[0]; gr[3] = (float)d[g][0].w * sc[0];
-#pragma unroll
-        for (int j = 1; j < 4; ++j) {
-            if (j < a.n_terms) {
-                gr[0] = __builtin_fmaf((float)d[g][j].x, sc[j], gr[0]);
-                gr[1] = __builtin_fmaf((float)d[g][j].y, sc[j], gr[1]);
-                gr[2] = __builtin_fmaf((float)d[g][j].z, sc[j], gr[2]);
-                gr[3] = __builtin_fmaf((float)d[g][j].w, sc[j], gr[3]);
-            }
-        }
-#pragma unroll
-        for (int c = 0; c < 4; ++c) w[g][c] = __builtin_fmaf(-lr_eff, gr[c], w[g][c]);
-        if (VEC) {
-            if (cnt[g]) {
-                *(float4*)(wrow + k) = make_float4(w[g][0], w[g][1], w[g][2], w[g][3]);
-#pragma unroll
-                for (int c = 0; c < 4; ++c) m = max(m, __float_as_uint(w[g][c]) & 0x7FFFFFFFu);
-            }
-        } else {
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (c < cnt[g]) {
-                    wrow[k + c] = w[g][c];
-                    m = max(m, __float_as_uint(w[g][c]) & 0x7FFFFFFFu);
+            for (int j = 0; j < 4; ++j) {
+                d[g][j] = make_int4(0, 0, 0, 0);
+                if (j < a.n_terms && cnt[g]) {   // last use of the accumulators: streaming hint
+                    const uint4 v = ld_stream16(a.dw[j] + n * a.lddw + k);
+                    d[g][j] = make_int4((int)v.x, (int)v.y, (int)v.z, (int)v.w);
                 }
+            }
         }
-    }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int64_t k = kbase + g * 1024;
+            float gr[4];
+            gr[0] = (float)d[g][0].x * sc[0]; gr[1] = (float)d[g][0].y * sc[0];
+            gr[2] = (float)d[g][0].z * sc[0]; gr[3] = (float)d[g][0].w * sc[0];
+#pragma unroll
+            for (int j = 1; j < 4; ++j) {
+                if (j < a.n_terms) {
+                    gr[0] = __builtin_fmaf((float)d[g][j].x, sc[j], gr[0]);
+                    gr[1] = __builtin_fmaf((float)d[g][j].y, sc[j], gr[1]);
+                    gr[2] = __builtin_fmaf((float)d[g][j].z, sc[j], gr[2]);
+                    gr[3] = __builtin_fmaf((float)d[g][j].w, sc[j], gr[3]);
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) w[g][c] = __builtin_fmaf(-lr_eff, gr[c], w[g][c]);
+            if (VEC) {
+                if (cnt[g]) {
+                    *(float4*)(wrow + k) = make_float4(w[g][0], w[g][1], w[g][2], w[g][3]);
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) m = max(m, __float_as_uint(w[g][c]) & 0x7FFFFFFFu);
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (c < cnt[g]) {
+                        wrow[k + c] = w[g][c];
+                        m = max(m, __float_as_uint(w[g][c]) & 0x7FFFFFFFu);
+                    }
+            }
+        }
     }
     if (a.block_max) {
         m = wave_max_u32(m);

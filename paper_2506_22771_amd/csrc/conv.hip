@@ -291,6 +291,79 @@ __global__ __launch_bounds__(256) void k_dwconv_forward(DwArgs p, int cgroups)
             if (c0 + e < C) wr = *(const uint4*)(p.w_q + (int64_t)(c0 + e) * 16);
             w[e][0] = wr.x; w[e][1] = wr.y; w[e][2] = wr.z;
         }
+        if (g.stride == 1 && (g.Wo & 3) == 0) {
+            // Stride 1, rows of whole 4-pixel groups: four consecutive output pixels at a time.  The six input columns
+            // they touch are loaded once per kernel row and transposed to (channel word x pixel bytes); the word of
+            // output j is a byte alignment of two such words, and a kernel row is one packed dot product with the
+            // three taps of that row (fourth byte zero): half the loads and address arithmetic of the loop below.
+            uint32_t wk[4][3];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                wk[e][0] = w[e][0] & 0x00FFFFFFu;
+                wk[e][1] = __builtin_amdgcn_alignbyte(w[e][1], w[e][0], 3u) & 0x00FFFFFFu;
+                wk[e][2] = __builtin_amdgcn_alignbyte(w[e][2], w[e][1], 2u) & 0x00FFFFFFu;
+            }
+            const int ngrp = hw >> 2;
+            const int grp0 = (int)blockIdx.x * lanes * (DW_PIX / 4) + pl;
+            for (int it = 0; it < DW_PIX / 4; ++it) {
+                const int grp = grp0 + it * lanes;
+                if (grp >= ngrp) break;
+                const int pix = 4 * grp;
+                const int ho = pix / g.Wo, wo = pix - ho * g.Wo;
+                int acc[4][4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[j][e] = 0;
+#pragma unroll
+                for (int kh = 0; kh < 3; ++kh) {
+                    const int hi = ho + kh - g.pad;
+                    if ((unsigned)hi >= (unsigned)g.H) continue;
+                    const int8_t* arow = a + (((int64_t)b * g.H + hi) * g.W) * g.cpitch + c0;
+                    uint32_t X[8];
+#pragma unroll
+                    for (int j = 0; j < 6; ++j) {
+                        const int wi = wo - g.pad + j;
+                        X[j] = (unsigned)wi < (unsigned)g.W ? *(const uint32_t*)(arow + (int64_t)wi * g.cpitch) : 0u;
+                    }
+                    X[6] = 0u;
+                    X[7] = 0u;
+                    uint32_t TA[4], TB[4];
+                    dw_transpose4x4(X, TA);
+                    dw_transpose4x4(X + 4, TB);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        acc[0][e] = __builtin_amdgcn_sdot4((int)TA[e], (int)wk[e][kh], acc[0][e], false);
+                        acc[1][e] = __builtin_amdgcn_sdot4((int)__builtin_amdgcn_alignbyte(TB[e], TA[e], 1u), (int)wk[e][kh], acc[1][e], false);
+                        acc[2][e] = __builtin_amdgcn_sdot4((int)__builtin_amdgcn_alignbyte(TB[e], TA[e], 2u), (int)wk[e][kh], acc[2][e], false);
+                        acc[3][e] = __builtin_amdgcn_sdot4((int)__builtin_amdgcn_alignbyte(TB[e], TA[e], 3u), (int)wk[e][kh], acc[3][e], false);
+                    }
+                }
+                typedef int i32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    __builtin_nontemporal_store((i32x4){acc[j][0], acc[j][1], acc[j][2], acc[j][3]},
+                                                (i32x4*)(p.acc + z * p.st_acc + ((int64_t)b * hw + pix + j) * p.ldacc + c0));
+                    if (p.gsum && p.relu && p.rshift == 0) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const unsigned y = (unsigned)max(acc[j][e], 0);
+                            sq += (unsigned long long)y * y;
+                            vm = max(vm, (int)y);
+                        }
+                    } else if (p.gsum) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            int y = acc[j][e];
+                            if (p.relu) y = max(y, 0);
+                            const long long yl = (long long)y;
+                            sq += ((unsigned long long)(yl * yl)) >> p.rshift;
+                            vm = max(vm, y < 0 ? -y : y);
+                        }
+                    }
+                }
+            }
+        } else {
         const int pix0 = (int)blockIdx.x * lanes * DW_PIX + pl;
 #pragma unroll 2
         for (int it = 0; it < DW_PIX; ++it) {
@@ -358,6 +431,7 @@ __global__ __launch_bounds__(256) void k_dwconv_forward(DwArgs p, int cgroups)
                     }
                 }
             }
+        }
         }
     }
     if (p.gsum) {

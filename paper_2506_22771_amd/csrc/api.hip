@@ -451,12 +451,17 @@ static ff_status run_wgrad(const Dims& d, const int8_t* gy_t, int64_t st_gy, con
                            int8_t* colT, int64_t st_colT, int32_t* part, int64_t st_part, int32_t* dw, int64_t st_dw,
                            int64_t dw_elems, int nb, hipStream_t s, bool aqt_transposed = false)
 {
+    // depthwise accumulators are added to with atomics and must start at zero: one fill over all passes and chunks when
+    // that span is small (it usually is: C x 12 words per accumulator), else one per accumulator
+    const int64_t dw_span = (int64_t)(nb - 1) * st_dw + (int64_t)(d.n_chunks - 1) * dw_elems + d.N * pitch32(d.K);
+    const bool dw_one_fill = d.kind == FF_DWCONV2D && dw_span <= (int64_t(1) << 20);
+    if (dw_one_fill) HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)dw, dw_span, 0u, s));
     for (int c = 0; c < d.n_chunks; ++c) {
         const int64_t b0 = c * d.chunk_b, b1 = min(d.B, b0 + d.chunk_b);
         const int64_t m0 = b0 * d.rps, mc = (b1 - b0) * d.rps;
         if (d.kind == FF_DWCONV2D) {
             // gy_t holds the ROW-MAJOR int8 gradient [M, pitch(C)] for this layer kind
-            for (int z = 0; z < nb; ++z)
+            for (int z = 0; z < nb && !dw_one_fill; ++z)
                 HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(dw + z * st_dw + c * dw_elems), d.N * pitch32(d.K), 0u, s));
             DwArgs p;
             memset(&p, 0, sizeof(p));

@@ -220,6 +220,7 @@ ff_status ff_goodness_loss(const ff_layer_desc* layer, const uint64_t* gsum_int,
  * (the value ff_goodness_loss wrote to next_amax).
  *   q   [M, ff_pitch(N)] (may be NULL), q_t [N, ff_pitch(M)] (may be NULL), scale: one fp32.
  * For a conv layer the rows are output pixels (NHWC), M = batch * H_out * W_out.
+ * batch == 0 is accepted: nothing is read, scale = 1.
  * ------------------------------------------------------------------------------------------- */
 ff_status ff_layer_handoff(const ff_layer_desc* layer, const int32_t* acc, const float* s_a,
                            const float* s_w, const float* goodness, const float* amax,
@@ -246,7 +247,7 @@ ff_status ff_lookahead(const float* coeff, int32_t n_layers, int64_t batch, floa
  * Convolutions: a_q_t is the NHWC int8 layer input itself.  Depthwise layers (FF_DWCONV2D): gy_q_t receives the
  * gradient ROW-MAJOR, int8 [M, ff_pitch(C)], and dw_acc is int32 [C, ff_pitch32(9)] with
  * dw_acc[c][kh*3+kw] = sum over output pixels of gy_q[m][c] * a_q[pixel(m) + tap][c].
- * ws: >= ff_layer_workspace_bytes(layer).
+ * ws: >= ff_layer_workspace_bytes(layer).  batch == 0 is accepted: s_g = 1 and dw_acc is all zero.
  * ------------------------------------------------------------------------------------------- */
 ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc, const int32_t* vmax,
                                   const float* s_a, const float* s_w, const float* coeff_total,

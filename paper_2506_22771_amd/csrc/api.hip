@@ -704,6 +704,10 @@ ff_status ff_layer_handoff(const ff_layer_desc* layer, const int32_t* acc, const
     if (round_mode != FF_ROUND_NEAREST_EVEN && round_mode != FF_ROUND_STOCHASTIC) return FF_ERR_INVALID_ARG;
     if (!aligned16(acc) || (q && !aligned16(q)) || (q_t && !aligned16(q_t))) return FF_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
+    if (d.M == 0) {   // empty batch: no codes; the scale of an empty tensor is 1, as in ff_quantize
+        HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)scale, 1, 0x3F800000u, s));
+        return FF_OK;
+    }
     QuantArgs a;
     memset(&a, 0, sizeof(a));
     a.acc = acc;
@@ -765,7 +769,11 @@ ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc
     if (!aligned16(acc) || !aligned16(a_q_t) || !aligned16(gy_q_t) || !aligned16(dw_acc) || !aligned16(ws))
         return FF_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
-    if (d.B == 0) return FF_OK;
+    if (d.B == 0) {   // empty batch: scale 1 (as for any empty tensor) and an all-zero weight gradient
+        HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)s_g, 1, 0x3F800000u, s));
+        HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)dw_acc, d.N * pitch32(d.K), 0u, s));
+        return FF_OK;
+    }
     uint32_t* slot = (uint32_t*)ws;
     HIPCHK_T(FF_K_SMALL, launch_grad_amax(coeff_total, vmax, s_a, s_w, d.B, slot, s));
     QuantArgs a;

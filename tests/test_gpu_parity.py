@@ -509,3 +509,33 @@ def test_train_step_chain_cfg5_full_size(ff):
     """The variant at the large-GEMM configuration (8192+8192 samples, 4096->4096->4096): the input-gradient
     contraction runs at the forward contraction's shape."""
     _run_steps(ff, workload("cfg5"), 1, lookahead="chain")
+
+
+def test_empty_batch_through_the_single_operations(ff):
+    """batch = 0: every single-operation entry point succeeds, launches nothing that reads the (absent) data, and
+    leaves defined results: loss 0, absmax 0, scales 1, an all-zero weight gradient, weights unchanged by the update."""
+    K, N = 20, 12
+    d0 = ff.layer_desc(_dense(0, K, N), 0)
+    i8 = torch.zeros((1, 32), dtype=torch.int8, device="cuda")
+    i32 = torch.zeros((1, 16), dtype=torch.int32, device="cuda")
+    f32 = torch.ones(4, device="cuda")
+    i64 = torch.zeros(2, dtype=torch.int64, device="cuda")
+    rng = np.random.default_rng(1)
+    w = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    w_q, s_w = O.quantize(w, 0)
+    ff.ff_layer_forward(d0, i8, dev(pad8(w_q)), i32, i64, i32, workspace())
+    loss, amax = scalar(), scalar()
+    ff.ff_goodness_loss(d0, i64, i32, f32, f32, 1, 2.0, f32, f32, loss, amax)
+    sc, sg = scalar(), scalar()
+    ff.ff_layer_handoff(d0, i32, f32, f32, f32, f32, 1, 1, 2, i8, None, sc)
+    ff.ff_lookahead(f32, 2, 0, 0.1, f32)
+    dw = empty32(N, K)
+    ff.ff_layer_backward_local(d0, i32, i32, f32, f32, f32, 1, 1, 2, i8, i8, sg, dw, workspace())
+    d_w, d_wq, d_sw = dev(w), empty8(N, K), scalar()
+    ff.ff_layer_update(d0, d_w, dw, sg, f32, dw, sg, f32, 0.05, 2, d_wq, d_sw, workspace())
+    torch.cuda.synchronize()
+    assert loss.item() == 0.0 and amax.item() == 0.0 and sc.item() == 1.0 and sg.item() == 1.0
+    assert not dw.cpu().numpy()[:, :K].any()
+    np.testing.assert_array_equal(d_w.cpu().numpy(), w)
+    check_q(d_wq, w_q, "w_q after an empty update")
+    assert d_sw.item() == s_w

@@ -104,7 +104,7 @@ enum { FF_SKIP_NONE = 0, FF_SKIP_IDENTITY = 1, FF_SKIP_PROJECTION = 2 };
  * A convolution after a dense layer is FF_ERR_UNSUPPORTED. */
 typedef struct {
     int32_t n_layers;
-    int32_t batch;               /* samples per pass; must equal every layer's batch */
+    int32_t batch;               /* samples per pass (>= 1); must equal every layer's batch */
     const ff_layer_desc* layers; /* [host] n_layers entries */
     const int32_t* train_layer;  /* [host] n_layers flags, or NULL = every layer is trained.  A layer whose flag
                                     is 0 takes part in the forward pass and in the look-ahead sums of the layers

@@ -347,12 +347,12 @@ def test_conv_weight_gradient_chunks(ff):
 
 
 # ------------------------------------------------------------------------------------------- whole step
-def _run_steps(ff, wl, n_steps, lam=None, lookahead="coeff", theta=None):
+def _run_steps(ff, wl, n_steps, lam=None, lookahead="coeff", theta=None, inputs=None):
     lam = wl.lam if lam is None else lam
     theta = wl.theta if theta is None else theta
     oracle_step = O.train_step if lookahead == "coeff" else O.train_step_chain
     W = make_weights(wl)
-    xp, xn = make_inputs(wl)
+    xp, xn = make_inputs(wl) if inputs is None else inputs
     k, B = len(wl.layers), wl.batch
     d_w = [dev(w.reshape(w.shape[0], -1)) for w in W]      # conv weights [C_out, k*k*C_in]
     d_wq = [empty8(l.N, l.K) for l in wl.layers]
@@ -539,3 +539,20 @@ def test_empty_batch_through_the_single_operations(ff):
     np.testing.assert_array_equal(d_w.cpu().numpy(), w)
     check_q(d_wq, w_q, "w_q after an empty update")
     assert d_sw.item() == s_w
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_l2", "tiny_conv16", "tiny_res", "tiny_dw"])
+def test_train_step_degenerate_inputs(ff, name):
+    """An all-zero positive set (every tensor of that pass has a vanishing range: zero codes, scale 1, goodness 0, no
+    weight gradient from it) next to an ordinary negative set, then both sets zero (the weights must not move), then
+    inputs of magnitude 1e-30 and 1e+12 in one batch (the range is set by the large ones; the goodness stays within fp32)."""
+    wl = workload(name)
+    xp, xn = make_inputs(wl)
+    _run_steps(ff, wl, 2, inputs=(np.zeros_like(xp), xn))
+    w_after = _run_steps(ff, wl, 1, inputs=(np.zeros_like(xp), np.zeros_like(xn)))
+    for w0, w1 in zip(make_weights(wl), w_after):
+        np.testing.assert_array_equal(w0.reshape(w1.shape), w1)
+    mixed = xp.copy()
+    mixed.reshape(-1)[::2] *= np.float32(1e-30)
+    mixed.reshape(-1)[1::2] *= np.float32(1e+12)
+    _run_steps(ff, wl, 1, inputs=(mixed, xn))

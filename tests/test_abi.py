@@ -141,3 +141,29 @@ def test_chain_lookahead_validation(ff):
     assert nbytes("cfg5", 1) > nbytes("cfg5", 0)
     assert nbytes("tiny_l2", 1) == 0 and nbytes("tiny_conv", 1) == 0 and nbytes("tiny_res", 1) == 0
     assert nbytes("tiny", 2) == 0 and nbytes("tiny", -1) == 0
+
+
+def test_int32_reduction_limits(ff):
+    """The longest weight-gradient reduction that cannot overflow int32 is 133 144 rows (127^2 * 133144 < 2^31): one
+    accumulator up to there, power-of-two sample blocks beyond, and the step refuses more than two blocks per pass."""
+    import ctypes as C
+    from workloads import Layer
+    assert 127 * 127 * 133144 < 2**31 <= 127 * 127 * 133145
+
+    def chunks_and_ws(B):
+        d = ff.layer_desc(Layer("dense", in_features=32, out_features=16), B)
+        descs = (ff.binding.LayerDesc * 1)(d)
+        return ff.ff_layer_dw_chunks(d), ff.lib().ff_workspace_bytes(C.byref(ff.binding.NetDesc(1, B, descs)))
+
+    assert chunks_and_ws(133144)[0] == 1 and chunks_and_ws(133144)[1] > 0
+    assert chunks_and_ws(133145)[0] == 2 and chunks_and_ws(133145)[1] > 0       # blocks of 131072 samples
+    assert chunks_and_ws(262144)[0] == 2 and chunks_and_ws(262144)[1] > 0
+    assert chunks_and_ws(262145) == (3, 0)                                       # a third block: not in ff_train_step
+    conv = Layer("conv", H=32, W=32, C_in=16, C_out=16, ksize=3, stride=1, pad=1)   # 1024 rows per sample
+    assert ff.ff_layer_dw_chunks(ff.layer_desc(conv, 130)) == 1                  # 133120 rows
+    assert ff.ff_layer_dw_chunks(ff.layer_desc(conv, 131)) == 2                  # blocks of 128 samples
+    assert ff.ff_layer_dw_chunks(ff.layer_desc(conv, 256)) == 2
+    assert ff.ff_layer_dw_chunks(ff.layer_desc(conv, 257)) == 3
+    # a reduction over the input features longer than the limit cannot be chunked: the forward pass refuses it
+    long = ff.layer_desc(Layer("dense", in_features=133145, out_features=16), 8)
+    assert ff.ff_goodness_shift(long) >= 0 and ff.ff_layer_workspace_bytes(long) >= 0

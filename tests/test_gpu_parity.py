@@ -556,3 +556,12 @@ def test_train_step_degenerate_inputs(ff, name):
     mixed.reshape(-1)[::2] *= np.float32(1e-30)
     mixed.reshape(-1)[1::2] *= np.float32(1e+12)
     _run_steps(ff, wl, 1, inputs=(mixed, xn))
+
+
+def test_train_step_dense_reduction_in_two_blocks(ff):
+    """A dense stack whose batch (133 200 samples per pass) is longer than an int32 accumulator allows: the weight
+    gradient of every layer is taken in two blocks of 131 072 and 2 128 samples and combined in the update."""
+    from workloads import Workload, mlp
+    wl = Workload("long_batch", mlp([16, 8, 12], False), 133200, "uniform_onehot", lam=0.1, theta=3.0)
+    assert ff.ff_layer_dw_chunks(ff.layer_desc(wl.layers[0], wl.batch)) == 2
+    _run_steps(ff, wl, 1)

@@ -565,3 +565,4 @@ def test_train_step_dense_reduction_in_two_blocks(ff):
     wl = Workload("long_batch", mlp([16, 8, 12], False), 133200, "uniform_onehot", lam=0.1, theta=3.0)
     assert ff.ff_layer_dw_chunks(ff.layer_desc(wl.layers[0], wl.batch)) == 2
     _run_steps(ff, wl, 1)
+    _run_steps(ff, wl, 1, lookahead="chain")

@@ -3,6 +3,7 @@ CPU oracle, int8 / int32 bit-exact, fp32 within 1e-5), on shapes nobody picked b
 columns, widths just past a tile or a 16-byte boundary."""
 import os
 import sys
+from dataclasses import replace
 
 import numpy as np
 import pytest
@@ -88,7 +89,10 @@ def test_random_dense_stacks(ff):
         widths = [_dims(rng, 1, 12, 300)[0]] + _dims(rng, depth, 1, 300)   # the label overlay needs ten input features
         B = int(rng.integers(1, 90))
         norm = bool(rng.integers(0, 2))
-        wl = Workload(f"rand{case}", mlp(widths, norm), B, "uniform_onehot", lam=float(rng.choice([0.0, 0.1, 0.7])),
+        layers = mlp(widths, norm)
+        if case % 3 == 2:      # some stacks mix ReLU and identity activations
+            layers = tuple(replace(l, relu=int(rng.integers(0, 2))) for l in layers)
+        wl = Workload(f"rand{case}", layers, B, "uniform_onehot", lam=float(rng.choice([0.0, 0.1, 0.7])),
                       theta=float(rng.choice([2.0, 10.0, 40.0])))
         P._run_steps(ff, wl, 2)
         if not norm:

@@ -94,24 +94,20 @@ float ffo_uniform(uint64_t seed, uint64_t tag, uint64_t idx)
 /* ------------------------------------------------------------------------
  * Symmetric uniform quantiser, per tensor, codes in [-127, 127]
  * (Section IV, Section IV-B).  n elements, element i uses random index i
- * (the linear index of the logical row-major tensor).
- * amax_in < 0: scan the tensor for max|x|; otherwise use the given amax.
+ * (the linear index of the logical row-major tensor).  The range is max|x|
+ * over the tensor itself.
  * The paper fixes no behaviour for a vanishing range; see the comment below.
  * ---------------------------------------------------------------------- */
 static int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 int ffo_quantize(const float *x, int64_t n, int mode, uint64_t seed, uint64_t tag,
-                 float amax_in, int8_t *q, float *scale_out)
+                 int8_t *q, float *scale_out)
 {
     if (!x || !q || !scale_out || n < 0) return FFO_ERR_ARG;
     float amax = 0.0f;
-    if (amax_in >= 0.0f) {
-        amax = amax_in;
-    } else {
-        for (int64_t i = 0; i < n; ++i) {
-            float a = fabsf(x[i]);
-            if (a > amax) amax = a;
-        }
+    for (int64_t i = 0; i < n; ++i) {
+        float a = fabsf(x[i]);
+        if (a > amax) amax = a;
     }
     /* A vanishing range (absmax below 2^-100, which includes the all-zero tensor) quantises to
      * all-zero codes with scale 1: 127/absmax must stay a finite fp32 number, and magnitudes this

@@ -42,7 +42,7 @@ def lib() -> C.CDLL:
         L.ffo_hash.argtypes = [u64, u64, u64]
         L.ffo_uniform.restype = f32
         L.ffo_uniform.argtypes = [u64, u64, u64]
-        L.ffo_quantize.argtypes = [P, i64, i32, u64, u64, f32, P, P]
+        L.ffo_quantize.argtypes = [P, i64, i32, u64, u64, P, P]
         L.ffo_dequantize.argtypes = [P, i64, f32, P]
         L.ffo_dequantize.restype = None
         L.ffo_dense_forward.argtypes = [P, P, i64, i64, i64, P]
@@ -98,12 +98,12 @@ def uniform(seed: int, tag: int, idx: int) -> float:
     return float(lib().ffo_uniform(seed, tag, idx))
 
 
-def quantize(x: np.ndarray, mode: int, seed: int = 0, tag: int = 0, amax: float = -1.0):
+def quantize(x: np.ndarray, mode: int, seed: int = 0, tag: int = 0):
     """Per-tensor symmetric int8 quantisation.  Returns (q with x's shape, scale)."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     q = np.empty(x.shape, dtype=np.int8)
     s = np.zeros(1, dtype=np.float32)
-    _chk(lib().ffo_quantize(_p(x), x.size, mode, seed, tag, amax, _p(q), _p(s)), "quantize")
+    _chk(lib().ffo_quantize(_p(x), x.size, mode, seed, tag, _p(q), _p(s)), "quantize")
     return q, np.float32(s[0])
 
 
@@ -342,6 +342,13 @@ def batch_chunks(B: int, rows_per_sample: int) -> List[tuple]:
 # --------------------------------------------------------------------------------------
 # Algorithm 1, one iteration.
 # --------------------------------------------------------------------------------------
+def _theta_of(theta, i: int) -> float:
+    """The goodness threshold of layer i: Section V-A uses one value (2.0) for every layer; a sequence
+    gives each layer its own (a generalisation the tests use to keep both passes' gradients live at
+    initialisation, where the goodness differs from layer to layer by orders of magnitude)."""
+    return float(theta[i]) if hasattr(theta, "__len__") else float(theta)
+
+
 def forward_layer(layer, a_f32: np.ndarray, w_q: np.ndarray, s_w, pass_sign: int, theta: float,
                   seed: int, tag_act: int) -> Dict:
     """Quantise the layer input (stochastic rounding), contract, goodness, loss coefficient,
@@ -401,7 +408,7 @@ def train_step(layers, w_master: List[np.ndarray], x_pos: np.ndarray, x_neg: np.
                 fwd[i][p] = dict(a_q=a_q, s_a=s_a, acc=acc, c=np.zeros(B, np.float32), loss_mean=0.0,
                                  G=np.zeros(B, np.float32))
             elif skip[i] == "none":
-                f = forward_layer(layer, a, wq[i][0], wq[i][1], sign, theta, seed, tag)
+                f = forward_layer(layer, a, wq[i][0], wq[i][1], sign, _theta_of(theta, i), seed, tag)
                 outs[i] = f.pop("a_next")
                 fwd[i][p] = f
             else:
@@ -413,7 +420,7 @@ def train_step(layers, w_master: List[np.ndarray], x_pos: np.ndarray, x_neg: np.
                     u = skip_projection(fwd[i - 2][p]["acc"], fwd[i - 2][p]["s_a"], wq[i - 2][1])
                 y = residual_act(acc, u.reshape(acc.shape), layer.relu, s_a, wq[i][1])
                 gd = goodness_fx(y)
-                c, loss, loss_mean = loss_coeff(gd["G"], sign, theta)
+                c, loss, loss_mean = loss_coeff(gd["G"], sign, _theta_of(theta, i))
                 outs[i] = y
                 fwd[i][p] = dict(a_q=a_q, s_a=s_a, acc=acc, y=y, c=c, loss=loss, loss_mean=loss_mean, **gd)
     ctil = [lookahead(np.stack([fwd[i][p]["c"] for i in range(k)]), lam) for p in range(2)]
@@ -493,7 +500,7 @@ def train_step_chain(layers, w_master: List[np.ndarray], x_pos: np.ndarray, x_ne
     for p, (x, sign) in enumerate(((x_pos, PASS_POS), (x_neg, PASS_NEG))):
         a = np.ascontiguousarray(x, dtype=np.float32)
         for i, layer in enumerate(layers):
-            f = forward_layer(layer, a, wq[i][0], wq[i][1], sign, theta, seed, stream_tag(step, i, p, KIND_ACT))
+            f = forward_layer(layer, a, wq[i][0], wq[i][1], sign, _theta_of(theta, i), seed, stream_tag(step, i, p, KIND_ACT))
             a = f.pop("a_next")
             fwd[i][p] = f
     grads: List[List[Dict]] = [[None, None] for _ in range(k)]

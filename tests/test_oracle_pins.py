@@ -173,6 +173,51 @@ def test_int32_overflow_is_reported():
     assert O.dense_forward(ok, ok.copy())[0, 0] == O.INT32_SAFE_ROWS * 16129
 
 
+def test_batch_chunks_cover_the_batch_and_fit_int32():
+    """Section IV-B (INT32 accumulation), reading R-CK: a weight-gradient reduction over more rows than
+    floor((2^31 - 1) / 127^2) = 133144 is cut into blocks of samples, each block with its own int32
+    accumulator.  Pinned here: the bound itself (worst-case codes of +-127 just fit, one more row does not),
+    the exact lists for the conv configurations, and for a sweep of shapes that the blocks are disjoint,
+    cover [0, B) in order, stay within the bound and have a power-of-two size (except the last)."""
+    assert O.INT32_SAFE_ROWS == 133144
+    assert O.INT32_SAFE_ROWS * 127 * 127 <= 2**31 - 1 < (O.INT32_SAFE_ROWS + 1) * 127 * 127
+    assert O.batch_chunks(256, 32 * 32) == [(0, 128), (128, 256)]          # cfg3, cfg4 stage 1
+    assert O.batch_chunks(140, 32 * 32) == [(0, 128), (128, 140)]          # ragged last block
+    assert O.batch_chunks(256, 16 * 16) == [(0, 256)]                      # 65536 rows fit one accumulator
+    assert O.batch_chunks(8192, 1) == [(0, 8192)]                          # every dense configuration
+    assert O.batch_chunks(0, 1024) == [(0, 0)]
+    assert O.batch_chunks(133144, 1) == [(0, 133144)]
+    assert O.batch_chunks(133145, 1) == [(0, 131072), (131072, 133145)]
+    with pytest.raises(O.OracleError):
+        O.batch_chunks(2, O.INT32_SAFE_ROWS + 1)                           # one sample alone is too long
+    rng = np.random.default_rng(7)
+    for _ in range(300):
+        rps = int(rng.integers(1, 70000))
+        B = int(rng.integers(1, 5000))
+        ch = O.batch_chunks(B, rps)
+        assert ch[0][0] == 0 and ch[-1][1] == B
+        for (a0, a1), (b0, b1) in zip(ch, ch[1:]):
+            assert a1 == b0
+        for b0, b1 in ch:
+            assert b0 < b1 and (b1 - b0) * rps <= O.INT32_SAFE_ROWS
+        if len(ch) > 1:
+            per = ch[0][1] - ch[0][0]
+            assert per & (per - 1) == 0 and 2 * per * rps > O.INT32_SAFE_ROWS   # the largest power of two that fits
+            assert all(b1 - b0 == per for b0, b1 in ch[:-1])
+
+
+def test_chunked_weight_gradient_sums_to_the_unchunked_one():
+    """Blocks of samples are a partition of the reduction: their int32 accumulators add up (in exact
+    integer arithmetic) to the accumulator of the whole batch whenever that one exists."""
+    rng = np.random.default_rng(11)
+    B, H, W, Ci, Co = 5, 4, 6, 3, 4
+    a = rng.integers(-127, 128, (B, H, W, Ci)).astype(np.int8)
+    g = rng.integers(-127, 128, (B, H, W, Co)).astype(np.int8)
+    whole = O.conv_wgrad(g, a, 3, 1, 1, 0, B).astype(np.int64)
+    parts = sum(O.conv_wgrad(g, a, 3, 1, 1, b0, b1).astype(np.int64) for b0, b1 in [(0, 2), (2, 4), (4, 5)])
+    assert np.array_equal(whole, parts)
+
+
 def _im2col(a, ks, stride, pad):
     B, H, W, C = a.shape
     Ho = (H + 2 * pad - ks) // stride + 1

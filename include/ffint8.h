@@ -11,14 +11,21 @@
  *  - Every data pointer is a DEVICE pointer unless marked [host].  Descriptors
  *    (ff_layer_desc, ff_net_desc, ff_net_state and the pointer arrays inside
  *    ff_net_state) are [host] memory.
- *  - The caller owns every buffer.  The library allocates nothing, frees
- *    nothing, and keeps no pointer after a call returns.
+ *  - The caller owns every buffer.  The library allocates and frees no device
+ *    memory and keeps no pointer after a call returns.  (The optional timing
+ *    instrumentation at the end of this file creates host-side HIP events on
+ *    first use; it is off unless ff_timing_enable is called.)
  *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *    the default stream).  Calls return without synchronising; scalars that are
  *    produced on the device (scales, losses) stay on the device.
- *  - Arguments are validated on the host before anything is launched; on error
- *    nothing has been enqueued and no output has been touched.  The library
- *    never throws, aborts or prints.
+ *  - Arguments, shapes and the launch limits of the kernels (FF_ERR_UNSUPPORTED
+ *    for sizes beyond them: a tensor of 2^32 elements or more, more than
+ *    8 388 480 rows in a quantised matrix, more than 65535 output features or
+ *    channels) are validated on the host before anything is launched; on such
+ *    an error nothing has been enqueued and no output has been touched.
+ *    FF_ERR_HIP reports a failure of the HIP runtime itself (a launch that the
+ *    runtime rejects); kernels enqueued before it have run.  The library never
+ *    throws, aborts or prints.
  *  - int8 matrices are row-major with a row pitch of ff_pitch(cols) bytes
  *    (cols rounded up to 16); the pad bytes of every int8 tensor the library
  *    WRITES are zero, and every int8 tensor it READS must have zero pad bytes.
@@ -29,8 +36,9 @@
  *  - Determinism: equal inputs and equal (seed, stream_tag / step) give
  *    bit-identical outputs on every run; all cross-workgroup accumulations are
  *    integer sums or maxima.
- *  - There is no input-gradient output anywhere: the method never forms g^A
- *    (Section IV-B).
+ *  - In the default reading there is no input-gradient output: the method
+ *    never forms g^A (Section IV-B).  Only the FF_LOOKAHEAD_CHAIN variant, which
+ *    takes Eq. (4) as an exact derivative, has one (ff_layer_input_grad).
  */
 #ifndef FFINT8_H
 #define FFINT8_H
@@ -111,6 +119,11 @@ typedef struct {
                                     before it, but its weights are left as they are (the greedy layer-by-layer
                                     schedule of Section III trains layer i with layers < i frozen). */
     int32_t lookahead;           /* FF_LOOKAHEAD_COEFF (0, the default reading) or FF_LOOKAHEAD_CHAIN, see below */
+    const float* theta_layer;    /* [host] n_layers goodness thresholds, or NULL = the `theta` argument of
+                                    ff_train_step for every layer (Section V-A uses one value, 2.0).  With freshly
+                                    initialised weights the goodness of different layers differs by orders of
+                                    magnitude; a threshold per layer keeps Eq. (1) and Eq. (2) away from saturation
+                                    in all of them. */
 } ff_net_desc;
 
 /* How the later layers' losses enter a layer's update (Eq. (3), Eq. (4)).
@@ -165,7 +178,7 @@ ff_status ff_quantize(const float* x, int64_t rows, int64_t cols, int32_t round_
 
 /* ---------------------------------------------------------------------------------------------
  * ff_layer_forward — the int8 x int8 -> int32 contraction of one layer for one pass
- * (Section IV-B: "INT8 inputs and INT32 accumulation"), with the per-sample reductions the
+ * (Section IV-B: int8 operands, int32 accumulators), with the per-sample reductions the
  * goodness needs fused into its epilogue (Algorithm 1: G = ||y||^2).
  *   a_q      int8 [M, ff_pitch(K)] (dense: M = batch, K = in_features)               (in)
  *   w_q      int8 [N, ff_pitch(K)]                                                   (in)
@@ -276,7 +289,7 @@ ff_status ff_layer_input_grad(const ff_layer_desc* layer, const int8_t* h_q, con
 
 /* ---------------------------------------------------------------------------------------------
  * ff_layer_update — SGD step on the fp32 master weights from both passes' integer accumulators
- * and requantisation (Algorithm 1: "update weights using gradients in INT8 precision"):
+ * and requantisation (Algorithm 1, the update line of the inner loop):
  *   g = fp32(dw_pos) * (s_g_pos * s_a_pos);  g = fma(fp32(dw_neg), s_g_neg * s_a_neg, g)
  *   w = fma(-(lr / total_samples), g, w)
  *   w_q, s_w = nearest-even quantisation of the new w.

@@ -33,7 +33,8 @@ class LayerDesc(C.Structure):
 
 class NetDesc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("batch", C.c_int32), ("layers", C.POINTER(LayerDesc)),
-                ("train_layer", C.POINTER(C.c_int32)), ("lookahead", C.c_int32)]
+                ("train_layer", C.POINTER(C.c_int32)), ("lookahead", C.c_int32),
+                ("theta_layer", C.POINTER(C.c_float))]
 
 
 class NetState(C.Structure):
@@ -216,12 +217,16 @@ class Net:
     Holds references to the tensors so that the pointer arrays stay valid."""
 
     def __init__(self, layers: Sequence, batch: int, w_master: List[torch.Tensor], w_q: List[torch.Tensor],
-                 s_w: List[torch.Tensor], train_layer: Optional[Sequence[int]] = None, lookahead: str = "coeff"):
+                 s_w: List[torch.Tensor], train_layer: Optional[Sequence[int]] = None, lookahead: str = "coeff",
+                 theta_layer: Optional[Sequence[float]] = None):
         self.k = len(layers)
         self.batch = batch
         self._descs = (LayerDesc * self.k)(*[layer_desc(l, batch) for l in layers])
         self._mask = (C.c_int32 * self.k)(*[int(bool(f)) for f in train_layer]) if train_layer is not None else None
-        self.desc = NetDesc(self.k, batch, self._descs, self._mask, {"coeff": 0, "chain": 1}[lookahead])
+        self._theta = (C.c_float * self.k)(*[float(t) for t in theta_layer]) if theta_layer is not None else None
+        if theta_layer is not None and len(theta_layer) != self.k:
+            raise ValueError("theta_layer needs one threshold per layer")
+        self.desc = NetDesc(self.k, batch, self._descs, self._mask, {"coeff": 0, "chain": 1}[lookahead], self._theta)
         self.w_master, self.w_q, self.s_w = list(w_master), list(w_q), list(s_w)
         self._pm = (C.c_void_p * self.k)(*[t.data_ptr() for t in self.w_master])
         self._pq = (C.c_void_p * self.k)(*[t.data_ptr() for t in self.w_q])

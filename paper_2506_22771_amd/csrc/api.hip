@@ -24,6 +24,13 @@ struct Dims {
     int role, skip;            // residual-block wiring (ff_layer_desc)
 };
 
+// Sizes the quantise kernels accept: fewer than 2^32 elements (32-bit element index in the random stream) and at
+// most 65535 row blocks of 128 rows (grid.y).
+static bool quant_shape_ok(int64_t rows, int64_t cols)
+{
+    return rows >= 0 && cols >= 0 && (cols == 0 || rows < (int64_t(1) << 32) / cols) && (rows + 127) / 128 <= 65535;
+}
+
 static ff_status layer_dims(const ff_layer_desc* L, Dims* d)
 {
     if (!L) return FF_ERR_INVALID_ARG;
@@ -66,6 +73,12 @@ static ff_status layer_dims(const ff_layer_desc* L, Dims* d)
     } else {
         return FF_ERR_INVALID_ARG;
     }
+    // Launch limits of the kernels behind this layer, checked here so that an unsupported size is reported before
+    // anything has been enqueued: the quantisers index elements with 32 bits and put 128 rows per workgroup on
+    // grid.y; the update puts one weight row (or four) on grid.y; the depthwise kernels one sample.
+    if (!quant_shape_ok(d->in_rows, d->in_cols) || !quant_shape_ok(d->M, d->N) || !quant_shape_ok(d->N, d->K) ||
+        d->N > 65535 || (L->kind == FF_DWCONV2D && d->B > 65535))
+        return FF_ERR_UNSUPPORTED;
     // Weight-gradient reduction: one accumulator if M * 127^2 fits int32, otherwise equal blocks of `per`
     // samples, per = the largest power of two with per * rps <= 133144.
     if (d->M <= INT32_SAFE_LEN) {
@@ -195,6 +208,8 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
         }
         if (L.skip != FF_SKIP_NONE) {
             if (d.kind != FF_CONV2D || L.role != FF_ROLE_LAYER || L.l2norm_out || (d.N & 3) || L.input_back != 0)
+                return FF_ERR_UNSUPPORTED;
+            if (d.B > 65535 || d.rps * (d.N >> 2) > (int64_t(1) << 28))   // launch limits of the block-output kernels
                 return FF_ERR_UNSUPPORTED;
             if (L.skip == FF_SKIP_IDENTITY) {
                 if (i < 1) return FF_ERR_SHAPE;
@@ -603,6 +618,7 @@ ff_status ff_quantize(const float* x, int64_t rows, int64_t cols, int32_t round_
 {
     if (rows < 0 || cols < 0 || !scale || (!q && !q_t) || !ws) return FF_ERR_INVALID_ARG;
     if (round_mode != FF_ROUND_NEAREST_EVEN && round_mode != FF_ROUND_STOCHASTIC) return FF_ERR_INVALID_ARG;
+    if (!quant_shape_ok(rows, cols)) return FF_ERR_UNSUPPORTED;
     if (ws_bytes < FF_WS_MIN_BYTES) return FF_ERR_WORKSPACE;
     if (!aligned16(ws) || (q && !aligned16(q)) || (q_t && !aligned16(q_t)) || !aligned4(scale)) return FF_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
@@ -1115,7 +1131,7 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         ga.rshift = goodness_shift(d.K, d.rps * d.N);
         ga.l2norm = L.l2norm_out ? 1 : 0;
         ga.pass_sign = FF_PASS_POS;
-        ga.theta = theta;
+        ga.theta = net->theta_layer ? net->theta_layer[i] : theta;
         ga.B = B;
         ga.goodness = goodness + (int64_t)i * 2 * B;
         ga.coeff = c + (int64_t)i * 2 * B;

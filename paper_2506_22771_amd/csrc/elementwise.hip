@@ -197,8 +197,9 @@ template <int CB> struct QTile {
 // to a word for q, byte-transposed in registers for q_t and regrouped through LDS so that q_t is
 // written in 16-byte pieces.  All eight 16-byte loads of a thread are issued before any arithmetic.
 // VEC: 16-byte loads are legal (always for the int32 sources; for fp32 when cols % 4 == 0 and the base
-// is 16-byte aligned).  BIG: the tensor has 2^32 elements or more (64-bit element index).
-template <int SRC, bool STOCH, bool VEC, bool BIG, int CB = 16>
+// is 16-byte aligned).  Tensors have fewer than 2^32 elements (checked by the entry points), so the low
+// word of the element index is the whole index.
+template <int SRC, bool STOCH, bool VEC, int CB = 16>
 __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
 {
     constexpr int QT_ROWS = QTile<CB>::ROWS, QT_COLS = QTile<CB>::COLS, QT_LDW = QTile<CB>::LDW, QT_RH = QTile<CB>::RH;
@@ -303,18 +304,7 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
         for (int j = 0; j < 4; ++j) {
             const int dr = QT_RH * u + j;
             const int64_t row = rowb + dr;
-            uint32_t base_lo;
-            uint32_t kk = key.k0;
-            bool straddle = false;
-            if (BIG) {
-                const uint64_t idx = idx0 + (uint64_t)dr * (uint64_t)a.cols;
-                base_lo = (uint32_t)idx;
-                const uint32_t hi = (uint32_t)(idx >> 32);
-                straddle = hi != (uint32_t)((idx + 3) >> 32);   // the four elements cross a 2^32 boundary (rare)
-                kk += hi * key.k1;
-            } else {
-                base_lo = (uint32_t)idx0 + (uint32_t)dr * (uint32_t)a.cols;
-            }
+            const uint32_t base_lo = (uint32_t)idx0 + (uint32_t)dr * (uint32_t)a.cols;
             uint32_t pack = 0;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -326,11 +316,9 @@ __global__ __launch_bounds__(QT_THREADS) void k_quantize(QuantArgs a)
                     if (SRC == QSRC_GRAD) v = rowf[u][j] * v;
                     else if (a.l2norm) v = rowf[u][j] > 0.0f ? v / rowf[u][j] : 0.0f;
                 }
-                uint32_t kc = kk;
-                if (BIG && straddle && base_lo + (uint32_t)c < base_lo) kc += key.k1;   // carried into the high half
                 // elements outside the tensor were loaded as zero and a dead range has inv == 0: in both
                 // cases t == 0, so the code is 0 in either rounding mode without any masking
-                const int code = quant_code<STOCH>(v, inv, (base_lo + (uint32_t)c) ^ kc);
+                const int code = quant_code<STOCH>(v, inv, (base_lo + (uint32_t)c) ^ key.k0);
                 pack |= ((uint32_t)code & 0xFFu) << (8 * c);
             }
             rowpack[j] = pack;
@@ -375,25 +363,19 @@ template <int SRC, bool STOCH>
 static void launch_quantize_t(const QuantArgs& a, hipStream_t s)
 {
     const dim3 block(QT_THREADS);
-    const bool big = (uint64_t)a.rows * (uint64_t)a.cols >= (uint64_t(1) << 32);
     bool vec = true;
     if (SRC == QSRC_F32 || SRC == QSRC_F32_GRAD) {
         vec = (a.cols & 3) == 0 && (((uintptr_t)a.x) & 15) == 0 && ((a.st_x & 3) == 0 || a.nb == 1);
     }
-    if (a.cols <= QTile<8>::COLS && vec && !big) {
+    if (a.cols <= QTile<8>::COLS && vec) {
         const dim3 grid(1, (unsigned)((a.rows + QTile<8>::ROWS - 1) / QTile<8>::ROWS), (unsigned)a.nb);
-        hipLaunchKernelGGL((k_quantize<SRC, STOCH, true, false, 8>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((k_quantize<SRC, STOCH, true, 8>), grid, block, 0, s, a);
         return;
     }
     const dim3 grid((unsigned)((a.cols + QTile<16>::COLS - 1) / QTile<16>::COLS),
                     (unsigned)((a.rows + QTile<16>::ROWS - 1) / QTile<16>::ROWS), (unsigned)a.nb);
-    if (big) {
-        if (vec) hipLaunchKernelGGL((k_quantize<SRC, STOCH, true, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_quantize<SRC, STOCH, SRC != QSRC_F32 && SRC != QSRC_F32_GRAD, true>), grid, block, 0, s, a);
-    } else {
-        if (vec) hipLaunchKernelGGL((k_quantize<SRC, STOCH, true, false>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_quantize<SRC, STOCH, SRC != QSRC_F32 && SRC != QSRC_F32_GRAD, false>), grid, block, 0, s, a);
-    }
+    if (vec) hipLaunchKernelGGL((k_quantize<SRC, STOCH, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((k_quantize<SRC, STOCH, SRC != QSRC_F32 && SRC != QSRC_F32_GRAD>), grid, block, 0, s, a);
 }
 
 hipError_t launch_quantize(int src, const QuantArgs& a, hipStream_t s)

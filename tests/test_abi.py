@@ -167,3 +167,29 @@ def test_int32_reduction_limits(ff):
     # a reduction over the input features longer than the limit cannot be chunked: the forward pass refuses it
     long = ff.layer_desc(Layer("dense", in_features=133145, out_features=16), 8)
     assert ff.ff_goodness_shift(long) >= 0 and ff.ff_layer_workspace_bytes(long) >= 0
+
+
+def test_launch_limits_are_host_side(ff):
+    """Sizes beyond what the kernels' grids and 32-bit element indices cover are refused on the host with
+    FF_ERR_UNSUPPORTED (-6) before anything is enqueued: tensors of 2^32 elements or more, more than 65535 row
+    blocks of 128 rows in a quantised matrix, more than 65535 output features."""
+    L = ff.lib()
+    from workloads import Layer
+    P = C.c_void_p
+    fake = P(0x1000)        # never dereferenced: validation fails first
+    assert L.ff_quantize(fake, 1 << 16, 1 << 16, 1, 0, 0, fake, P(0), fake, fake, 4096, P(0)) == -6   # 2^32 elements
+    assert L.ff_quantize(fake, 65535 * 128 + 1, 4, 1, 0, 0, fake, P(0), fake, fake, 4096, P(0)) == -6   # grid rows
+
+    def status(layer, B):
+        d = ff.layer_desc(layer, B)
+        return L.ff_layer_forward(C.byref(d), fake, fake, fake, fake, fake, fake, 4096, P(0))
+
+    assert status(Layer("dense", in_features=1 << 15, out_features=1 << 15), 1 << 17) == -6   # B*K = 2^32
+    assert status(Layer("dense", in_features=16, out_features=65536), 8) == -6                # weight rows on grid.y
+    assert status(Layer("dense", in_features=16, out_features=16), 65535 * 128 + 1) == -6     # batch rows on grid.y
+    assert ff.ff_layer_workspace_bytes(ff.layer_desc(Layer("dense", in_features=16, out_features=65535), 8)) > 0
+    assert ff.ff_layer_workspace_bytes(ff.layer_desc(Layer("dense", in_features=16, out_features=16), 65535 * 128)) > 0
+    many = Layer("conv", H=32, W=32, C_in=16, C_out=16, ksize=3, stride=1, pad=1, skip="identity")
+    descs = (ff.binding.LayerDesc * 2)(ff.layer_desc(Layer("conv", H=32, W=32, C_in=16, C_out=16, ksize=3, stride=1, pad=1), 70000),
+                                       ff.layer_desc(many, 70000))
+    assert L.ff_workspace_bytes(C.byref(ff.binding.NetDesc(2, 70000, descs))) == 0            # block-output kernels: B on grid.y

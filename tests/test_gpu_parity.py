@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 from oracle import ff_oracle as O  # noqa: E402
-from workloads import Layer, make_inputs, make_weights, workload  # noqa: E402
+from workloads import Layer, make_inputs, make_weights, scaled, workload  # noqa: E402
 
 
 @pytest.fixture(scope="module")
@@ -347,7 +347,31 @@ def test_conv_weight_gradient_chunks(ff):
 
 
 # ------------------------------------------------------------------------------------------- whole step
-def _run_steps(ff, wl, n_steps, lam=None, lookahead="coeff", theta=None, inputs=None):
+def _matched_thetas(wl, sample_batch=32):
+    """One goodness threshold per layer at which Eq. (1) and Eq. (2) are both away from saturation for freshly
+    initialised weights: the median goodness of the layer over a small batch of both data sets, from the oracle.
+    (At the paper's theta = 2.0 and Kaiming weights the goodness is in the hundreds to tens of thousands, the
+    positive-pass coefficient sits at the exponent clamp and its int8 gradient is all zeros.)"""
+    small = scaled(wl, min(sample_batch, wl.batch))
+    xp, xn = make_inputs(small)
+    ref = O.train_step(small.layers, make_weights(small), xp, xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, 0, keep=False)
+    return [float(np.median(ref["goodness"][i])) if l.role != "proj" else 0.0 for i, l in enumerate(wl.layers)]
+
+
+def _assert_live(ref, wl):
+    """Oracle side: in every trained layer both passes carry a live int8 local gradient (a real scale, non-zero
+    codes) and a non-zero weight gradient."""
+    for i, l in enumerate(wl.layers):
+        if l.role == "proj":
+            continue
+        for p in range(2):
+            g = ref["grads"][i][p]
+            assert g["s_g"] != np.float32(1.0), f"layer {i} pass {p}: dead gradient range"
+            assert np.count_nonzero(g["gy_q"]) > g["gy_q"].size // 100, f"layer {i} pass {p}: gradient codes (almost) all zero"
+            assert all(np.any(d) for d in g["dw"]), f"layer {i} pass {p}: zero weight gradient"
+
+
+def _run_steps(ff, wl, n_steps, lam=None, lookahead="coeff", theta=None, inputs=None, theta_layer=None, live=False):
     lam = wl.lam if lam is None else lam
     theta = wl.theta if theta is None else theta
     oracle_step = O.train_step if lookahead == "coeff" else O.train_step_chain
@@ -360,7 +384,7 @@ def _run_steps(ff, wl, n_steps, lam=None, lookahead="coeff", theta=None, inputs=
     ws1 = workspace()
     for i, l in enumerate(wl.layers):
         ff.ff_quantize(d_w[i], l.N, l.K, 0, 0, 0, d_wq[i], None, d_sw[i], ws1)
-    net = ff.Net(wl.layers, B, d_w, d_wq, d_sw, lookahead=lookahead)
+    net = ff.Net(wl.layers, B, d_w, d_wq, d_sw, lookahead=lookahead, theta_layer=theta_layer)
     nbytes = net.workspace_bytes()
     assert nbytes > 0
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
@@ -371,7 +395,10 @@ def _run_steps(ff, wl, n_steps, lam=None, lookahead="coeff", theta=None, inputs=
     for step in range(n_steps):
         ff.ff_train_step(net, d_xp, d_xn, theta, lam, wl.lr, wl.sr_seed, step, loss, good, ws)
         torch.cuda.synchronize()
-        ref = oracle_step(wl.layers, Wref, xp, xn, theta, lam, wl.lr, wl.sr_seed, step, keep=False)
+        ref = oracle_step(wl.layers, Wref, xp, xn, theta if theta_layer is None else theta_layer, lam, wl.lr,
+                          wl.sr_seed, step, keep=live)
+        if live:
+            _assert_live(ref, wl)
         Wref = ref["w_master"]
         assert rel_close(good.cpu().numpy(), ref["goodness"], TOL), f"goodness step {step}"
         assert rel_close(loss.cpu().numpy(), ref["loss"], TOL), f"loss step {step}"
@@ -428,6 +455,27 @@ def test_train_step_cfg5_full_size(ff):
     configuration bench.py times, against the complete oracle step: every master weight and int8 weight of
     both layers bit-exact, goodness and loss within 1e-5.  Takes a minute or two of CPU oracle time."""
     _run_steps(ff, workload("cfg5"), 1)
+
+
+@pytest.mark.slow
+@pytest.mark.timeout(1500)
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg5", "cfg3", "cfg4"])
+def test_train_step_full_size_live_positive_pass(ff, name):
+    """Every configuration at its full size once more, with a goodness threshold per layer matched to the layer's
+    initial goodness, so that the positive pass (Eq. (1)) is not at the exponent clamp: its int8 local gradient
+    and weight-gradient contraction are then compared on live codes in every layer, not on zeros.  The oracle
+    side asserts that liveness before the comparison counts."""
+    wl = workload(name)
+    _run_steps(ff, wl, 1, theta_layer=_matched_thetas(wl), live=True)
+
+
+def test_theta_per_layer_equals_scalar_theta(ff):
+    """A per-layer threshold array holding the same value everywhere gives the scalar-theta step bit for bit."""
+    wl = workload("tiny_l2")
+    a = _run_steps(ff, wl, 2)
+    b = _run_steps(ff, wl, 2, theta_layer=[wl.theta] * len(wl.layers))
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(x, y)
 
 
 def test_train_step_lambda_zero_and_reproducible(ff):

@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the FF-INT8 layer-local train step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg2|cfg1] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg1|cfg2|cfg3|cfg4|...]
+                    [--theta matched|paper] [--no-cpu-baseline] [--no-other-configs]
 
 A "step" is one ff_train_step: one iteration of the paper's Algorithm 1 over one synthetic batch
 (positive + negative set, all layers: quantise, int8 forward, goodness/loss, look-ahead, int8 local
@@ -11,8 +12,17 @@ region starts.  One JSON line is printed.
 metric: FF-INT8 train samples/s per layer step = (B_pos + B_neg) * n_layers / step time, i.e. the rate
 at which samples pass through one layer's complete step.  `roofline` scores the dominant kernel (the
 int8 MFMA contraction, forward and weight-gradient launches together) from HIP events recorded on
-the launch stream during the timed steps.  `cpu_baseline` times the CPU oracle on a bounded sample
-(a smaller batch of the same network).
+the launch stream during the timed steps.
+
+Goodness threshold.  The paper's theta = 2.0 (Section V-A) is far below the goodness of freshly
+initialised layers (4000 for cfg5), so at theta = 2.0 the positive-pass coefficient of Eq. (1) is at the
+exponent clamp, its int8 local gradient is all zeros and half of every weight-gradient launch multiplies
+zeros, which runs faster than live data.  The default (--theta matched) therefore gives every layer its
+own threshold, the median of its initial goodness (taken from one untimed step of the library itself), so
+that both passes carry live int8 gradients; the theta = 2.0 figures are reported beside it as
+`theta_paper`.  `operand_zero_fraction` lists the share of zero codes in every contraction operand.
+
+`cpu_baseline` times the CPU oracle on the same workload (or a bounded sample of it).
 """
 from __future__ import annotations
 
@@ -30,29 +40,47 @@ INT8_MFMA_PEAK_TOPS = 256 * 2.4e9 * 8192 / 1e12   # 256 CUs x 2.4 GHz x 8192 int
 HBM_PEAK_GBS = 8000.0
 
 
-def setup(ff, torch, wl, lookahead="coeff"):
+def setup(ff, torch, wl, lookahead="coeff", theta_layer=None, state=None):
+    """Device state of one workload.  `state` (from an earlier call) re-uses weights, inputs and workspace under a
+    new descriptor, e.g. one with per-layer thresholds."""
     from workloads import make_inputs, make_weights
-    W = make_weights(wl)
-    xp, xn = make_inputs(wl)
     B, k = wl.batch, len(wl.layers)
-    d_w = [torch.from_numpy(w.reshape(w.shape[0], -1)).cuda() for w in W]
-    d_wq = [torch.zeros((l.N, ff.ff_pitch(l.K)), dtype=torch.int8, device="cuda") for l in wl.layers]
-    d_sw = [torch.zeros(1, device="cuda") for _ in wl.layers]
-    ws1 = torch.empty(ff.WS_MIN_BYTES, dtype=torch.uint8, device="cuda")
-    for i, l in enumerate(wl.layers):
-        ff.ff_quantize(d_w[i], l.N, l.K, ff.ROUND_NEAREST, 0, 0, d_wq[i], None, d_sw[i], ws1)
-    net = ff.Net(wl.layers, B, d_w, d_wq, d_sw, lookahead=lookahead)
+    if state is None:
+        W = make_weights(wl)
+        xp, xn = make_inputs(wl)
+        d_w = [torch.from_numpy(w.reshape(w.shape[0], -1)).cuda() for w in W]
+        d_wq = [torch.zeros((l.N, ff.ff_pitch(l.K)), dtype=torch.int8, device="cuda") for l in wl.layers]
+        d_sw = [torch.zeros(1, device="cuda") for _ in wl.layers]
+        ws1 = torch.empty(ff.WS_MIN_BYTES, dtype=torch.uint8, device="cuda")
+        for i, l in enumerate(wl.layers):
+            ff.ff_quantize(d_w[i], l.N, l.K, ff.ROUND_NEAREST, 0, 0, d_wq[i], None, d_sw[i], ws1)
+        d_xp = torch.from_numpy(xp.reshape(B, -1)).cuda()
+        d_xn = torch.from_numpy(xn.reshape(B, -1)).cuda()
+        loss = torch.empty((k, 2), device="cuda")
+        good = torch.empty((k, 2, B), device="cuda")
+        ws = None
+    else:
+        _, d_xp, d_xn, loss, good, ws, d_w, d_wq, d_sw = state
+    net = ff.Net(wl.layers, B, d_w, d_wq, d_sw, lookahead=lookahead, theta_layer=theta_layer)
     if net.workspace_bytes() == 0:
         raise SystemExit(f"bench.py: workload {wl.name} is not covered by --lookahead {lookahead}")
-    ws = torch.empty(net.workspace_bytes(), dtype=torch.uint8, device="cuda")
-    loss = torch.empty((k, 2), device="cuda")
-    good = torch.empty((k, 2, B), device="cuda")
-    d_xp = torch.from_numpy(xp.reshape(B, -1)).cuda()
-    d_xn = torch.from_numpy(xn.reshape(B, -1)).cuda()
-    return net, d_xp, d_xn, loss, good, ws
+    if ws is None:
+        ws = torch.empty(net.workspace_bytes(), dtype=torch.uint8, device="cuda")
+    return net, d_xp, d_xn, loss, good, ws, d_w, d_wq, d_sw
 
 
-def cpu_baseline(wl, sample_batch: int, lookahead: str = "coeff"):
+def matched_thetas(ff, torch, wl, st):
+    """One threshold per layer: the median goodness of the layer over both data sets at the initial weights, from
+    one untimed step of the library with lr = 0 (the weights are left as they are)."""
+    net, d_xp, d_xn, loss, good, ws = st[:6]
+    ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, 0.0, wl.sr_seed, 0, loss, good, ws)
+    torch.cuda.synchronize()
+    k = len(wl.layers)
+    med = good.reshape(k, -1).median(dim=1).values.cpu().tolist()
+    return [float(m) if l.role != "proj" else 0.0 for m, l in zip(med, wl.layers)]
+
+
+def cpu_baseline(wl, sample_batch: int, lookahead: str = "coeff", theta=None):
     """The CPU oracle as it stands, timed on this host, on a smaller batch of the same network."""
     from oracle import ff_oracle as O
     from workloads import make_inputs, make_weights, scaled
@@ -62,7 +90,7 @@ def cpu_baseline(wl, sample_batch: int, lookahead: str = "coeff"):
     O.lib()
     t0 = time.perf_counter()
     step = O.train_step if lookahead == "coeff" else O.train_step_chain
-    step(small.layers, W, xp, xn, small.theta, small.lam, small.lr, small.sr_seed, 0, keep=False)
+    step(small.layers, W, xp, xn, small.theta if theta is None else theta, small.lam, small.lr, small.sr_seed, 0, keep=False)
     dt = time.perf_counter() - t0
     try:
         cores = len(os.sched_getaffinity(0))
@@ -104,23 +132,144 @@ def gemm_data_probe(ff, torch, wl, iters: int = 20):
 
     res = {}
     gi = ff.KERNEL_CLASSES.index("gemm_fwd")
+    clk = torch.zeros(16, dtype=torch.int64, device="cuda")
     for kind in ("gaussian", "constant", "zeros"):
         a_q, w_q = codes(a_shape[0], a_shape[1], kind), codes(l.N, l.K, kind)
         for _ in range(3):
             ff.ff_layer_forward(desc, a_q, w_q, acc, gsum, vmax, ws)
         torch.cuda.synchronize()
+        clk.zero_()
+        ff.ff_timing_clock_probe(clk)
         ff.ff_timing_reset()
         ff.ff_timing_enable(True)
         for _ in range(iters):
             ff.ff_layer_forward(desc, a_q, w_q, acc, gsum, vmax, ws)
         torch.cuda.synchronize()
         ff.ff_timing_enable(False)
+        ff.ff_timing_clock_probe(None)
         ms, n = ff.ff_timing_read(gi)
         ops = 2.0 * M * l.K * l.N
+        c = clk.cpu().tolist()
         res[kind] = {"avg_launch_ms": ms / n, "TOPs": ops / (ms / n * 1e-3) / 1e12,
-                     "frac_of_peak": ops / (ms / n * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS}
+                     "frac_of_peak": ops / (ms / n * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS,
+                     "mean_shader_clock_GHz": c[0] / max(c[1], 1) * 0.1}
     return {"probe": "forward contraction vs operand values", "workload": wl.name, "M": M, "K": l.K, "N": l.N,
             "launches": iters, "results": res}
+
+
+def operand_zero_fractions(ff, torch, wl, theta_layer, theta):
+    """Share of zero int8 codes in every operand of the two contractions, per layer and pass, for a dense stack at
+    its initial weights: the step taken apart into the single-operation entry points (quantise / hand-off, forward,
+    goodness and loss, look-ahead, local gradient)."""
+    if any(l.kind != "dense" for l in wl.layers):
+        return None
+    from workloads import make_inputs, make_weights
+    B, k = wl.batch, len(wl.layers)
+    W = make_weights(wl)
+    xs = make_inputs(wl)
+    ws = torch.empty(max([ff.WS_MIN_BYTES] + [ff.ff_layer_workspace_bytes(ff.layer_desc(l, B)) for l in wl.layers]),
+                     dtype=torch.uint8, device="cuda")
+    f32 = lambda: torch.zeros(1, device="cuda")
+    d_w = [torch.from_numpy(w).cuda() for w in W]
+    w_q = [torch.zeros((l.N, ff.ff_pitch(l.K)), dtype=torch.int8, device="cuda") for l in wl.layers]
+    s_w = [f32() for _ in wl.layers]
+    out = {"weights": [], "pos": [], "neg": []}
+    for i, l in enumerate(wl.layers):
+        ff.ff_quantize(d_w[i], l.N, l.K, ff.ROUND_NEAREST, 0, 0, w_q[i], None, s_w[i], ws)
+        out["weights"].append(round(float((w_q[i][:, :l.K] == 0).float().mean()), 4))
+    for p, name in enumerate(("pos", "neg")):
+        x = torch.from_numpy(xs[p]).cuda()
+        coeff = torch.zeros((k, B), device="cuda")
+        keep = []
+        a_q = a_qt = s_a = None
+        for i, l in enumerate(wl.layers):
+            desc = ff.layer_desc(l, B)
+            nq, nqt, ns = (torch.zeros((B, ff.ff_pitch(l.K)), dtype=torch.int8, device="cuda"),
+                           torch.zeros((l.K, ff.ff_pitch(B)), dtype=torch.int8, device="cuda"), f32())
+            tag = ff.ff_stream_tag(0, i, p, ff.KIND_ACT)
+            if i == 0:
+                ff.ff_quantize(x, B, l.K, ff.ROUND_STOCHASTIC, wl.sr_seed, tag, nq, nqt, ns, ws)
+            else:
+                pd, pacc, psa, pG, pamax = keep[-1][0], keep[-1][1], keep[-1][2], keep[-1][5], keep[-1][6]
+                ff.ff_layer_handoff(pd, pacc, psa, s_w[i - 1], pG, pamax, ff.ROUND_STOCHASTIC, wl.sr_seed, tag, nq, nqt, ns)
+            a_q, a_qt, s_a = nq, nqt, ns
+            acc = torch.empty((B, ff.ff_pitch32(l.N)), dtype=torch.int32, device="cuda")
+            gsum = torch.zeros(B, dtype=torch.int64, device="cuda")
+            vmax = torch.zeros(B, dtype=torch.int32, device="cuda")
+            ff.ff_layer_forward(desc, a_q, w_q[i], acc, gsum, vmax, ws)
+            G, lm, amax = torch.empty(B, device="cuda"), f32(), f32()
+            th = theta if theta_layer is None else theta_layer[i]
+            ff.ff_goodness_loss(desc, gsum, vmax, s_a, s_w[i], ff.PASS_POS if p == 0 else ff.PASS_NEG, th, G, coeff[i], lm, amax)
+            keep.append((desc, acc, s_a, vmax, a_qt, G, amax, a_q))
+        ct = torch.empty_like(coeff)
+        ff.ff_lookahead(coeff, k, B, wl.lam, ct)
+        for i, l in enumerate(wl.layers):
+            desc, acc, s_a, vmax, a_qt, G, amax, a_q = keep[i]
+            gy = torch.zeros((l.N, ff.ff_pitch(B)), dtype=torch.int8, device="cuda")
+            dw = torch.empty((l.N, ff.ff_pitch32(l.K)), dtype=torch.int32, device="cuda")
+            s_g = f32()
+            ff.ff_layer_backward_local(desc, acc, vmax, s_a, s_w[i], ct[i], ff.ROUND_STOCHASTIC, wl.sr_seed,
+                                       ff.ff_stream_tag(0, i, p, ff.KIND_GRAD), a_qt, gy, s_g, dw, ws)
+            torch.cuda.synchronize()
+            out[name].append({"layer_input_codes": round(float((a_q[:, :l.K] == 0).float().mean()), 4),
+                              "local_gradient_codes": round(float((gy[:, :B] == 0).float().mean()), 4)})
+        del keep
+    return out
+
+
+def time_steps(ff, torch, wl, st, theta, steps, start, classes=("gemm_fwd", "gemm_dw")):
+    net, d_xp, d_xn, loss, good, ws = st[:6]
+    ff.ff_timing_reset()
+    ff.ff_timing_enable(True, classes)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ff.ff_train_step(net, d_xp, d_xn, theta, wl.lam, wl.lr, wl.sr_seed, start + i, loss, good, ws)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ff.ff_timing_enable(False)
+    out = {}
+    for ci, name in enumerate(ff.KERNEL_CLASSES):
+        ms, n = ff.ff_timing_read(ci)
+        out[name] = {"ms_per_step": ms / steps, "launches_per_step": n / steps}
+    return dt / steps * 1e3, out
+
+
+def contraction_ops_per_step(wl):
+    # fwd + dW, both passes, of the layers that run on the MFMA contraction kernel (depthwise layers do not)
+    return sum(2.0 * 2 * wl.batch * l.rows_per_sample * l.K * l.N * 2 for l in wl.layers if l.kind != "dwconv")
+
+
+def gemm_figures(wl, kern):
+    gemm_ms = kern["gemm_fwd"]["ms_per_step"] + kern["gemm_dw"]["ms_per_step"]
+    launches = kern["gemm_fwd"]["launches_per_step"] + kern["gemm_dw"]["launches_per_step"]
+    ops = contraction_ops_per_step(wl)
+    avg_ms = gemm_ms / max(launches, 1)
+    ach = ops / max(launches, 1) / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
+    half = lambda c: (ops / 2) / (kern[c]["ms_per_step"] * 1e-3) / 1e12 if kern[c]["ms_per_step"] > 0 else 0.0
+    return {"achieved": ach, "ops_per_launch": ops / max(launches, 1), "avg_launch_ms": avg_ms,
+            "fwd_TOPs": half("gemm_fwd"), "dw_TOPs": half("gemm_dw")}
+
+
+def other_config(ff, torch, name, steps=10, warmup=3):
+    """ms per step and the derived rates of another configuration (eager launches; matched thresholds)."""
+    from workloads import workload
+    wl = workload(name)
+    st = setup(ff, torch, wl)
+    th = matched_thetas(ff, torch, wl, st)
+    st = setup(ff, torch, wl, theta_layer=th, state=st)
+    net, d_xp, d_xn, loss, good, ws = st[:6]
+    for i in range(warmup):
+        ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, i, loss, good, ws)
+    ms, kern = time_steps(ff, torch, wl, st, wl.theta, steps, warmup)
+    k, B = len(wl.layers), wl.batch
+    ops = contraction_ops_per_step(wl)
+    g = gemm_figures(wl, kern)
+    return {"layers": k, "batch_per_pass": B, "ms_per_step": round(ms, 4),
+            "samples_per_s_per_layer_step": round(2 * B * k / (ms * 1e-3), 1),
+            "whole_step_int8_TOPs": round(ops / (ms * 1e-3) / 1e12, 1),
+            "whole_step_frac_of_int8_peak": round(ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 4),
+            "contraction_launches_frac_of_int8_peak": round(g["achieved"] / INT8_MFMA_PEAK_TOPS, 4)}
 
 
 def main() -> int:
@@ -129,8 +278,12 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg5")
+    ap.add_argument("--theta", choices=("matched", "paper"), default="matched",
+                    help="matched: one threshold per layer, the median initial goodness (both passes carry live int8 "
+                         "gradients); paper: theta = 2.0 for every layer (Section V-A)")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the cfg1-cfg4 step times")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB-read / 1 GiB-write elementwise kernel (torch.add) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against known traffic")
@@ -159,8 +312,11 @@ def main() -> int:
     if args.gemm_data_probe:
         print(json.dumps(gemm_data_probe(ff, torch, wl)))
         return 0
-    net, d_xp, d_xn, loss, good, ws = setup(ff, torch, wl, args.lookahead)
+    st_paper = setup(ff, torch, wl, args.lookahead)
     k, B = len(wl.layers), wl.batch
+    theta_layer = matched_thetas(ff, torch, wl, st_paper) if args.theta == "matched" else None
+    st = setup(ff, torch, wl, args.lookahead, theta_layer=theta_layer, state=st_paper) if theta_layer else st_paper
+    net, d_xp, d_xn, loss, good, ws = st[:6]
 
     if args.pmc_calibration:
         cal_in = torch.ones(1 << 28, device="cuda")          # 2^28 fp32 = 1 GiB
@@ -169,44 +325,36 @@ def main() -> int:
         torch.cuda.synchronize()
         del cal_in, cal_out
 
-    def run_steps(n, start):
-        for i in range(n):
-            ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, start + i, loss, good, ws)
-        return start + n
-
-    def read_classes(steps):
-        out = {}
-        for ci, name in enumerate(ff.KERNEL_CLASSES):
-            ms, n = ff.ff_timing_read(ci)
-            out[name] = {"ms_per_step": ms / steps, "launches_per_step": n / steps}
-        return out
-
-    step_no = run_steps(args.warmup, 0)
+    step_no = 0
+    for i in range(args.warmup):
+        ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, step_no, loss, good, ws)
+        step_no += 1
     torch.cuda.synchronize()
     # ---- the timed region: K steps; HIP events bracket only the launches of the dominant kernel (the two
     # contractions), because an event record after every one of the ~30 launches of a step would itself
     # lengthen the step by 5-10 % (it keeps consecutive launches from overlapping)
-    ff.ff_timing_reset()
-    ff.ff_timing_enable(True, ("gemm_fwd", "gemm_dw"))
-    t0 = time.perf_counter()
-    step_no = run_steps(args.steps, step_no)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ff.ff_timing_enable(False)
-    ms_per_step = dt / args.steps * 1e3
+    ms_per_step, kern = time_steps(ff, torch, wl, st, wl.theta, args.steps, step_no)
+    step_no += args.steps
     samples = 2 * B
-    kern = read_classes(args.steps)
 
-    # ---- outside the timed region: the same K steps with every kernel class timed (the per-class breakdown),
-    # and as K replays of one captured HIP graph (ff_train_step_at keeps the step number in device memory)
-    ff.ff_timing_reset()
-    ff.ff_timing_enable(True)
-    t0 = time.perf_counter()
-    step_no = run_steps(args.steps, step_no)
-    torch.cuda.synchronize()
-    extra = {"all_classes_timed_ms_per_step": (time.perf_counter() - t0) / args.steps * 1e3}
-    ff.ff_timing_enable(False)
-    breakdown = read_classes(args.steps)
+    # ---- outside the timed region: the same K steps with every kernel class timed (the per-class breakdown) and the
+    # shader-clock probe of the contraction launches switched on; then K replays of one captured HIP graph
+    # (ff_train_step_at keeps the step number in device memory)
+    clk = torch.zeros(16, dtype=torch.int64, device="cuda")
+    ff.ff_timing_clock_probe(clk)
+    all_ms, breakdown = time_steps(ff, torch, wl, st, wl.theta, args.steps, step_no, None)
+    ff.ff_timing_clock_probe(None)
+    step_no += args.steps
+    clk_v = clk.cpu().tolist()
+    mean_clock_ghz = clk_v[0] / max(clk_v[1], 1) * 0.1
+
+    def phases(o):   # shader clocks per tile by phase, as seen by the first thread of each workgroup
+        n = max(clk_v[o + 4], 1)
+        return {"tiles": clk_v[o + 4], "operand_round_trip": round(clk_v[o] / n), "main_loop": round(clk_v[o + 1] / n),
+                "epilogue": round(clk_v[o + 2] / n), "wait_for_other_waves": round(clk_v[o + 3] / n)}
+    phase_clocks = {"forward": phases(8), "weight_gradient": phases(2),
+                    "note": "shader clocks per 256x256 tile; the MFMA pipe needs 2048 clocks per 128-byte reduction step"}
+    extra = {"all_classes_timed_ms_per_step": all_ms}
     if not args.no_graph:
         step_dev = torch.tensor([step_no], dtype=torch.int64, device="cuda")
         graph = torch.cuda.CUDAGraph()
@@ -220,32 +368,48 @@ def main() -> int:
             graph.replay()
         torch.cuda.synchronize()
         g_ms = (time.perf_counter() - t0) / args.steps * 1e3
+        step_no += args.steps + 3
         extra["graph_replay_ms_per_step"] = g_ms
         extra["graph_replay_samples_per_s_per_layer_step"] = 2 * B * k / (g_ms * 1e-3)
 
     # dominant kernel: the int8 contraction (forward + weight-gradient launches; each launch covers both passes)
-    gemm_ms = kern["gemm_fwd"]["ms_per_step"] + kern["gemm_dw"]["ms_per_step"]
-    gemm_launches = kern["gemm_fwd"]["launches_per_step"] + kern["gemm_dw"]["launches_per_step"]
-    # fwd + dW, both passes, of the layers that run on the MFMA contraction kernel (depthwise layers do not)
-    ops_per_step = sum(2.0 * 2 * B * l.rows_per_sample * l.K * l.N * 2 for l in wl.layers if l.kind != "dwconv")
-    ops_per_launch = ops_per_step / max(gemm_launches, 1)
-    avg_launch_ms = gemm_ms / max(gemm_launches, 1)
-    achieved = ops_per_launch / (avg_launch_ms * 1e-3) / 1e12 if avg_launch_ms > 0 else 0.0
-    traffic = None
+    g = gemm_figures(wl, kern)
+    ops_per_step = contraction_ops_per_step(wl)
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{wl.name}.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("gemm_bytes_per_launch")
+            tj = json.load(open(tpath))
+            traffic = tj.get("gemm_bytes_per_launch")
+            traffic_source = ("not measured in this run: recorded rocprofv3 FETCH_SIZE / WRITE_SIZE figure read from "
+                              f"profiles/traffic_{wl.name}.json ({tj.get('source', '')})")
         except Exception:
             traffic = None
+    peak_at_clock = 256 * mean_clock_ghz * 1e9 * 8192 / 1e12
     roofline = {"bound": "mfma", "kernel": "k_gemm_nt_i8 (forward and weight-gradient launches)",
-                "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": traffic,
-                "ops_per_launch": ops_per_launch, "avg_launch_ms": avg_launch_ms,
-                "fwd_TOPs": (ops_per_step / 2) / (kern["gemm_fwd"]["ms_per_step"] * 1e-3) / 1e12
-                if kern["gemm_fwd"]["ms_per_step"] > 0 else 0.0,
-                "dw_TOPs": (ops_per_step / 2) / (kern["gemm_dw"]["ms_per_step"] * 1e-3) / 1e12
-                if kern["gemm_dw"]["ms_per_step"] > 0 else 0.0}
+                "achieved": g["achieved"], "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                "frac": g["achieved"] / INT8_MFMA_PEAK_TOPS, "traffic": traffic, "traffic_source": traffic_source,
+                "ops_per_launch": g["ops_per_launch"], "avg_launch_ms": g["avg_launch_ms"],
+                "fwd_TOPs": g["fwd_TOPs"], "dw_TOPs": g["dw_TOPs"],
+                "fwd_frac": g["fwd_TOPs"] / INT8_MFMA_PEAK_TOPS, "dw_frac": g["dw_TOPs"] / INT8_MFMA_PEAK_TOPS,
+                "mean_shader_clock_GHz": round(mean_clock_ghz, 4),
+                "peak_measured_clock": round(peak_at_clock, 1),
+                "frac_of_peak_measured_clock": round(g["achieved"] / peak_at_clock, 4) if peak_at_clock > 0 else None,
+                "phase_clocks_per_tile": phase_clocks,
+                "clock_note": "mean shader clock of the contraction launches, read inside the kernels (shader-clock "
+                              "cycles over constant-100-MHz ticks) during the fully instrumented pass; "
+                              "peak_measured_clock = 256 CU x 8192 op/clk x that clock"}
+
+    # theta = 2.0 (Section V-A) beside the matched thresholds: the positive-pass gradient operand is then all zeros
+    theta_paper = None
+    if theta_layer is not None:
+        p_ms, p_kern = time_steps(ff, torch, wl, st_paper, wl.theta, max(5, args.steps // 2), step_no)
+        step_no += max(5, args.steps // 2)
+        pg = gemm_figures(wl, p_kern)
+        theta_paper = {"theta": wl.theta, "ms_per_step": p_ms, "contraction_frac": pg["achieved"] / INT8_MFMA_PEAK_TOPS,
+                       "fwd_TOPs": pg["fwd_TOPs"], "dw_TOPs": pg["dw_TOPs"],
+                       "note": "positive-pass local gradient is all zeros at this threshold (see operand_zero_fraction "
+                               "for the matched run); not the headline"}
 
     # HBM-bound kernel classes (dense stacks): algorithmic bytes per step / time of the fully instrumented pass
     hbm = None
@@ -272,20 +436,40 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8 (int32 accumulate; fp32 scales, goodness, master weights)", "data": "synthetic",
         "config": {"workload": wl.name, "layers": [f"{l.K}->{l.N}" for l in wl.layers],
-                   "batch_pos": B, "batch_neg": B, "lookahead": args.lookahead, "lambda": wl.lam, "theta": wl.theta, "lr": wl.lr,
+                   "batch_pos": B, "batch_neg": B, "lookahead": args.lookahead, "lambda": wl.lam,
+                   "theta": ("per layer, median initial goodness (both passes live): " + str([round(t, 1) for t in theta_layer]))
+                   if theta_layer is not None else wl.theta,
+                   "lr": wl.lr,
                    "layer_steps_per_step": k, "whole_step_samples_per_s": samples / (ms_per_step * 1e-3),
-                   "int8_TOPs_whole_step": ops_per_step / (ms_per_step * 1e-3) / 1e12},
-        "int8_mfma_pct_of_peak": 100.0 * achieved / INT8_MFMA_PEAK_TOPS,
+                   "int8_TOPs_whole_step": ops_per_step / (ms_per_step * 1e-3) / 1e12,
+                   "whole_step_frac_of_int8_peak": ops_per_step / (ms_per_step * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS},
+        "int8_mfma_pct_of_peak": 100.0 * g["achieved"] / INT8_MFMA_PEAK_TOPS,
         "roofline": roofline,
+        "theta_paper": theta_paper,
         "kernels_ms_per_step": {n: round(v["ms_per_step"], 5) for n, v in breakdown.items()},
         "hbm_bound_kernels": hbm,
         "other_launch_modes": extra,
         "paper_context": "Jetson Orin Nano, whole training runs: 4.6% faster, 8.3% less energy, 27.0% less memory "
                          "than BP-GDAI8 (Table V); no per-step figure is published",
     }
+    # free the main workload before the side measurements
+    del net, d_xp, d_xn, loss, good, ws, st, st_paper
+    torch.cuda.empty_cache()
+    try:
+        out["operand_zero_fraction"] = operand_zero_fractions(ff, torch, wl, theta_layer, wl.theta)
+    except ff.FFError as e:   # a side measurement never takes the headline down
+        out["operand_zero_fraction"] = {"error": str(e)}
+    torch.cuda.empty_cache()
+    if not args.no_other_configs and wl.name == "cfg5":
+        oc = {}
+        for name in ("cfg1", "cfg2", "cfg3", "cfg4"):
+            oc[name] = other_config(ff, torch, name)
+            torch.cuda.empty_cache()
+        oc["note"] = "eager launches, 10 steps after 3 warm-up steps, thresholds matched per layer; outside the timed region"
+        out["other_configs"] = oc
     if not args.no_cpu_baseline:
         sb = args.cpu_sample_batch or {"cfg5": 8192, "cfg2": 1024, "cfg1": 64, "cfg3": 64, "cfg4_plain": 32}.get(wl.name, min(B, 256))
-        out["cpu_baseline"] = cpu_baseline(wl, min(sb, B), args.lookahead)
+        out["cpu_baseline"] = cpu_baseline(wl, min(sb, B), args.lookahead, theta_layer)
     print(json.dumps(out))
     return 0
 

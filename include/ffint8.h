@@ -365,6 +365,15 @@ enum {
 };
 #define FF_TIMING_MAX_RECORDS 16384
 ff_status ff_timing_enable(int32_t class_mask);
+/* Clock probe of the contraction launches: while `counters` (16 uint64 in DEVICE memory, zeroed by the caller,
+ * 8-byte aligned) is set, every workgroup of the forward and weight-gradient contraction kernels adds
+ *   [0] the shader-clock cycles it was alive, [1] the ticks of the constant 100 MHz clock over the same interval
+ *       ([0] / [1] * 100 MHz = the clock the launches actually ran at under the power manager),
+ *   per tile, as seen by the workgroup's first thread, for weight-gradient launches in [2..6] and for forward
+ *   launches in [8..12]: shader clocks from the start of the tile to its first fragments (operand round trip),
+ *   of the main loop, of the epilogue, of the wait for the other wavefronts' epilogues, and the tile count.
+ * NULL switches it off (the default).  The buffer must stay allocated while set. */
+ff_status ff_timing_clock_probe(uint64_t* counters);
 ff_status ff_timing_reset(void);
 ff_status ff_timing_read(int32_t kernel_class, double* total_ms, int64_t* launches);
 

@@ -93,6 +93,8 @@ def lib() -> C.CDLL:
         L.ff_workspace_bytes.argtypes = [C.POINTER(NetDesc)]
         L.ff_timing_enable.restype = i32
         L.ff_timing_enable.argtypes = [i32]
+        L.ff_timing_clock_probe.restype = i32
+        L.ff_timing_clock_probe.argtypes = [P]
         L.ff_timing_reset.restype = i32
         L.ff_timing_read.restype = i32
         L.ff_timing_read.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -263,6 +265,11 @@ def ff_timing_enable(on, classes: Optional[Sequence[str]] = None) -> None:
     if on:
         mask = -1 if classes is None else sum(1 << KERNEL_CLASSES.index(c) for c in classes)
     _chk(lib().ff_timing_enable(mask), "ff_timing_enable")
+
+
+def ff_timing_clock_probe(counters: Optional[torch.Tensor]) -> None:
+    """counters: a zeroed int64 CUDA tensor of 16 elements (kept alive by the caller), or None to switch off."""
+    _chk(lib().ff_timing_clock_probe(_ptr(counters)), "ff_timing_clock_probe")
 
 
 def ff_timing_reset() -> None:

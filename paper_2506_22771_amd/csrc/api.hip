@@ -340,6 +340,7 @@ struct TimingState {
     int created = 0;
 };
 static TimingState g_timing;
+static unsigned long long* g_clock_probe = nullptr;   // device counters of ff_timing_clock_probe (null: off)
 
 struct Timed {
     hipStream_t s;
@@ -446,6 +447,7 @@ static ff_status run_forward(const Dims& d, int relu, const int8_t* aq, int64_t 
         g.st_p = st_col;
         g.ldp = pitch8(d.K);
     }
+    g.clk = g_clock_probe;
     HIPCHK_T(FF_K_GEMM_FWD, launch_gemm_nt_i8(g, s));
     return FF_OK;
 }
@@ -546,6 +548,7 @@ static ff_status run_wgrad(const Dims& d, const int8_t* gy_t, int64_t st_gy, con
             }
         }
         g.splits = gemm_plan(g.I, g.J, g.R, nb, true).splits;
+        g.clk = g_clock_probe;
         if (g.splits > 1) {
             int32_t* out = g.C;
             g.C = part;
@@ -1462,6 +1465,13 @@ ff_status ff_train_step_at(const ff_net_desc* net, const ff_net_state* state, co
 ff_status ff_timing_enable(int32_t class_mask)
 {
     g_timing.mask = (uint32_t)class_mask & ((1u << FF_K_COUNT) - 1u);
+    return FF_OK;
+}
+
+ff_status ff_timing_clock_probe(uint64_t* counters)
+{
+    if (counters && ((uintptr_t)counters & 7)) return FF_ERR_ALIGN;
+    g_clock_probe = (unsigned long long*)counters;
     return FF_OK;
 }
 

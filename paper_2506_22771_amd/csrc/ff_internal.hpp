@@ -256,6 +256,10 @@ struct GemmArgs {
     // wtaps_only; row j of the contraction is (kh, kw, ci), the reduction runs over output pixels.  W_out % 16 == 0.
     int32_t conv, H, W, Cin, cpitch, ks, stride, pad, Ho, Wo;
     int64_t p_bytes;  // bytes of one implicit operand tensor (conv only; must be < 2^31)
+    // instrumentation (null normally): every workgroup adds the shader-clock cycles and the 100 MHz constant-clock
+    // ticks it was alive to clk[0] and clk[1] (their ratio is the mean shader clock during the launch) and the
+    // shader clocks of each tile by phase to clk[2..6] / clk[8..12]
+    unsigned long long* clk;   // 16 counters, see ff_timing_clock_probe
 };
 hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s);
 struct GemmPlan {

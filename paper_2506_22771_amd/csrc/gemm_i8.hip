@@ -32,6 +32,12 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 128;  // reduction bytes per LDS stage
 
+#ifndef FF_PRO2
+#define FF_PRO2 1
+#endif
+#ifndef FF_PERSIST
+#define FF_PERSIST 1
+#endif
 #ifndef FF_STAGED_EPI
 #define FF_STAGED_EPI 1   // 1: interior tiles leave through LDS as whole rows (see the epilogue)
 #endif
@@ -87,13 +93,11 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     constexpr int LDS_BYTES = 2 * STAGE_BYTES > WM * WN * ESLICE ? 2 * STAGE_BYTES : WM * WN * ESLICE;
     __shared__ __attribute__((aligned(16))) int8_t lds[LDS_BYTES];
 
-    const int z = blockIdx.z;
-    const int8_t* __restrict__ P = a.P + z * a.st_p;
-    const int8_t* __restrict__ Q = a.Q + z * a.st_q;
-    int32_t* __restrict__ C = a.C + z * a.st_c;
-    const int tiles_i = (a.I + BM - 1) / BM;
-    const int bi = blockIdx.x % tiles_i, bj = blockIdx.x / tiles_i;
-    const int i0 = bi * BM, j0 = bj * BN;
+    unsigned long long clk0 = 0, rt0 = 0;
+    if (a.clk && threadIdx.x == 0) {
+        clk0 = clock64();
+        rt0 = wall_clock64();
+    }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
@@ -103,6 +107,21 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     const int nk_per = (nk_all + a.splits - 1) / a.splits;
     const int kt0 = MODE == 2 ? (int)blockIdx.y * nk_per : 0;
     const int nk = MODE == 2 ? min(nk_all, kt0 + nk_per) : nk_all;   // the plan leaves no split empty
+    const int tiles_i = (a.I + BM - 1) / BM;
+    const int tiles_z = tiles_i * ((a.J + BN - 1) / BN);
+    const int ntiles = tiles_z * a.nb;
+    // Tiles of all nb problems are numbered t = z * tiles_z + bj * tiles_i + bi.  A launch has either one workgroup
+    // per tile, or (persistent: large dense problems) one workgroup per compute unit that takes every gridDim.x-th
+    // tile in turn -- no workgroup start-up and drain between a compute unit's tiles.
+    for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    unsigned long long pht = 0, ph1 = 0, ph2 = 0;   // phase marks of the clock probe (thread 0 only)
+    if (a.clk && threadIdx.x == 0) pht = clock64();
+    const int z = t / tiles_z, tz = t - z * tiles_z;
+    const int bi = tz % tiles_i, bj = tz / tiles_i;
+    const int8_t* __restrict__ P = a.P + z * a.st_p;
+    const int8_t* __restrict__ Q = a.Q + z * a.st_q;
+    int32_t* __restrict__ C = a.C + z * a.st_c;
+    const int i0 = bi * BM, j0 = bj * BN;
     if (MODE == 2) C += (int64_t)blockIdx.y * a.st_split;
 
     const int rows_p = min(BM, a.I - i0), rows_q = min(BN, a.J - j0);
@@ -212,11 +231,26 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     // stage kt are issued before the barrier of step kt, so its buffer is free right after that barrier and
     // the copy of stage kt+2 is issued there: one copy is in flight at every moment, each with a whole step
     // of time to land.
+#if FF_PRO2
+    // both stages are free at the start of a tile: the copies of the first two steps go out together, so that only
+    // one round trip to memory is exposed (copies complete in issue order)
+    issue(kt0, 0);
+    if (kt0 + 1 < nk) {
+        issue(kt0 + 1, 1);
+        wait_vmcnt<CH_P + CH_Q>();
+    } else {
+        wait_vmcnt<0>();
+    }
+    __builtin_amdgcn_s_barrier();
+    ldfrag(0, lds, 0);
+#else
     issue(kt0, 0);
     wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     ldfrag(0, lds, 0);
     if (kt0 + 1 < nk) issue(kt0 + 1, 1);
+#endif
+    if (a.clk && threadIdx.x == 0) ph1 = clock64();
     for (int kt = kt0; kt < nk; ++kt) {
         const int cur = (kt - kt0) & 1;
         const int8_t* sb = lds + cur * STAGE_BYTES;
@@ -241,6 +275,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     // then reads that give every store instruction whole contiguous row segments of WTN*4 bytes.
     // Edge tiles take the same route when J is a multiple of 4 (a lane's 16 bytes then never straddle the last
     // column): rows and column groups beyond the matrix are simply not stored.
+    if (a.clk && threadIdx.x == 0) ph2 = clock64();
     const bool interior = i0 + BM <= a.I && j0 + BN <= a.J;
     const bool staged = FF_STAGED_EPI && (interior || (a.J & 3) == 0);
     const bool fast_sq = a.relu && a.rshift == 0;
@@ -336,15 +371,52 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
             }
         }
     }
+    // the staging slices of the epilogue lie in the operand stages: every wave must be done with them before the
+    // copies of the next tile land there
+    unsigned long long ph3 = 0;
+    if (a.clk && threadIdx.x == 0) ph3 = clock64();
+    if (t + (int)gridDim.x < ntiles) __builtin_amdgcn_s_barrier();
+    if (a.clk && threadIdx.x == 0) {
+        // shader clocks of this tile by phase: slots 2.. for plain / split launches, 8.. for forward launches
+        const unsigned long long ph4 = clock64();
+        unsigned long long* pc = a.clk + (MODE == 1 ? 8 : 2);
+        atomicAdd(pc + 0, ph1 - pht);   // tile start to the first fragments (operand round trip)
+        atomicAdd(pc + 1, ph2 - ph1);   // main loop
+        atomicAdd(pc + 2, ph3 - ph2);   // epilogue of wave 0
+        atomicAdd(pc + 3, ph4 - ph3);   // waiting for the other waves' epilogues
+        atomicAdd(pc + 4, 1ull);        // tiles
+    }
+    }   // tile loop
+    if (a.clk && threadIdx.x == 0) {
+        atomicAdd(a.clk + 0, (unsigned long long)clock64() - clk0);
+        atomicAdd(a.clk + 1, (unsigned long long)wall_clock64() - rt0);
+    }
 }
 
+
+static int num_cus()
+{
+    static int n = 0;   // (one GPU model per process: the count of the first device queried is kept)
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) n = v;
+        else n = 256;
+    }
+    return n;
+}
 
 template <int BM, int BN, int WM, int WN>
 static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s)
 {
     const int tiles_i = (a.I + BM - 1) / BM, tiles_j = (a.J + BN - 1) / BN;
-    const dim3 grid((unsigned)(tiles_i * tiles_j), (unsigned)a.splits, (unsigned)a.nb), block(WM * WN * 64);
+    const int64_t ntiles = (int64_t)tiles_i * tiles_j * a.nb;
+    if (ntiles > 0x7FFFFFFF) return hipErrorInvalidValue;
     const int mode = a.splits > 1 ? 2 : (a.gsum ? 1 : 0);
+    // persistent launch: one workgroup per compute unit when every compute unit has at least two whole tiles
+    int64_t gx = ntiles;
+    if (FF_PERSIST && BM == 256 && BN == 256 && a.conv == 0 && mode != 2 && ntiles >= 2 * num_cus() && ntiles % num_cus() == 0)
+        gx = num_cus();
+    const dim3 grid((unsigned)gx, (unsigned)a.splits, 1), block(WM * WN * 64);
     if (a.conv == 1) {
         if (mode == 1) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 1, 1>), grid, block, 0, s, a);
         else if (mode == 0) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 0, 1>), grid, block, 0, s, a);

@@ -269,6 +269,28 @@ ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc
                                   void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * ff_layer_backward_local_noalloc — ff_layer_backward_local for callers that cannot allocate device
+ * memory or pass a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, outputs and errors, without ws / ws_bytes: the scratch (absmax slot, patch
+ * matrix of a convolution, partial sums of a split reduction) is a fixed array of
+ * FF_NOALLOC_SCRATCH_BYTES inside the library's device image, one copy per GPU, held until the process
+ * ends.  The call allocates and frees nothing and creates no HIP objects.
+ *   - A layer that needs more scratch than that (ff_layer_workspace_bytes(layer) >
+ *     FF_NOALLOC_SCRATCH_BYTES) is refused with FF_ERR_WORKSPACE before anything is launched.
+ *   - Every call on a GPU uses that GPU's one array, which keeps the previous call's contents; nothing
+ *     in it needs to start at zero.  Calls that overlap on one GPU (different streams, different
+ *     threads) race on it: serialise them.
+ * ff_noalloc_scratch_bytes() returns FF_NOALLOC_SCRATCH_BYTES. [host only]
+ * ------------------------------------------------------------------------------------------- */
+#define FF_NOALLOC_SCRATCH_BYTES (16u << 20)
+size_t ff_noalloc_scratch_bytes(void);
+ff_status ff_layer_backward_local_noalloc(const ff_layer_desc* layer, const int32_t* acc,
+                                          const int32_t* vmax, const float* s_a, const float* s_w,
+                                          const float* coeff_total, int32_t round_mode, uint64_t seed,
+                                          uint64_t stream_tag, const int8_t* a_q_t, int8_t* gy_q_t,
+                                          float* s_g, int32_t* dw_acc, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * ff_chain_gradients, ff_layer_input_grad — the two operations FF_LOOKAHEAD_CHAIN adds (Eq. (4) as an exact
  * derivative; dense layers).
  * ff_chain_gradients, one layer and pass:  y = act(s_a s_w acc);  E = (s_h s_w_up) e_acc, or 0 if e_acc == NULL

@@ -77,6 +77,9 @@ def lib() -> C.CDLL:
         L.ff_lookahead.argtypes = [P, i32, i64, f32, P, P]
         L.ff_layer_backward_local.restype = i32
         L.ff_layer_backward_local.argtypes = [LD, P, P, P, P, P, i32, u64, u64, P, P, P, P, P, sz, P]
+        L.ff_layer_backward_local_noalloc.restype = i32
+        L.ff_layer_backward_local_noalloc.argtypes = [LD, P, P, P, P, P, i32, u64, u64, P, P, P, P, P]
+        L.ff_noalloc_scratch_bytes.restype = sz
         L.ff_chain_gradients.restype = i32
         L.ff_chain_gradients.argtypes = [LD, P, P, P, P, P, P, P, f32, P, P, P, P, P]
         L.ff_layer_input_grad.restype = i32
@@ -193,6 +196,18 @@ def ff_layer_backward_local(desc, acc, vmax, s_a, s_w, coeff_total, round_mode, 
                                        round_mode, seed, stream_tag, _ptr(a_q_t), _ptr(gy_q_t), _ptr(s_g), _ptr(dw_acc),
                                        _ptr(ws), ws.numel() * ws.element_size() if ws is not None else 0, _stream()),
          "ff_layer_backward_local")
+
+
+def ff_layer_backward_local_noalloc(desc, acc, vmax, s_a, s_w, coeff_total, round_mode, seed, stream_tag, a_q_t,
+                                    gy_q_t, s_g, dw_acc) -> None:
+    _chk(lib().ff_layer_backward_local_noalloc(C.byref(desc), _ptr(acc), _ptr(vmax), _ptr(s_a), _ptr(s_w),
+                                               _ptr(coeff_total), round_mode, seed, stream_tag, _ptr(a_q_t),
+                                               _ptr(gy_q_t), _ptr(s_g), _ptr(dw_acc), _stream()),
+         "ff_layer_backward_local_noalloc")
+
+
+def ff_noalloc_scratch_bytes() -> int:
+    return int(lib().ff_noalloc_scratch_bytes())
 
 
 def ff_chain_gradients(desc, acc, s_a, s_w, coeff, e_acc, s_h, s_w_up, lam, h, g, h_amax, g_amax) -> None:

@@ -2,6 +2,8 @@
 // caller's stream.  Nothing here allocates device memory or synchronises.
 #include <string.h>
 
+#include <mutex>
+
 #include "ff_internal.hpp"
 
 namespace ffi {
@@ -822,6 +824,51 @@ ff_status ff_layer_backward_local(const ff_layer_desc* layer, const int32_t* acc
     const int64_t dw_elems = d.N * pitch32(d.K);
     int8_t* colT = (int8_t*)ws + FF_WS_MIN_BYTES;
     return run_wgrad(d, gy_q_t, 0, a_q_t, 0, colT, 0, (int32_t*)(colT + layer_col_bytes(d)), 0, dw_acc, 0, dw_elems, 1, s);
+}
+
+// ---- the entry point that allocates nothing: its scratch is a fixed array in the library's own device image ----
+// Each GPU holds its own copy of the array at its own address; in host code the array's name is only a handle for
+// hipGetSymbolAddress, never a device address.  The address is looked up once per device (with that device current)
+// and kept; launches and kernels only ever see that pointer.
+static __device__ __align__(256) unsigned char scratch[FF_NOALLOC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void* g_scratch_ptr[MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+static ff_status scratch_of_current_device(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return FF_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return FF_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return FF_OK;
+}
+
+size_t ff_noalloc_scratch_bytes(void) { return FF_NOALLOC_SCRATCH_BYTES; }
+
+ff_status ff_layer_backward_local_noalloc(const ff_layer_desc* layer, const int32_t* acc, const int32_t* vmax,
+                                          const float* s_a, const float* s_w, const float* coeff_total,
+                                          int32_t round_mode, uint64_t seed, uint64_t stream_tag, const int8_t* a_q_t,
+                                          int8_t* gy_q_t, float* s_g, int32_t* dw_acc, void* stream)
+{
+    Dims d;
+    const ff_status st = layer_dims(layer, &d);
+    if (st != FF_OK) return st;
+    // the layer's patch matrix and split partial sums must fit the fixed array
+    if (FF_WS_MIN_BYTES + layer_scratch_bytes(d) > FF_NOALLOC_SCRATCH_BYTES) return FF_ERR_WORKSPACE;
+    void* ws = nullptr;
+    const ff_status ss = scratch_of_current_device(&ws);
+    if (ss != FF_OK) return ss;
+    // Nothing in the array has to start at zero: the absmax slot is stored (not accumulated into), the patch matrix
+    // is written whole (pad bytes included) before the contraction reads it, and every split stores its own partial
+    // sums before they are added up.
+    return ff_layer_backward_local(layer, acc, vmax, s_a, s_w, coeff_total, round_mode, seed, stream_tag, a_q_t,
+                                   gy_q_t, s_g, dw_acc, ws, FF_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 ff_status ff_chain_gradients(const ff_layer_desc* layer, const int32_t* acc, const float* s_a, const float* s_w,

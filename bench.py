@@ -40,7 +40,7 @@ INT8_MFMA_PEAK_TOPS = 256 * 2.4e9 * 8192 / 1e12   # 256 CUs x 2.4 GHz x 8192 int
 HBM_PEAK_GBS = 8000.0
 
 
-def setup(ff, torch, wl, lookahead="coeff", theta_layer=None, state=None):
+def setup(ff, torch, wl, lookahead="coeff", theta_layer=None, state=None, launch_mode="auto"):
     """Device state of one workload.  `state` (from an earlier call) re-uses weights, inputs and workspace under a
     new descriptor, e.g. one with per-layer thresholds."""
     from workloads import make_inputs, make_weights
@@ -61,10 +61,10 @@ def setup(ff, torch, wl, lookahead="coeff", theta_layer=None, state=None):
         ws = None
     else:
         _, d_xp, d_xn, loss, good, ws, d_w, d_wq, d_sw = state
-    net = ff.Net(wl.layers, B, d_w, d_wq, d_sw, lookahead=lookahead, theta_layer=theta_layer)
+    net = ff.Net(wl.layers, B, d_w, d_wq, d_sw, lookahead=lookahead, theta_layer=theta_layer, launch_mode=launch_mode)
     if net.workspace_bytes() == 0:
-        raise SystemExit(f"bench.py: workload {wl.name} is not covered by --lookahead {lookahead}")
-    if ws is None:
+        raise SystemExit(f"bench.py: workload {wl.name} is not covered by --lookahead {lookahead} --launch-mode {launch_mode}")
+    if ws is None or ws.numel() < net.workspace_bytes():
         ws = torch.empty(net.workspace_bytes(), dtype=torch.uint8, device="cuda")
     return net, d_xp, d_xn, loss, good, ws, d_w, d_wq, d_sw
 
@@ -261,15 +261,43 @@ def other_config(ff, torch, name, steps=10, warmup=3):
     net, d_xp, d_xn, loss, good, ws = st[:6]
     for i in range(warmup):
         ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, i, loss, good, ws)
-    ms, kern = time_steps(ff, torch, wl, st, wl.theta, steps, warmup)
+    ms, kern = time_steps(ff, torch, wl, st, wl.theta, steps, warmup, ("gemm_fwd", "gemm_dw", "fused"))
     k, B = len(wl.layers), wl.batch
     ops = contraction_ops_per_step(wl)
     g = gemm_figures(wl, kern)
-    return {"layers": k, "batch_per_pass": B, "ms_per_step": round(ms, 4),
+    fused = kern["fused"]["launches_per_step"] > 0
+    out_extra = {}
+    if fused:
+        # the step ran as one persistent launch (FF_LAUNCH_AUTO picks it for small dense stacks): time the
+        # per-operation kernels beside it
+        st_k = setup(ff, torch, wl, theta_layer=th, state=st, launch_mode="kernels")
+        for i in range(warmup):
+            ff.ff_train_step(st_k[0], d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, i, loss, good, st_k[5])
+        ms_k, _ = time_steps(ff, torch, wl, st_k, wl.theta, steps, warmup)
+        # phase durations inside the launch (100 MHz stamps of its first workgroup), mean of 20 steps
+        stamps = torch.zeros(32, dtype=torch.int64, device="cuda")
+        ff.ff_timing_fused_stamps(stamps)
+        nph = 2 * k + 4
+        acc = None
+        for i in range(20):
+            ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, 1000 + i, loss, good, ws)
+            torch.cuda.synchronize()
+            t = stamps[:nph + 1].cpu().numpy().astype("int64")
+            d = (t[1:] - t[:-1]) * 0.01   # us
+            acc = d if acc is None else acc + d
+        ff.ff_timing_fused_stamps(None)
+        names = ["absmax_input"] + [n for i in range(k) for n in (f"quantise_{i}", f"forward_{i}")] + \
+                ["goodness_lookahead_gradquant", "wgrad_update", "requantise"]
+        phases = {n: round(float(v) / 20, 2) for n, v in zip(names, acc)}
+        out_extra = {"launch": "single persistent launch (FF_LAUNCH_FUSED via FF_LAUNCH_AUTO)",
+                     "ms_per_step_per_operation_kernels": round(ms_k, 4),
+                     "phase_us_inside_the_launch": phases,
+                     "phase_note": "each phase but the last ends in a device-wide barrier across the 8 XCDs"}
+    return {"layers": k, "batch_per_pass": B, "ms_per_step": round(ms, 4), **out_extra,
             "samples_per_s_per_layer_step": round(2 * B * k / (ms * 1e-3), 1),
             "whole_step_int8_TOPs": round(ops / (ms * 1e-3) / 1e12, 1),
             "whole_step_frac_of_int8_peak": round(ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 4),
-            "contraction_launches_frac_of_int8_peak": round(g["achieved"] / INT8_MFMA_PEAK_TOPS, 4)}
+            "contraction_launches_frac_of_int8_peak": None if fused else round(g["achieved"] / INT8_MFMA_PEAK_TOPS, 4)}
 
 
 def main() -> int:
@@ -288,6 +316,9 @@ def main() -> int:
                     help="also run one plain 1 GiB-read / 1 GiB-write elementwise kernel (torch.add) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against known traffic")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph-replay timing")
+    ap.add_argument("--launch-mode", choices=("auto", "kernels", "fused"), default="auto",
+                    help="kernels: one kernel per operation; fused: the whole step as one persistent launch (small "
+                         "dense stacks); auto: fused where it applies and the stack is small")
     ap.add_argument("--lookahead", choices=("coeff", "chain"), default="coeff",
                     help="chain: the exact-derivative variant of the look-ahead (dense stacks; one more contraction per layer)")
     ap.add_argument("--gemm-data-probe", action="store_true",
@@ -312,10 +343,11 @@ def main() -> int:
     if args.gemm_data_probe:
         print(json.dumps(gemm_data_probe(ff, torch, wl)))
         return 0
-    st_paper = setup(ff, torch, wl, args.lookahead)
+    st_paper = setup(ff, torch, wl, args.lookahead, launch_mode=args.launch_mode)
     k, B = len(wl.layers), wl.batch
     theta_layer = matched_thetas(ff, torch, wl, st_paper) if args.theta == "matched" else None
-    st = setup(ff, torch, wl, args.lookahead, theta_layer=theta_layer, state=st_paper) if theta_layer else st_paper
+    st = (setup(ff, torch, wl, args.lookahead, theta_layer=theta_layer, state=st_paper, launch_mode=args.launch_mode)
+          if theta_layer else st_paper)
     net, d_xp, d_xn, loss, good, ws = st[:6]
 
     if args.pmc_calibration:
@@ -436,7 +468,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8 (int32 accumulate; fp32 scales, goodness, master weights)", "data": "synthetic",
         "config": {"workload": wl.name, "layers": [f"{l.K}->{l.N}" for l in wl.layers],
-                   "batch_pos": B, "batch_neg": B, "lookahead": args.lookahead, "lambda": wl.lam,
+                   "batch_pos": B, "batch_neg": B, "lookahead": args.lookahead, "launch_mode": args.launch_mode, "lambda": wl.lam,
                    "theta": ("per layer, median initial goodness (both passes live): " + str([round(t, 1) for t in theta_layer]))
                    if theta_layer is not None else wl.theta,
                    "lr": wl.lr,

@@ -124,7 +124,21 @@ typedef struct {
                                     initialised weights the goodness of different layers differs by orders of
                                     magnitude; a threshold per layer keeps Eq. (1) and Eq. (2) away from saturation
                                     in all of them. */
+    int32_t launch_mode;         /* FF_LAUNCH_AUTO (0), FF_LAUNCH_KERNELS or FF_LAUNCH_FUSED, see below */
 } ff_net_desc;
+
+/* How ff_train_step issues its work.
+ * FF_LAUNCH_KERNELS: one kernel per operation (quantise, contraction, goodness/loss, ...), about nine launches per
+ *   layer.
+ * FF_LAUNCH_FUSED: the whole step as ONE persistent kernel (after the fill that clears the workspace head) whose
+ *   workgroups meet at device-wide barriers where the method has device-wide dependencies (a per-tensor absmax, a
+ *   per-sample goodness).  For the launch-bound regime of small networks and batches, the one nearest the paper's
+ *   own batch of 32 (Section V-A).  Plain dense stacks (no convolutions, residual wiring or FF_LOOKAHEAD_CHAIN) of at
+ *   most 8 layers and 1024 samples per pass; FF_ERR_UNSUPPORTED otherwise.  Same results, bit for bit.
+ * FF_LAUNCH_AUTO: FF_LAUNCH_FUSED when the stack qualifies and one pass through it is at most 2^27 multiply-adds
+ *   (784 -> 500 -> 500 at 64 samples is 41 M), else FF_LAUNCH_KERNELS.
+ * ff_workspace_bytes depends on the mode (the fused step keeps every layer's int8 local gradient). */
+enum { FF_LAUNCH_AUTO = 0, FF_LAUNCH_KERNELS = 1, FF_LAUNCH_FUSED = 2 };
 
 /* How the later layers' losses enter a layer's update (Eq. (3), Eq. (4)).
  * FF_LOOKAHEAD_COEFF: through their per-sample loss derivatives only (ff_lookahead); no gradient crosses a layer
@@ -383,7 +397,8 @@ enum {
     FF_K_RESIDUAL = 9,   /* block output and its goodness (residual layers)   */
     FF_K_DWCONV = 10,    /* depthwise convolution: forward and weight gradient */
     FF_K_CHAIN = 11,     /* FF_LOOKAHEAD_CHAIN: gradient combination, its quantisation, input-gradient contraction */
-    FF_K_COUNT = 12
+    FF_K_FUSED = 12,     /* the single-launch step of a small dense stack (FF_LAUNCH_FUSED)  */
+    FF_K_COUNT = 13
 };
 #define FF_TIMING_MAX_RECORDS 16384
 ff_status ff_timing_enable(int32_t class_mask);
@@ -396,6 +411,13 @@ ff_status ff_timing_enable(int32_t class_mask);
  *   of the main loop, of the epilogue, of the wait for the other wavefronts' epilogues, and the tile count.
  * NULL switches it off (the default).  The buffer must stay allocated while set. */
 ff_status ff_timing_clock_probe(uint64_t* counters);
+/* Phase stamps of the single-launch step (FF_LAUNCH_FUSED): while `stamps` (FF_FUSED_STAMPS uint64 in DEVICE memory,
+ * 8-byte aligned) is set, the first workgroup of every such launch stores the constant 100 MHz clock at its start
+ * ([0]), after each device-wide barrier ([1], [2], ...: 2 * n_layers + 3 barriers) and at its end: differences of
+ * consecutive entries are the durations of the phases (absmax of the input; per layer: quantise, forward contraction;
+ * last goodness + look-ahead + gradient quantise; weight gradient + update; requantise).  NULL switches it off. */
+#define FF_FUSED_STAMPS 32
+ff_status ff_timing_fused_stamps(uint64_t* stamps);
 ff_status ff_timing_reset(void);
 ff_status ff_timing_read(int32_t kernel_class, double* total_ms, int64_t* launches);
 

@@ -34,7 +34,7 @@ class LayerDesc(C.Structure):
 class NetDesc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("batch", C.c_int32), ("layers", C.POINTER(LayerDesc)),
                 ("train_layer", C.POINTER(C.c_int32)), ("lookahead", C.c_int32),
-                ("theta_layer", C.POINTER(C.c_float))]
+                ("theta_layer", C.POINTER(C.c_float)), ("launch_mode", C.c_int32)]
 
 
 class NetState(C.Structure):
@@ -98,6 +98,8 @@ def lib() -> C.CDLL:
         L.ff_timing_enable.argtypes = [i32]
         L.ff_timing_clock_probe.restype = i32
         L.ff_timing_clock_probe.argtypes = [P]
+        L.ff_timing_fused_stamps.restype = i32
+        L.ff_timing_fused_stamps.argtypes = [P]
         L.ff_timing_reset.restype = i32
         L.ff_timing_read.restype = i32
         L.ff_timing_read.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -235,7 +237,7 @@ class Net:
 
     def __init__(self, layers: Sequence, batch: int, w_master: List[torch.Tensor], w_q: List[torch.Tensor],
                  s_w: List[torch.Tensor], train_layer: Optional[Sequence[int]] = None, lookahead: str = "coeff",
-                 theta_layer: Optional[Sequence[float]] = None):
+                 theta_layer: Optional[Sequence[float]] = None, launch_mode: str = "auto"):
         self.k = len(layers)
         self.batch = batch
         self._descs = (LayerDesc * self.k)(*[layer_desc(l, batch) for l in layers])
@@ -243,7 +245,8 @@ class Net:
         self._theta = (C.c_float * self.k)(*[float(t) for t in theta_layer]) if theta_layer is not None else None
         if theta_layer is not None and len(theta_layer) != self.k:
             raise ValueError("theta_layer needs one threshold per layer")
-        self.desc = NetDesc(self.k, batch, self._descs, self._mask, {"coeff": 0, "chain": 1}[lookahead], self._theta)
+        self.desc = NetDesc(self.k, batch, self._descs, self._mask, {"coeff": 0, "chain": 1}[lookahead], self._theta,
+                            {"auto": 0, "kernels": 1, "fused": 2}[launch_mode])
         self.w_master, self.w_q, self.s_w = list(w_master), list(w_q), list(s_w)
         self._pm = (C.c_void_p * self.k)(*[t.data_ptr() for t in self.w_master])
         self._pq = (C.c_void_p * self.k)(*[t.data_ptr() for t in self.w_q])
@@ -271,7 +274,7 @@ def ff_train_step_at(net: Net, x_pos, x_neg, theta, lam, lr, seed, step_dev, adv
 
 
 KERNEL_CLASSES = ("gemm_fwd", "gemm_dw", "quant_act", "quant_grad", "quant_w", "update", "absmax", "small", "im2col",
-                  "residual", "dwconv", "chain")
+                  "residual", "dwconv", "chain", "fused")
 
 
 def ff_timing_enable(on, classes: Optional[Sequence[str]] = None) -> None:
@@ -285,6 +288,11 @@ def ff_timing_enable(on, classes: Optional[Sequence[str]] = None) -> None:
 def ff_timing_clock_probe(counters: Optional[torch.Tensor]) -> None:
     """counters: a zeroed int64 CUDA tensor of 16 elements (kept alive by the caller), or None to switch off."""
     _chk(lib().ff_timing_clock_probe(_ptr(counters)), "ff_timing_clock_probe")
+
+
+def ff_timing_fused_stamps(stamps: Optional[torch.Tensor]) -> None:
+    """stamps: an int64 CUDA tensor of 32 elements (kept alive by the caller), or None to switch off."""
+    _chk(lib().ff_timing_fused_stamps(_ptr(stamps)), "ff_timing_fused_stamps")
 
 
 def ff_timing_reset() -> None:

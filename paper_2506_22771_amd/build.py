@@ -15,8 +15,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libffint8.so")
-SOURCES = ["elementwise.hip", "gemm_i8.hip", "conv.hip", "api.hip"]
-HEADERS = [os.path.join(CSRC, "ff_internal.hpp"), os.path.join(os.path.dirname(HERE), "include", "ffint8.h")]
+SOURCES = ["elementwise.hip", "gemm_i8.hip", "conv.hip", "fused.hip", "api.hip"]
+HEADERS = [os.path.join(CSRC, "ff_internal.hpp"), os.path.join(CSRC, "device_math.hpp"), os.path.join(os.path.dirname(HERE), "include", "ffint8.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-ffp-contract=off", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]
 

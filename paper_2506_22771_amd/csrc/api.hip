@@ -161,6 +161,11 @@ struct WsLayout {
     size_t off_hq, st_hq;          // int8 scratch [2][st_hq]: the gradient handed down, row-major
     size_t off_e, st_e;            // int32 scratch [2][st_e] (bytes): input-gradient accumulators
     size_t off_wqt;                // int8 scratch: transposed int8 weights of one layer
+    // single-launch step of a small dense stack (all sizes 0 when the stack does not qualify)
+    int fused_ok;                  // the stack qualifies for the single-launch kernel
+    int fused_auto;                // ... and is small enough that FF_LAUNCH_AUTO picks it
+    int fused_wgs;                 // workgroups of that launch
+    size_t off_fgy[MAX_LAYERS], st_fgy[MAX_LAYERS];   // per layer: transposed int8 local gradient [2][st]
     size_t total;
 };
 
@@ -329,6 +334,44 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
         w->off_wqt = off;
         off += align_up(wqt, A);
     }
+    // Single-launch step: plain dense stacks of at most FU_MAX_LAYERS layers and FU_MAX_B samples per pass.  It keeps
+    // the local gradient of EVERY layer (the per-operation path reuses one scratch for all layers), hence the extra
+    // buffers; weight gradients are applied straight from the accumulator registers.
+    if (net->launch_mode != FF_LAUNCH_AUTO && net->launch_mode != FF_LAUNCH_KERNELS && net->launch_mode != FF_LAUNCH_FUSED)
+        return FF_ERR_INVALID_ARG;
+    w->fused_ok = !w->chain && w->k <= FU_MAX_LAYERS && w->B <= FU_MAX_B;
+    double macs = 0.0;
+    int64_t fwd_tiles = 0, dw_tiles = 0;
+    for (int i = 0; i < w->k && w->fused_ok; ++i) {
+        const Dims& d = w->d[i];
+        const ff_layer_desc& L = net->layers[i];
+        if (d.kind != FF_DENSE || L.role != FF_ROLE_LAYER || L.skip != FF_SKIP_NONE || L.input_back != 0 || d.n_chunks != 1)
+            w->fused_ok = 0;
+        // (the kernel indexes with 32 bits)
+        if (d.N * pitch8(d.K) > (int64_t(1) << 30) || d.K * pitch8(d.B) > (int64_t(1) << 30) || d.N * pitch8(d.B) > (int64_t(1) << 30))
+            w->fused_ok = 0;
+        macs += (double)d.B * (double)d.K * (double)d.N;
+        fwd_tiles = max(fwd_tiles, 2 * ((d.B + 31) / 32) * ((d.N + 31) / 32));
+        dw_tiles += ((d.N + 31) / 32) * ((d.K + 31) / 32);
+    }
+    w->fused_auto = w->fused_ok && macs <= (double)(int64_t(1) << 27);   // 41 M for 784 -> 500 -> 500 at 64 samples
+    // workgroups: one per forward tile (both passes), and enough wavefronts (8 per workgroup) to take the weight-gradient
+    // tiles of all layers in one round; an even number
+    w->fused_wgs = (int)min((int64_t)256, max(max((int64_t)32, fwd_tiles), (dw_tiles + FU_THREADS / 64 - 1) / (FU_THREADS / 64)));
+    w->fused_wgs = (w->fused_wgs + 1) & ~1;
+    for (int i = 0; i < w->k; ++i) w->off_fgy[i] = w->st_fgy[i] = 0;
+    if (net->launch_mode == FF_LAUNCH_FUSED && !w->fused_ok) return FF_ERR_UNSUPPORTED;
+    if (w->fused_ok && net->launch_mode != FF_LAUNCH_KERNELS && (w->fused_auto || net->launch_mode == FF_LAUNCH_FUSED)) {
+        for (int i = 0; i < w->k; ++i) {
+            const Dims& d = w->d[i];
+            w->st_fgy[i] = align_up((size_t)(d.N * pitch8(d.M)), A);
+            w->off_fgy[i] = off;
+            off += 2 * w->st_fgy[i];
+        }
+    } else {
+        w->fused_auto = 0;
+        if (net->launch_mode != FF_LAUNCH_FUSED) w->fused_ok = 0;
+    }
     w->total = off;
     return FF_OK;
 }
@@ -343,6 +386,7 @@ struct TimingState {
 };
 static TimingState g_timing;
 static unsigned long long* g_clock_probe = nullptr;   // device counters of ff_timing_clock_probe (null: off)
+static unsigned long long* g_fused_stamps = nullptr;  // device buffer of ff_timing_fused_stamps (null: off)
 
 struct Timed {
     hipStream_t s;
@@ -1037,9 +1081,59 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
     float* c = (float*)(base + w.off_c);
     float* ct = (float*)(base + w.off_ct);
 
-    HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)base, (int64_t)(w.zero_bytes / 4), 0u, s));
     const int64_t n_in = w.d[0].in_rows * w.d[0].in_cols;
     const int64_t st_x = ((intptr_t)x_neg - (intptr_t)x_pos) / (intptr_t)sizeof(float);
+    if (w.fused_ok && (w.fused_auto || net->launch_mode == FF_LAUNCH_FUSED)) {
+        // the whole step in one persistent launch (small dense stacks; see fused.hip): it clears what it adds to itself
+        FusedArgs fa;
+        memset(&fa, 0, sizeof(fa));
+        fa.k = k;
+        fa.B = (int32_t)B;
+        fa.lambda = lambda;
+        fa.lr = lr;
+        fa.seed = seed;
+        fa.step = step;
+        fa.step_dev = step_dev;
+        fa.advance = advance;
+        fa.x = x_pos;
+        fa.st_x = st_x;
+        fa.wg_amax = (uint32_t*)(base + w.off_wbmax);   // (UPDATE_MAX_BLOCKS words: more than the 256 workgroups at most)
+        fa.w_amax = w_amax;
+        fa.gsum = gsum;
+        fa.vmax = vmax;
+        fa.s_a = s_a;
+        fa.s_g = s_g;
+        fa.c = c;
+        fa.ct = ct;
+        fa.goodness = goodness;
+        fa.loss = loss;
+        for (int i = 0; i < k; ++i) {
+            const Dims& d = w.d[i];
+            FusedLayer& fl = fa.L[i];
+            fl.K = (int32_t)d.K;
+            fl.N = (int32_t)d.N;
+            fl.relu = net->layers[i].relu ? 1 : 0;
+            fl.l2norm = net->layers[i].l2norm_out ? 1 : 0;
+            fl.train = (!net->train_layer || net->train_layer[i]) ? 1 : 0;
+            fl.rshift = goodness_shift(d.K, d.rps * d.N);
+            fl.theta = net->theta_layer ? net->theta_layer[i] : theta;
+            fl.w = state->w_master[i];
+            fl.wq = state->w_q[i];
+            fl.sw = state->s_w[i];
+            fl.aq = (int8_t*)(base + w.off_aq[i]);
+            fl.st_aq = (int64_t)w.st_aq[i];
+            fl.aqt = (int8_t*)(base + w.off_aqt[i]);
+            fl.st_aqt = (int64_t)w.st_aqt[i];
+            fl.acc = (int32_t*)(base + w.off_acc[i]);
+            fl.st_acc = (int64_t)(w.st_acc[i] / sizeof(int32_t));
+            fl.gy = (int8_t*)(base + w.off_fgy[i]);
+            fl.st_gy = (int64_t)w.st_fgy[i];
+        }
+        fa.stamps = g_fused_stamps;
+        HIPCHK_T(FF_K_FUSED, launch_fused_dense_step(fa, w.fused_wgs, s));
+        return FF_OK;
+    }
+    HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)base, (int64_t)(w.zero_bytes / 4), 0u, s));
     HIPCHK_T(FF_K_ABSMAX, launch_absmax(x_pos, st_x, 2, n_in, out_amax, s));
 
     // ---- forward pass through all layers, both data sets together (Algorithm 1) -----------------
@@ -1519,6 +1613,13 @@ ff_status ff_timing_clock_probe(uint64_t* counters)
 {
     if (counters && ((uintptr_t)counters & 7)) return FF_ERR_ALIGN;
     g_clock_probe = (unsigned long long*)counters;
+    return FF_OK;
+}
+
+ff_status ff_timing_fused_stamps(uint64_t* stamps)
+{
+    if (stamps && ((uintptr_t)stamps & 7)) return FF_ERR_ALIGN;
+    g_fused_stamps = (unsigned long long*)stamps;
     return FF_OK;
 }
 

@@ -11,8 +11,8 @@
 namespace ffi {
 
 // ---- layout helpers -------------------------------------------------------------------------
-static inline int64_t pitch8(int64_t cols) { return (cols + 15) & ~int64_t(15); }
-static inline int64_t pitch32(int64_t cols) { return (cols + 3) & ~int64_t(3); }
+__host__ __device__ static inline int64_t pitch8(int64_t cols) { return (cols + 15) & ~int64_t(15); }
+__host__ __device__ static inline int64_t pitch32(int64_t cols) { return (cols + 3) & ~int64_t(3); }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- stochastic-rounding key (Section IV-B cites stochastic rounding; the generator is ours) --
@@ -269,6 +269,46 @@ GemmPlan gemm_plan(int64_t I, int64_t J, int64_t R, int nb, bool allow_split);
 // out[z][e] = sum over s < splits of part[z][s][e], e < n (n a multiple of 4); strides in elements
 hipError_t launch_reduce_splits(const int32_t* part, int splits, int64_t st_split, int64_t st_part_z, int32_t* out,
                                 int64_t st_out_z, int64_t n, int nb, hipStream_t s);
+
+// ---- single-launch step of a small dense stack (fused.hip) ---------------------------------------------------------
+constexpr int FU_MAX_LAYERS = 8;
+constexpr int FU_THREADS = 512;
+constexpr int FU_MAX_B = 2 * FU_THREADS;   // samples per pass
+struct FusedLayer {
+    int32_t K, N, relu, l2norm, train, rshift;
+    float theta;
+    float* w;      // fp32 master weights [N, K]
+    int8_t* wq;    // [N, pitch8(K)]
+    float* sw;
+    // workspace of the step, two passes each (strides in elements of the respective type)
+    int8_t* aq;    int64_t st_aq;    // quantised layer input [B, pitch8(K)]
+    int8_t* aqt;   int64_t st_aqt;   // its transposed copy [K, pitch8(B)]
+    int32_t* acc;  int64_t st_acc;   // accumulators [B, pitch32(N)]
+    int8_t* gy;    int64_t st_gy;    // transposed int8 local gradient [N, pitch8(B)]
+};
+struct FusedArgs {
+    int32_t k, B;
+    float lambda, lr;
+    uint64_t seed, step;
+    uint64_t* step_dev;   // null: `step` is used
+    int32_t advance;
+    const float* x;       // positive set; the negative set is st_x elements further on
+    int64_t st_x;
+    uint32_t* wg_amax;    // [workgroups]: per-workgroup absmax of the net input
+    uint32_t* w_amax;     // [k]
+    unsigned long long* gsum;   // [k][2][B]
+    int32_t* vmax;        // [k][2][B]
+    float* s_a;           // [k][2]
+    float* s_g;           // [k][2]
+    float* c;             // [k][2][B]
+    float* ct;            // [k][2][B]
+    float* goodness;      // [k][2][B]
+    float* loss;          // [k][2]
+    unsigned* bar;        // device-wide barrier counters (filled in by the launcher)
+    unsigned long long* stamps;   // instrumentation, see ff_timing_fused_stamps (null normally)
+    FusedLayer L[FU_MAX_LAYERS];
+};
+hipError_t launch_fused_dense_step(const FusedArgs& a, int workgroups, hipStream_t s);
 
 // ---- explicit im2col (conv.hip) ----------------------------------------------------------------------
 struct ConvGeom {

@@ -82,7 +82,10 @@ def test_workspace_bytes_and_train_step_validation(ff):
     wl = workload("cfg1")
     descs = (ff.binding.LayerDesc * 2)(*[ff.layer_desc(l, wl.batch) for l in wl.layers])
     net = ff.binding.NetDesc(2, wl.batch, descs)
-    n = ff.lib().ff_workspace_bytes(C.byref(net))
+    n = ff.lib().ff_workspace_bytes(C.byref(ff.binding.NetDesc(2, wl.batch, descs, None, 0, None, 1)))   # per-operation kernels
+    # the single-launch step (what FF_LAUNCH_AUTO picks for this stack) keeps every layer's int8 local gradient
+    extra = 2 * sum(l.N * ff.ff_pitch(wl.batch) for l in wl.layers)
+    assert n + extra <= ff.lib().ff_workspace_bytes(C.byref(net)) <= n + extra + 8192
     # at least the retained int32 accumulators and transposed int8 inputs of both layers, both passes
     need = 2 * sum(wl.batch * l.N * 4 + l.K * ff.ff_pitch(wl.batch) for l in wl.layers)
     scratch = 2 * max(l.N * l.K * 4 + wl.batch * ff.ff_pitch(l.K) + l.N * ff.ff_pitch(wl.batch) for l in wl.layers)
@@ -135,7 +138,8 @@ def test_chain_lookahead_validation(ff):
     def nbytes(name, mode):
         wl = workload(name)
         descs = (ff.binding.LayerDesc * len(wl.layers))(*[ff.layer_desc(l, wl.batch) for l in wl.layers])
-        return ff.lib().ff_workspace_bytes(C.byref(ff.binding.NetDesc(len(wl.layers), wl.batch, descs, None, mode)))
+        # (per-operation kernels on both sides: the single-launch step has workspace needs of its own)
+        return ff.lib().ff_workspace_bytes(C.byref(ff.binding.NetDesc(len(wl.layers), wl.batch, descs, None, mode, None, 1)))
 
     assert nbytes("tiny", 1) > nbytes("tiny", 0) > 0
     assert nbytes("cfg5", 1) > nbytes("cfg5", 0)
@@ -193,3 +197,23 @@ def test_launch_limits_are_host_side(ff):
     descs = (ff.binding.LayerDesc * 2)(ff.layer_desc(Layer("conv", H=32, W=32, C_in=16, C_out=16, ksize=3, stride=1, pad=1), 70000),
                                        ff.layer_desc(many, 70000))
     assert L.ff_workspace_bytes(C.byref(ff.binding.NetDesc(2, 70000, descs))) == 0            # block-output kernels: B on grid.y
+
+
+def test_launch_mode_validation(ff):
+    """ff_net_desc.launch_mode: unknown values are argument errors; the single launch is refused (workspace 0) for
+    stacks it does not cover; where it applies it needs more workspace than the per-operation kernels."""
+    import ctypes as C
+    from workloads import workload
+
+    def nbytes(name, mode):
+        wl = workload(name)
+        descs = (ff.binding.LayerDesc * len(wl.layers))(*[ff.layer_desc(l, wl.batch) for l in wl.layers])
+        return ff.lib().ff_workspace_bytes(C.byref(ff.binding.NetDesc(len(wl.layers), wl.batch, descs, None, 0, None, mode)))
+
+    assert nbytes("cfg1", 3) == 0 and nbytes("cfg1", -1) == 0
+    assert nbytes("cfg1", 2) == nbytes("cfg1", 0) > nbytes("cfg1", 1) > 0        # auto picks the single launch for cfg1
+    assert nbytes("cfg5", 2) == 0 and nbytes("cfg5", 0) == nbytes("cfg5", 1) > 0  # 8192 samples per pass: too many
+    assert nbytes("cfg3", 2) == 0 and nbytes("tiny_res", 2) == 0                  # convolutions, residual wiring
+    wl = workload("tiny")
+    descs = (ff.binding.LayerDesc * 2)(*[ff.layer_desc(l, wl.batch) for l in wl.layers])
+    assert ff.lib().ff_workspace_bytes(C.byref(ff.binding.NetDesc(2, wl.batch, descs, None, 1, None, 2))) == 0   # chain + fused

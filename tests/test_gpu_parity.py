@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 from oracle import ff_oracle as O  # noqa: E402
-from workloads import Layer, make_inputs, make_weights, scaled, workload  # noqa: E402
+from workloads import Layer, Workload, make_inputs, make_weights, mlp, scaled, workload  # noqa: E402
 
 
 @pytest.fixture(scope="module")
@@ -371,7 +371,8 @@ def _assert_live(ref, wl):
             assert all(np.any(d) for d in g["dw"]), f"layer {i} pass {p}: zero weight gradient"
 
 
-def _run_steps(ff, wl, n_steps, lam=None, lookahead="coeff", theta=None, inputs=None, theta_layer=None, live=False):
+def _run_steps(ff, wl, n_steps, lam=None, lookahead="coeff", theta=None, inputs=None, theta_layer=None, live=False,
+               launch_mode="auto"):
     lam = wl.lam if lam is None else lam
     theta = wl.theta if theta is None else theta
     oracle_step = O.train_step if lookahead == "coeff" else O.train_step_chain
@@ -384,7 +385,7 @@ def _run_steps(ff, wl, n_steps, lam=None, lookahead="coeff", theta=None, inputs=
     ws1 = workspace()
     for i, l in enumerate(wl.layers):
         ff.ff_quantize(d_w[i], l.N, l.K, 0, 0, 0, d_wq[i], None, d_sw[i], ws1)
-    net = ff.Net(wl.layers, B, d_w, d_wq, d_sw, lookahead=lookahead, theta_layer=theta_layer)
+    net = ff.Net(wl.layers, B, d_w, d_wq, d_sw, lookahead=lookahead, theta_layer=theta_layer, launch_mode=launch_mode)
     nbytes = net.workspace_bytes()
     assert nbytes > 0
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
@@ -414,6 +415,43 @@ def _run_steps(ff, wl, n_steps, lam=None, lookahead="coeff", theta=None, inputs=
                                         ("tiny_conv16", 3), ("tiny_conv_s2", 3), ("tiny_res", 3), ("tiny_dw", 3), ("tiny_cnn_head", 3)])
 def test_train_step(ff, name, steps):
     _run_steps(ff, workload(name), steps)
+
+
+@pytest.mark.parametrize("mode", ["kernels", "fused"])
+@pytest.mark.parametrize("name,steps", [("tiny", 3), ("tiny_l2", 3), ("cfg1", 3)])
+def test_train_step_launch_modes(ff, name, steps, mode):
+    """Small dense stacks through both ways of issuing the step -- one kernel per operation, and the whole step as a
+    single persistent launch -- each against the oracle (FF_LAUNCH_AUTO, which the other tests use, picks the single
+    launch for stacks this small)."""
+    _run_steps(ff, workload(name), steps, launch_mode=mode)
+
+
+def test_train_step_fused_live_and_per_layer_theta(ff):
+    """The single-launch step with matched per-layer thresholds (both passes live, asserted on the oracle side), with
+    and for a one-layer stack (frozen layers: the schedule tests run through this path too)."""
+    wl = workload("cfg1")
+    _run_steps(ff, wl, 2, theta_layer=_matched_thetas(wl), live=True, launch_mode="fused")
+    wl = workload("tiny_l2")
+    _run_steps(ff, wl, 2, theta_layer=_matched_thetas(wl), live=True, launch_mode="fused")
+    one = Workload("one_layer", mlp([40, 24], False), 9, "uniform_onehot", lam=0.3, theta=5.0)
+    _run_steps(ff, one, 2, launch_mode="fused")
+    _run_steps(ff, one, 2, launch_mode="kernels")
+
+
+def test_fused_launch_mode_limits(ff):
+    """Stacks the single launch does not cover are refused when it is asked for explicitly (workspace size 0:
+    FF_ERR_UNSUPPORTED from the descriptor check) and fall back to per-operation kernels under FF_LAUNCH_AUTO."""
+    for name in ("tiny_conv", "tiny_res", "cfg2"):
+        wl = workload(name)
+        W = make_weights(wl)
+        d_w = [dev(w.reshape(w.shape[0], -1)) for w in W]
+        mk = lambda mode: ff.Net(wl.layers, wl.batch, d_w, [empty8(l.N, l.K) for l in wl.layers],
+                                 [scalar() for _ in wl.layers], launch_mode=mode).workspace_bytes()
+        assert mk("auto") > 0 and mk("kernels") > 0
+        if name != "cfg2":
+            assert mk("fused") == 0
+        else:   # cfg2 qualifies structurally (dense, 1024 samples) but is far too large for FF_LAUNCH_AUTO to pick it
+            assert mk("fused") > mk("auto") == mk("kernels")
 
 
 @pytest.mark.slow

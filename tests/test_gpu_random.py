@@ -94,7 +94,8 @@ def test_random_dense_stacks(ff):
             layers = tuple(replace(l, relu=int(rng.integers(0, 2))) for l in layers)
         wl = Workload(f"rand{case}", layers, B, "uniform_onehot", lam=float(rng.choice([0.0, 0.1, 0.7])),
                       theta=float(rng.choice([2.0, 10.0, 40.0])))
-        P._run_steps(ff, wl, 2)
+        P._run_steps(ff, wl, 2, launch_mode="kernels")
+        P._run_steps(ff, wl, 2, launch_mode="fused")
         if not norm:
             P._run_steps(ff, wl, 2, lookahead="chain")
 

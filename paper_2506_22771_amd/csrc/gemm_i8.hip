@@ -38,6 +38,12 @@ constexpr int BK = 128;  // reduction bytes per LDS stage
 #ifndef FF_PERSIST
 #define FF_PERSIST 1
 #endif
+#ifndef FF_NEXT_TILE_PREFETCH
+#define FF_NEXT_TILE_PREFETCH 1
+#endif
+#ifndef FF_SPLIT_ISSUE
+#define FF_SPLIT_ISSUE 1
+#endif
 #ifndef FF_STAGED_EPI
 #define FF_STAGED_EPI 1   // 1: interior tiles leave through LDS as whole rows (see the epilogue)
 #endif
@@ -87,14 +93,21 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     constexpr int CH_P = BM * 8 / T, CH_Q = BN * 8 / T;
     constexpr int STAGE_BYTES = (BM + BN) * BK;
     static_assert(BM * 8 % T == 0 && BN * 8 % T == 0, "tile/threads mismatch");
-    // epilogue staging: one 32-row slice of a wave's tile, rows padded by 16 bytes to spread the banks
+    // epilogue staging: one slice of EROWS rows of a wave's tile, rows padded by 16 bytes to spread the banks.  The big
+    // dense tile stages 16 rows at a time in the SECOND operand stage (and a little beyond it), which leaves the first
+    // stage free for the first copies of the workgroup's next tile (persistent launches); the others 32 rows from 0.
+    constexpr bool PREFETCH = FF_NEXT_TILE_PREFETCH && BM == 256 && BN == 256 && CONV == 0 && MODE != 2;
+    constexpr int EROWS = PREFETCH ? 16 : 32;
     constexpr int EROW = WTN * 4 + 16;
-    constexpr int ESLICE = 32 * EROW;
-    constexpr int LDS_BYTES = 2 * STAGE_BYTES > WM * WN * ESLICE ? 2 * STAGE_BYTES : WM * WN * ESLICE;
+    constexpr int ESLICE = EROWS * EROW;
+    constexpr int EOFF = PREFETCH ? STAGE_BYTES : 0;
+    constexpr int LDS_BYTES = 2 * STAGE_BYTES > EOFF + WM * WN * ESLICE ? 2 * STAGE_BYTES : EOFF + WM * WN * ESLICE;
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS");
     __shared__ __attribute__((aligned(16))) int8_t lds[LDS_BYTES];
 
+    // clock probe: the counters are wavefront-uniform (scalar registers); only the final atomics are per thread
     unsigned long long clk0 = 0, rt0 = 0;
-    if (a.clk && threadIdx.x == 0) {
+    if (a.clk) {
         clk0 = clock64();
         rt0 = wall_clock64();
     }
@@ -113,9 +126,10 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     // Tiles of all nb problems are numbered t = z * tiles_z + bj * tiles_i + bi.  A launch has either one workgroup
     // per tile, or (persistent: large dense problems) one workgroup per compute unit that takes every gridDim.x-th
     // tile in turn -- no workgroup start-up and drain between a compute unit's tiles.
+    bool prefetched = false;   // the copies of this tile's first reduction step were issued during the previous tile's epilogue
     for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
-    unsigned long long pht = 0, ph1 = 0, ph2 = 0;   // phase marks of the clock probe (thread 0 only)
-    if (a.clk && threadIdx.x == 0) pht = clock64();
+    unsigned long long pht = 0, ph1 = 0, ph2 = 0;   // phase marks of the clock probe
+    if (a.clk) pht = clock64();
     const int z = t / tiles_z, tz = t - z * tiles_z;
     const int bi = tz % tiles_i, bj = tz / tiles_i;
     const int8_t* __restrict__ P = a.P + z * a.st_p;
@@ -232,6 +246,13 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     // the copy of stage kt+2 is issued there: one copy is in flight at every moment, each with a whole step
     // of time to land.
 #if FF_PRO2
+    if (PREFETCH && prefetched) {
+        // Step 0 is in LDS already: every wavefront waited for its own copies of it before the stores of the previous
+        // epilogue, and the barrier at the end of that tile made them visible to all.  Only step 1 goes out now; the
+        // main loop waits for it (and, copies and stores completing in issue order, for the previous tile's stores).
+        if (kt0 + 1 < nk) issue(kt0 + 1, 1);
+        ldfrag(0, lds, 0);
+    } else {
     // both stages are free at the start of a tile: the copies of the first two steps go out together, so that only
     // one round trip to memory is exposed (copies complete in issue order)
     issue(kt0, 0);
@@ -243,6 +264,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     }
     __builtin_amdgcn_s_barrier();
     ldfrag(0, lds, 0);
+    }
 #else
     issue(kt0, 0);
     wait_vmcnt<0>();
@@ -250,7 +272,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     ldfrag(0, lds, 0);
     if (kt0 + 1 < nk) issue(kt0 + 1, 1);
 #endif
-    if (a.clk && threadIdx.x == 0) ph1 = clock64();
+    if (a.clk) ph1 = clock64();
     for (int kt = kt0; kt < nk; ++kt) {
         const int cur = (kt - kt0) & 1;
         const int8_t* sb = lds + cur * STAGE_BYTES;
@@ -264,9 +286,21 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
+#if FF_SPLIT_ISSUE
+        // The copy instructions of a step keep the address unit busy for about a thousand clocks (64 KB at 64 bytes
+        // per clock).  Half of the wavefronts -- one of the two on every SIMD -- issue theirs before the last
+        // multiplies of the step, the other half after them, so that every SIMD has multiplies to run while the
+        // copies queue up.
+        const bool early = wave < WM * WN / 2;
+        if (early && kt + 2 < nk) issue(kt + 2, cur);
+        if (kt + 1 < nk) ldfrag(0, sn, 0);
+        mma(1);
+        if (!early && kt + 2 < nk) issue(kt + 2, cur);
+#else
         if (kt + 2 < nk) issue(kt + 2, cur);
         if (kt + 1 < nk) ldfrag(0, sn, 0);
         mma(1);
+#endif
     }
 
     // Epilogue.  A lane holds, per accumulator quad, four consecutive columns of ONE row, so a direct store
@@ -275,11 +309,30 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     // then reads that give every store instruction whole contiguous row segments of WTN*4 bytes.
     // Edge tiles take the same route when J is a multiple of 4 (a lane's 16 bytes then never straddle the last
     // column): rows and column groups beyond the matrix are simply not stored.
-    if (a.clk && threadIdx.x == 0) ph2 = clock64();
+    if (a.clk) ph2 = clock64();
+    // Persistent launches of the big dense tile: the copies of the NEXT tile's first reduction step go out now, into
+    // the first operand stage (nobody reads the stages any more; the staging below keeps to the second one), so that
+    // their round trip to memory runs under this tile's epilogue instead of in front of the next tile's main loop.
+    bool wait_copies = false;
+    prefetched = false;
+    if (PREFETCH && t + (int)gridDim.x < ntiles) {
+        const int tn = t + (int)gridDim.x;
+        const int zn = tn / tiles_z, tzn = tn - zn * tiles_z;
+        const int i0n = (tzn % tiles_i) * BM, j0n = (tzn / tiles_i) * BN;
+        rp = __builtin_amdgcn_make_buffer_rsrc((void*)(a.P + zn * a.st_p + (int64_t)i0n * a.ldp), 0, (int)(min(BM, a.I - i0n) * a.ldp), 0x00020000);
+        rq = __builtin_amdgcn_make_buffer_rsrc((void*)(a.Q + zn * a.st_q + (int64_t)j0n * a.ldq), 0, (int)(min(BN, a.J - j0n) * a.ldq), 0x00020000);
+        issue(0, 0);
+        prefetched = true;
+        wait_copies = true;
+    }
     const bool interior = i0 + BM <= a.I && j0 + BN <= a.J;
     const bool staged = FF_STAGED_EPI && (interior || (a.J & 3) == 0);
     const bool fast_sq = a.relu && a.rshift == 0;
-    int8_t* const ebase = lds + wave * ESLICE;
+    int8_t* const ebase = lds + EOFF + wave * ESLICE;
+    if (wait_copies && !staged) {   // (copies and stores complete in issue order: wait before the first store)
+        wait_vmcnt<0>();
+        wait_copies = false;
+    }
 #pragma unroll
     for (int ti = 0; ti < TI; ++ti) {
         const int i = i0 + wm * WTM + ti * 32 + lr;
@@ -292,9 +345,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
                 const int j = j0 + wn * WTN + tj * 32 + 8 * g + 4 * lh;
                 const int c0 = acc[ti][tj][4 * g + 0], c1 = acc[ti][tj][4 * g + 1];
                 const int c2 = acc[ti][tj][4 * g + 2], c3 = acc[ti][tj][4 * g + 3];
-                if (staged) {
-                    *(v4i*)(ebase + lr * EROW + (tj * 32 + 8 * g + 4 * lh) * 4) = (v4i){c0, c1, c2, c3};
-                } else if (i < a.I) {
+                if (!staged && i < a.I) {
                     int32_t* dst = C + (int64_t)i * a.ldc + j;
                     if (j + 3 < a.J) {
                         *(v4i*)dst = (v4i){c0, c1, c2, c3};
@@ -328,23 +379,41 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
             }
         }
         if (staged) {
-            wave_lds_fence();
-            constexpr int LPR = WTN / 4;          // lanes (16 bytes each) per staged row
-            constexpr int RPI = 64 / LPR;         // rows per store instruction
-            const int rl = lane / LPR, cc = lane - rl * LPR;
-            int32_t* const ctile = C + (int64_t)(i0 + wm * WTM + ti * 32) * a.ldc + j0 + wn * WTN + cc * 4;
+            // EROWS rows of the 32 at a time: the lanes that hold those rows write their quads, then every store
+            // instruction takes whole contiguous row segments
 #pragma unroll
-            for (int r = 0; r < 32 / RPI; ++r) {
-                const int row = r * RPI + rl;
-                const v4i v = *(const v4i*)(ebase + row * EROW + cc * 16);
-                if (!interior && (i0 + wm * WTM + ti * 32 + row >= a.I || j0 + wn * WTN + cc * 4 >= a.J)) continue;
-                // forward accumulators are not read again until other kernels have streamed more than the caches
-                // hold: a non-temporal store keeps them from displacing what is needed next.  Weight gradients are
-                // read by the update right away: ordinary stores.
-                if (MODE == 1) __builtin_nontemporal_store(v, (v4i*)(ctile + (int64_t)row * a.ldc));
-                else *(v4i*)(ctile + (int64_t)row * a.ldc) = v;
+            for (int h = 0; h < 32 / EROWS; ++h) {
+                if (EROWS == 32 || (lr / EROWS) == h) {
+#pragma unroll
+                    for (int tj = 0; tj < TJ; ++tj)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g)
+                            *(v4i*)(ebase + (lr % EROWS) * EROW + (tj * 32 + 8 * g + 4 * lh) * 4) =
+                                (v4i){acc[ti][tj][4 * g + 0], acc[ti][tj][4 * g + 1], acc[ti][tj][4 * g + 2], acc[ti][tj][4 * g + 3]};
+                }
+                wave_lds_fence();
+                if (wait_copies) {   // once per tile, before its first store (copies and stores complete in issue order)
+                    wait_vmcnt<0>();
+                    wait_copies = false;
+                }
+                constexpr int LPR = WTN / 4;          // lanes (16 bytes each) per staged row
+                constexpr int RPI = 64 / LPR;         // rows per store instruction
+                const int rl = lane / LPR, cc = lane - rl * LPR;
+                const int row0 = i0 + wm * WTM + ti * 32 + h * EROWS;
+                int32_t* const ctile = C + (int64_t)row0 * a.ldc + j0 + wn * WTN + cc * 4;
+#pragma unroll
+                for (int r = 0; r < EROWS / RPI; ++r) {
+                    const int row = r * RPI + rl;
+                    const v4i v = *(const v4i*)(ebase + row * EROW + cc * 16);
+                    if (!interior && (row0 + row >= a.I || j0 + wn * WTN + cc * 4 >= a.J)) continue;
+                    // forward accumulators are not read again until other kernels have streamed more than the caches
+                    // hold: a non-temporal store keeps them from displacing what is needed next.  Weight gradients are
+                    // read by the update right away: ordinary stores.
+                    if (MODE == 1) __builtin_nontemporal_store(v, (v4i*)(ctile + (int64_t)row * a.ldc));
+                    else *(v4i*)(ctile + (int64_t)row * a.ldc) = v;
+                }
+                wave_lds_fence();
             }
-            wave_lds_fence();
         }
         if (EPI) {
             // the two half-waves hold the two column halves of the same row
@@ -374,17 +443,19 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     // the staging slices of the epilogue lie in the operand stages: every wave must be done with them before the
     // copies of the next tile land there
     unsigned long long ph3 = 0;
-    if (a.clk && threadIdx.x == 0) ph3 = clock64();
+    if (a.clk) ph3 = clock64();
     if (t + (int)gridDim.x < ntiles) __builtin_amdgcn_s_barrier();
-    if (a.clk && threadIdx.x == 0) {
+    if (a.clk) {
         // shader clocks of this tile by phase: slots 2.. for plain / split launches, 8.. for forward launches
         const unsigned long long ph4 = clock64();
+        if (threadIdx.x == 0) {
         unsigned long long* pc = a.clk + (MODE == 1 ? 8 : 2);
         atomicAdd(pc + 0, ph1 - pht);   // tile start to the first fragments (operand round trip)
         atomicAdd(pc + 1, ph2 - ph1);   // main loop
         atomicAdd(pc + 2, ph3 - ph2);   // epilogue of wave 0
         atomicAdd(pc + 3, ph4 - ph3);   // waiting for the other waves' epilogues
         atomicAdd(pc + 4, 1ull);        // tiles
+        }
     }
     }   // tile loop
     if (a.clk && threadIdx.x == 0) {

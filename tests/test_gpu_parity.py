@@ -106,6 +106,14 @@ def test_layer_forward(ff, B, K, N, relu):
     np.testing.assert_array_equal(vmax.cpu().numpy(), g_ref["vmax"])
 
 
+@pytest.mark.parametrize("B,K,N", [(8192, 128, 4096), (8192, 400, 4096), (12288, 272, 4096)])
+def test_layer_forward_persistent_launch(ff, B, K, N):
+    """Outputs of 512 or 768 tiles of 256 x 256: the contraction then runs as a persistent launch, one workgroup per
+    compute unit walking over two or three tiles, with the first copies of a workgroup's next tile issued during the
+    epilogue of the current one.  Short reductions (one to four steps, one with a ragged tail) keep the oracle quick."""
+    test_layer_forward(ff, B, K, N, 1)
+
+
 def test_layer_forward_extreme_codes(ff):
     """All-(+-127) operands at the longest reduction used here: the int32 accumulator and the uint64
     sum of squares take their largest values."""

@@ -217,6 +217,33 @@ def operand_zero_fractions(ff, torch, wl, theta_layer, theta):
     return out
 
 
+def mfma_ceiling_probe(ff, torch, iterations=16384, launches=10):
+    """Register-resident int8 MFMA loop (ff_probe_mfma_ceiling) by operand kind: TOP/s and the clock it ran at."""
+    sink = torch.empty(256 * 512, dtype=torch.int32, device="cuda")
+    out = {"probe": "v_mfma_i32_32x32x32_i8 on register-resident operands, 8 wavefronts per compute unit, "
+                    f"{iterations} x 8 instructions per wavefront, {launches} launches timed back to back",
+           "peak_TOPs": INT8_MFMA_PEAK_TOPS}
+    for kind, name in ((0, "zeros"), (1, "all_codes_1"), (2, "pseudo_random_words")):
+        for _ in range(3):
+            ff.ff_probe_mfma_ceiling(kind, iterations, sink, None)
+        torch.cuda.synchronize()
+        clk = torch.zeros(2, dtype=torch.int64, device="cuda")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ops = 0.0
+        for _ in range(launches):
+            ops += ff.ff_probe_mfma_ceiling(kind, iterations, sink, clk)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        c = clk.cpu().tolist()
+        tops = ops / (ms * 1e-3) / 1e12
+        out[name] = {"ms_per_launch": round(ms / launches, 4), "TOPs": round(tops, 1),
+                     "frac_of_peak": round(tops / INT8_MFMA_PEAK_TOPS, 4),
+                     "mean_shader_clock_GHz": round(c[0] / max(c[1], 1) * 0.1, 3)}
+    return out
+
+
 def time_steps(ff, torch, wl, st, theta, steps, start, classes=("gemm_fwd", "gemm_dw")):
     net, d_xp, d_xn, loss, good, ws = st[:6]
     ff.ff_timing_reset()
@@ -306,6 +333,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg5")
+    ap.add_argument("--settle-seconds", type=float, default=0.4,
+                    help="before the W warmup steps, keep the GPU under the same load for this long (untimed), so that "
+                         "the timed region starts from the clock/power state of sustained training rather than from "
+                         "idle; 0 switches it off (the first ~10 steps after idle run 3-8 %% slower)")
     ap.add_argument("--theta", choices=("matched", "paper"), default="matched",
                     help="matched: one threshold per layer, the median initial goodness (both passes carry live int8 "
                          "gradients); paper: theta = 2.0 for every layer (Section V-A)")
@@ -324,6 +355,10 @@ def main() -> int:
     ap.add_argument("--gemm-data-probe", action="store_true",
                     help="instead of the train step, time the forward contraction of the first layer on Gaussian, "
                          "constant and zero int8 operands (same kernel and traffic; shows the clock/power effect)")
+    ap.add_argument("--mfma-ceiling-probe", action="store_true",
+                    help="instead of the train step, time a register-resident loop of the contraction kernel's MFMA "
+                         "instruction on zero, constant and pseudo-random operands (no operand movement: the rate the "
+                         "matrix pipes sustain under the power manager)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives are part of it); use --gpus 1",
@@ -343,6 +378,9 @@ def main() -> int:
     if args.gemm_data_probe:
         print(json.dumps(gemm_data_probe(ff, torch, wl)))
         return 0
+    if args.mfma_ceiling_probe:
+        print(json.dumps(mfma_ceiling_probe(ff, torch)))
+        return 0
     st_paper = setup(ff, torch, wl, args.lookahead, launch_mode=args.launch_mode)
     k, B = len(wl.layers), wl.batch
     theta_layer = matched_thetas(ff, torch, wl, st_paper) if args.theta == "matched" else None
@@ -358,6 +396,14 @@ def main() -> int:
         del cal_in, cal_out
 
     step_no = 0
+    settle_steps = 0
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < args.settle_seconds:
+        for i in range(10):
+            ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, step_no, loss, good, ws)
+            step_no += 1
+        settle_steps += 10
+        torch.cuda.synchronize()
     for i in range(args.warmup):
         ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, step_no, loss, good, ws)
         step_no += 1
@@ -465,6 +511,8 @@ def main() -> int:
         "value": samples * k / (ms_per_step * 1e-3),
         "unit": "samples/s per layer step",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "settle": {"seconds": args.settle_seconds, "untimed_steps_before_warmup": settle_steps,
+                   "why": "the timed region starts from the clock state of sustained training, not from idle"},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8 (int32 accumulate; fp32 scales, goodness, master weights)", "data": "synthetic",
         "config": {"workload": wl.name, "layers": [f"{l.K}->{l.N}" for l in wl.layers],
@@ -492,6 +540,8 @@ def main() -> int:
     except ff.FFError as e:   # a side measurement never takes the headline down
         out["operand_zero_fraction"] = {"error": str(e)}
     torch.cuda.empty_cache()
+    # what the matrix pipes sustain with no operand movement at all, by operand values (outside the timed region)
+    out["roofline"]["register_loop_ceiling"] = mfma_ceiling_probe(ff, torch, iterations=8192, launches=5)
     if not args.no_other_configs and wl.name == "cfg5":
         oc = {}
         for name in ("cfg1", "cfg2", "cfg3", "cfg4"):

@@ -418,6 +418,18 @@ ff_status ff_timing_clock_probe(uint64_t* counters);
  * last goodness + look-ahead + gradient quantise; weight gradient + update; requantise).  NULL switches it off. */
 #define FF_FUSED_STAMPS 32
 ff_status ff_timing_fused_stamps(uint64_t* stamps);
+/* Ceiling probe (measurement aid, not part of the train step): one launch of a kernel that issues nothing but the
+ * int8 MFMA instruction of the contraction kernel on register-resident operands -- one workgroup of 8 wavefronts per
+ * compute unit, `iterations` x 8 instructions per wavefront -- on operand words of the given kind: 0 zeros, 1 every
+ * code equal to 1, 2 pseudo-random words.  Timed by the caller (events on `stream`), it gives the rate the matrix pipes
+ * sustain under the power manager for that kind of data, with no operand movement at all.
+ *   sink      DEVICE, at least 256 * 512 * 4 bytes (512 KiB): receives one word per thread (keeps the work live)
+ *   counters  DEVICE, 2 uint64 zeroed by the caller, or NULL: [0] += shader-clock cycles, [1] += 100 MHz ticks, per
+ *             workgroup (their ratio * 100 MHz = the clock the launch ran at)
+ *   ops       HOST out: int8 operations (2 per multiply-add) of the launch
+ * Errors: FF_ERR_INVALID_ARG, FF_ERR_ALIGN, FF_ERR_WORKSPACE (sink too small), FF_ERR_HIP. */
+ff_status ff_probe_mfma_ceiling(int32_t operand_kind, int32_t iterations, int32_t* sink, size_t sink_bytes,
+                                uint64_t* counters, double* ops, void* stream);
 ff_status ff_timing_reset(void);
 ff_status ff_timing_read(int32_t kernel_class, double* total_ms, int64_t* launches);
 

@@ -98,6 +98,8 @@ def lib() -> C.CDLL:
         L.ff_timing_enable.argtypes = [i32]
         L.ff_timing_clock_probe.restype = i32
         L.ff_timing_clock_probe.argtypes = [P]
+        L.ff_probe_mfma_ceiling.restype = i32
+        L.ff_probe_mfma_ceiling.argtypes = [i32, i32, P, sz, P, C.POINTER(C.c_double), P]
         L.ff_timing_fused_stamps.restype = i32
         L.ff_timing_fused_stamps.argtypes = [P]
         L.ff_timing_reset.restype = i32
@@ -288,6 +290,14 @@ def ff_timing_enable(on, classes: Optional[Sequence[str]] = None) -> None:
 def ff_timing_clock_probe(counters: Optional[torch.Tensor]) -> None:
     """counters: a zeroed int64 CUDA tensor of 16 elements (kept alive by the caller), or None to switch off."""
     _chk(lib().ff_timing_clock_probe(_ptr(counters)), "ff_timing_clock_probe")
+
+
+def ff_probe_mfma_ceiling(operand_kind: int, iterations: int, sink: torch.Tensor, counters: Optional[torch.Tensor]) -> float:
+    """Launches the register-resident MFMA loop on the current stream; returns the int8 operations of the launch."""
+    ops = C.c_double(0.0)
+    _chk(lib().ff_probe_mfma_ceiling(operand_kind, iterations, _ptr(sink), sink.numel() * sink.element_size(),
+                                     _ptr(counters), C.byref(ops), _stream()), "ff_probe_mfma_ceiling")
+    return ops.value
 
 
 def ff_timing_fused_stamps(stamps: Optional[torch.Tensor]) -> None:

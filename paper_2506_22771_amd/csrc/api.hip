@@ -1616,6 +1616,20 @@ ff_status ff_timing_clock_probe(uint64_t* counters)
     return FF_OK;
 }
 
+ff_status ff_probe_mfma_ceiling(int32_t operand_kind, int32_t iterations, int32_t* sink, size_t sink_bytes,
+                                uint64_t* counters, double* ops, void* stream)
+{
+    if (operand_kind < 0 || operand_kind > 2 || iterations < 1 || !sink || !ops) return FF_ERR_INVALID_ARG;
+    if (!aligned4(sink) || (counters && ((uintptr_t)counters & 7))) return FF_ERR_ALIGN;
+    const int g = num_cus();
+    if (sink_bytes < (size_t)g * 512 * sizeof(int32_t)) return FF_ERR_WORKSPACE;
+    int wgs = 0;
+    if (launch_mfma_ceiling(sink, iterations, operand_kind, (unsigned long long*)counters, &wgs, (hipStream_t)stream) != hipSuccess)
+        return FF_ERR_HIP;
+    *ops = (double)wgs * 8.0 * (double)iterations * 8.0 * 65536.0;   // workgroups x wavefronts x iterations x MFMAs x ops
+    return FF_OK;
+}
+
 ff_status ff_timing_fused_stamps(uint64_t* stamps)
 {
     if (stamps && ((uintptr_t)stamps & 7)) return FF_ERR_ALIGN;

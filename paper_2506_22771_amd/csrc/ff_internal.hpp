@@ -262,6 +262,9 @@ struct GemmArgs {
     unsigned long long* clk;   // 16 counters, see ff_timing_clock_probe
 };
 hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s);
+int num_cus();   // compute units of the current device (256 when the query fails)
+// register-resident MFMA loop (see ff_probe_mfma_ceiling): one workgroup of 512 threads per compute unit
+hipError_t launch_mfma_ceiling(int32_t* sink, int iters, int kind, unsigned long long* clk, int* workgroups, hipStream_t s);
 struct GemmPlan {
     int bm, bn, splits;
 };

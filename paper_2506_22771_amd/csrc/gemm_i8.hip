@@ -465,7 +465,7 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
 }
 
 
-static int num_cus()
+int num_cus()
 {
     static int n = 0;   // (one GPU model per process: the count of the first device queried is kept)
     if (n == 0) {
@@ -639,6 +639,63 @@ hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s)
     if (bm == 256) return launch_cfg<256, 64, 4, 1>(a, s);
     if (bm == 128) return launch_cfg<128, 64, 4, 1>(a, s);
     return launch_cfg<64, 64, 2, 2>(a, s);
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// Ceiling probe: nothing but v_mfma_i32_32x32x32_i8 on register-resident operands, two wavefronts per SIMD, eight
+// independent accumulators per wavefront (the contraction kernel's own shape of MFMA work, without any operand
+// movement).  What it sustains on a given kind of operand values is the most the matrix pipes deliver under the
+// power manager: the datasheet rate on zeros, clearly less once every multiplier input toggles.
+// ------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void k_mfma_ceiling(int32_t* __restrict__ sink, int iters, int kind,
+                                                      unsigned long long* __restrict__ clk)
+{
+    unsigned long long c0 = 0, r0 = 0;
+    if (clk) {
+        c0 = clock64();
+        r0 = wall_clock64();
+    }
+    v16i acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0;
+    // operand words: 0 -> zeros, 1 -> every code 1, 2 -> one pseudo-random word per lane and register
+    v4i fa[4], fb[2];
+#pragma unroll
+    for (int i = 0; i < 6; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            uint32_t h = (threadIdx.x * 24u + (uint32_t)(i * 4 + v) + 1u) * 0x9E3779B1u;
+            h ^= h >> 15;
+            h *= 0x85EBCA6Bu;
+            h ^= h >> 13;
+            const int word = kind == 0 ? 0 : (kind == 1 ? 0x01010101 : (int)h);
+            if (i < 4) fa[i][v] = word;
+            else fb[i - 4][v] = word;
+        }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i & 3], fb[i >> 2], acc[i], 0, 0, 0);
+    }
+    int sum = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum += acc[i][v];
+    sink[blockIdx.x * 512 + threadIdx.x] = sum;   // keeps the accumulators live
+    if (clk && threadIdx.x == 0) {
+        atomicAdd(clk + 0, (unsigned long long)clock64() - c0);
+        atomicAdd(clk + 1, (unsigned long long)wall_clock64() - r0);
+    }
+}
+
+hipError_t launch_mfma_ceiling(int32_t* sink, int iters, int kind, unsigned long long* clk, int* workgroups, hipStream_t s)
+{
+    const int g = num_cus();
+    if (workgroups) *workgroups = g;
+    hipLaunchKernelGGL(k_mfma_ceiling, dim3((unsigned)g), dim3(512), 0, s, sink, iters, kind, clk);
+    return hipGetLastError();
 }
 
 }  // namespace ffi

@@ -446,6 +446,28 @@ def test_train_step_fused_live_and_per_layer_theta(ff):
     _run_steps(ff, one, 2, launch_mode="kernels")
 
 
+def test_mfma_ceiling_probe_counts_what_it_claims(ff):
+    """The register-resident MFMA loop: with every code equal to 1 each instruction adds 32 to each of a thread's 128
+    accumulator words, so the word a thread leaves behind is 4096 x iterations; zeros leave zero.  The operation count
+    it reports is workgroups x 8 wavefronts x iterations x 8 instructions x 65 536."""
+    sink = torch.full((256 * 512,), -1, dtype=torch.int32, device="cuda")
+    clk = torch.zeros(2, dtype=torch.int64, device="cuda")
+    ops = ff.ff_probe_mfma_ceiling(1, 7, sink, clk)
+    torch.cuda.synchronize()
+    wgs = torch.cuda.get_device_properties(0).multi_processor_count
+    assert ops == wgs * 8 * 7 * 8 * 65536
+    got = sink.cpu().numpy()
+    assert np.all(got[: wgs * 512] == 4096 * 7)
+    assert all(v > 0 for v in clk.cpu().tolist())
+    ff.ff_probe_mfma_ceiling(0, 3, sink, None)
+    torch.cuda.synchronize()
+    assert np.all(sink.cpu().numpy()[: wgs * 512] == 0)
+    with pytest.raises(ff.FFError):
+        ff.ff_probe_mfma_ceiling(3, 1, sink, None)
+    with pytest.raises(ff.FFError):
+        ff.ff_probe_mfma_ceiling(1, 1, sink[:1000], None)
+
+
 def test_fused_launch_mode_limits(ff):
     """Stacks the single launch does not cover are refused when it is asked for explicitly (workspace size 0:
     FF_ERR_UNSUPPORTED from the descriptor check) and fall back to per-operation kernels under FF_LAUNCH_AUTO."""

@@ -347,9 +347,10 @@ def main() -> int:
                     help="also run one plain 1 GiB-read / 1 GiB-write elementwise kernel (torch.add) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against known traffic")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph-replay timing")
-    ap.add_argument("--launch-mode", choices=("auto", "kernels", "fused"), default="auto",
-                    help="kernels: one kernel per operation; fused: the whole step as one persistent launch (small "
-                         "dense stacks); auto: fused where it applies and the stack is small")
+    ap.add_argument("--launch-mode", choices=("auto", "kernels", "fused", "lanes"), default="auto",
+                    help="kernels: one kernel per operation on one stream; lanes: the same, the update chains of "
+                         "different layers on up to three streams; fused: the whole step as one persistent launch (small "
+                         "dense stacks); auto: fused or lanes where they apply and the layers are small")
     ap.add_argument("--lookahead", choices=("coeff", "chain"), default="coeff",
                     help="chain: the exact-derivative variant of the look-ahead (dense stacks; one more contraction per layer)")
     ap.add_argument("--gemm-data-probe", action="store_true",

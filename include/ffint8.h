@@ -12,9 +12,12 @@
  *    (ff_layer_desc, ff_net_desc, ff_net_state and the pointer arrays inside
  *    ff_net_state) are [host] memory.
  *  - The caller owns every buffer.  The library allocates and frees no device
- *    memory and keeps no pointer after a call returns.  (The optional timing
- *    instrumentation at the end of this file creates host-side HIP events on
- *    first use; it is off unless ff_timing_enable is called.)
+ *    memory and keeps no pointer after a call returns.  (Host-side HIP objects
+ *    it does create, once and for the life of the process: two streams and
+ *    three events per device on the first ff_train_step that runs update
+ *    chains on several streams, see FF_LAUNCH_LANES; events of the optional
+ *    timing instrumentation at the end of this file, off unless
+ *    ff_timing_enable is called.)
  *  - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *    the default stream).  Calls return without synchronising; scalars that are
  *    produced on the device (scales, losses) stay on the device.
@@ -124,7 +127,7 @@ typedef struct {
                                     initialised weights the goodness of different layers differs by orders of
                                     magnitude; a threshold per layer keeps Eq. (1) and Eq. (2) away from saturation
                                     in all of them. */
-    int32_t launch_mode;         /* FF_LAUNCH_AUTO (0), FF_LAUNCH_KERNELS or FF_LAUNCH_FUSED, see below */
+    int32_t launch_mode;         /* FF_LAUNCH_AUTO (0), _KERNELS, _FUSED or _LANES, see below */
 } ff_net_desc;
 
 /* How ff_train_step issues its work.
@@ -135,10 +138,20 @@ typedef struct {
  *   per-sample goodness).  For the launch-bound regime of small networks and batches, the one nearest the paper's
  *   own batch of 32 (Section V-A).  Plain dense stacks (no convolutions, residual wiring or FF_LOOKAHEAD_CHAIN) of at
  *   most 8 layers and 1024 samples per pass; FF_ERR_UNSUPPORTED otherwise.  Same results, bit for bit.
+ * FF_LAUNCH_LANES: one kernel per operation, but the update chains of different layers (local gradient -> weight
+ *   gradient -> update -> requantise; independent of each other, the learning being layer-local) go to up to three
+ *   streams at once: the caller's and two that the library creates once per device (default priority) and keeps.  The
+ *   chains are forked off the caller's stream after the look-ahead kernel and joined back before the call returns, so
+ *   the step remains one piece of work in stream order, also under graph capture (a capture started before the
+ *   library's streams exist runs on the caller's stream alone).  Every lane has its own copy of the chain scratch in
+ *   the workspace.  For stacks of many small layers, whose single launches leave compute units idle.  Not with
+ *   FF_LOOKAHEAD_CHAIN (FF_ERR_UNSUPPORTED).  Same results, bit for bit.
  * FF_LAUNCH_AUTO: FF_LAUNCH_FUSED when the stack qualifies and one pass through it is at most 2^27 multiply-adds
- *   (784 -> 500 -> 500 at 64 samples is 41 M), else FF_LAUNCH_KERNELS.
- * ff_workspace_bytes depends on the mode (the fused step keeps every layer's int8 local gradient). */
-enum { FF_LAUNCH_AUTO = 0, FF_LAUNCH_KERNELS = 1, FF_LAUNCH_FUSED = 2 };
+ *   (784 -> 500 -> 500 at 64 samples is 41 M); else lanes when the layers are small -- three below 2^33 multiply-adds
+ *   per layer and pass on average, two below 2^36 -- else FF_LAUNCH_KERNELS.
+ * ff_workspace_bytes depends on the mode (the fused step keeps every layer's int8 local gradient; lanes multiply the
+ * chain scratch). */
+enum { FF_LAUNCH_AUTO = 0, FF_LAUNCH_KERNELS = 1, FF_LAUNCH_FUSED = 2, FF_LAUNCH_LANES = 3 };
 
 /* How the later layers' losses enter a layer's update (Eq. (3), Eq. (4)).
  * FF_LOOKAHEAD_COEFF: through their per-sample loss derivatives only (ff_lookahead); no gradient crosses a layer

@@ -248,7 +248,7 @@ class Net:
         if theta_layer is not None and len(theta_layer) != self.k:
             raise ValueError("theta_layer needs one threshold per layer")
         self.desc = NetDesc(self.k, batch, self._descs, self._mask, {"coeff": 0, "chain": 1}[lookahead], self._theta,
-                            {"auto": 0, "kernels": 1, "fused": 2}[launch_mode])
+                            {"auto": 0, "kernels": 1, "fused": 2, "lanes": 3}[launch_mode])
         self.w_master, self.w_q, self.s_w = list(w_master), list(w_q), list(s_w)
         self._pm = (C.c_void_p * self.k)(*[t.data_ptr() for t in self.w_master])
         self._pq = (C.c_void_p * self.k)(*[t.data_ptr() for t in self.w_q])

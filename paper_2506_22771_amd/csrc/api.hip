@@ -10,6 +10,7 @@ namespace ffi {
 
 constexpr int64_t INT32_SAFE_LEN = 2147483647ll / (127 * 127);  // longest reduction that cannot overflow int32
 constexpr int MAX_LAYERS = 32;
+constexpr int MAX_LANES = 3;   // streams that run the update chains of different layers side by side
 constexpr int MAX_CHUNKS = 2;  // weight-gradient accumulators per pass (k_update combines at most 4 terms)
 
 // Shapes of one layer as the kernels see them.
@@ -145,6 +146,12 @@ struct WsLayout {
     size_t off_gl;         // scratch of the goodness / loss kernel (see GoodnessArgs::loss_part)
     size_t zero_bytes;     // the region [0, zero_bytes) is cleared at the start of a step
     size_t off_scales;     // fp32: s_a[k][2], s_g[k][2]
+    // Scratch of one layer's update chain (local gradient -> weight gradient -> update -> requantise), `lanes` copies
+    // `lane_stride` bytes apart: off_wbmax, off_gy, off_dw, off_col and off_part below are those of lane 0.  The chains
+    // of different layers are independent of each other (layer-local learning), so a step may run them on several
+    // streams at once, each with a scratch of its own.
+    int lanes;
+    size_t lane_stride;
     size_t off_wbmax;      // uint32 [UPDATE_MAX_BLOCKS]
     size_t off_c, off_ct;  // fp32 [k][2][B]
     size_t off_gy, st_gy;  // int8 scratch [2][st_gy]: transposed quantised local gradient
@@ -247,8 +254,6 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
     w->zero_bytes = off;
     w->off_scales = off;
     off = align_up(off + sizeof(float) * (k * 4 + 4), A);   // + s_h[2], the scale of the transposed weight copy
-    w->off_wbmax = off;   // per-workgroup maxima of a small weight update (UpdateArgs::block_max)
-    off = align_up(off + sizeof(uint32_t) * UPDATE_MAX_BLOCKS, A);
     w->off_c = off;
     off = align_up(off + sizeof(float) * k * 2 * B, A);
     w->off_ct = off;
@@ -265,6 +270,52 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
     aq_dense = align_up(aq_dense, A);
     const size_t off_aq_dense = off;
     off += 2 * aq_dense;
+    if (net->launch_mode != FF_LAUNCH_AUTO && net->launch_mode != FF_LAUNCH_KERNELS && net->launch_mode != FF_LAUNCH_FUSED &&
+        net->launch_mode != FF_LAUNCH_LANES)
+        return FF_ERR_INVALID_ARG;
+    // Single-launch step: plain dense stacks of at most FU_MAX_LAYERS layers and FU_MAX_B samples per pass.  It keeps
+    // the local gradient of EVERY layer (the per-operation path reuses one scratch for all layers), hence the extra
+    // buffers; weight gradients are applied straight from the accumulator registers.
+    w->fused_ok = net->lookahead != FF_LOOKAHEAD_CHAIN && w->k <= FU_MAX_LAYERS && w->B <= FU_MAX_B;
+    double macs = 0.0;
+    int64_t fwd_tiles = 0, dw_tiles = 0;
+    for (int i = 0; i < w->k && w->fused_ok; ++i) {
+        const Dims& d = w->d[i];
+        const ff_layer_desc& L = net->layers[i];
+        if (d.kind != FF_DENSE || L.role != FF_ROLE_LAYER || L.skip != FF_SKIP_NONE || L.input_back != 0 || d.n_chunks != 1)
+            w->fused_ok = 0;
+        // (the kernel indexes with 32 bits)
+        if (d.N * pitch8(d.K) > (int64_t(1) << 30) || d.K * pitch8(d.B) > (int64_t(1) << 30) || d.N * pitch8(d.B) > (int64_t(1) << 30))
+            w->fused_ok = 0;
+        macs += (double)d.B * (double)d.K * (double)d.N;
+        fwd_tiles = max(fwd_tiles, 2 * ((d.B + 31) / 32) * ((d.N + 31) / 32));
+        dw_tiles += ((d.N + 31) / 32) * ((d.K + 31) / 32);
+    }
+    w->fused_auto = w->fused_ok && macs <= (double)(int64_t(1) << 27);   // 41 M for 784 -> 500 -> 500 at 64 samples
+    // workgroups: one per forward tile (both passes), and enough wavefronts (8 per workgroup) to take the weight-gradient
+    // tiles of all layers in one round; an even number
+    w->fused_wgs = (int)min((int64_t)256, max(max((int64_t)32, fwd_tiles), (dw_tiles + FU_THREADS / 64 - 1) / (FU_THREADS / 64)));
+    w->fused_wgs = (w->fused_wgs + 1) & ~1;
+    // Update chains on several streams: asked for (FF_LAUNCH_LANES), or chosen (FF_LAUNCH_AUTO) when the layers are small
+    // enough that single launches leave compute units idle -- mean multiply-adds per layer and pass below 2^33 (three
+    // lanes) or 2^36 (two).  Large dense layers fill the chip on their own and share one power budget: one lane.
+    {
+        double mean = 0.0;
+        for (int i = 0; i < w->k; ++i) mean += (double)w->d[i].M * (double)w->d[i].K * (double)w->d[i].N;
+        mean /= (double)w->k;
+        int lanes = 1;
+        if (net->lookahead == FF_LOOKAHEAD_COEFF && w->k >= 2) {
+            if (net->launch_mode == FF_LAUNCH_LANES) lanes = MAX_LANES;
+            else if (net->launch_mode == FF_LAUNCH_AUTO && !w->fused_auto)
+                lanes = mean < 8589934592.0 ? 3 : (mean < 68719476736.0 ? 2 : 1);
+        } else if (net->launch_mode == FF_LAUNCH_LANES) {
+            return FF_ERR_UNSUPPORTED;
+        }
+        w->lanes = min(lanes, w->k);
+    }
+    const size_t lane0 = off;
+    w->off_wbmax = off;   // per-workgroup maxima of a small weight update (UpdateArgs::block_max)
+    off = align_up(off + sizeof(uint32_t) * UPDATE_MAX_BLOCKS, A);
     w->st_gy = align_up(gy, A);
     w->off_gy = off;
     off += 2 * w->st_gy;
@@ -278,6 +329,8 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
     w->st_part = part;
     w->off_part = off;
     off += 2 * w->st_part;
+    w->lane_stride = align_up(off - lane0, A);
+    off = lane0 + (size_t)w->lanes * w->lane_stride;
     for (int i = 0; i < w->k; ++i) {
         const Dims& d = w->d[i];
         if (d.kind == FF_DENSE) {
@@ -334,31 +387,6 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
         w->off_wqt = off;
         off += align_up(wqt, A);
     }
-    // Single-launch step: plain dense stacks of at most FU_MAX_LAYERS layers and FU_MAX_B samples per pass.  It keeps
-    // the local gradient of EVERY layer (the per-operation path reuses one scratch for all layers), hence the extra
-    // buffers; weight gradients are applied straight from the accumulator registers.
-    if (net->launch_mode != FF_LAUNCH_AUTO && net->launch_mode != FF_LAUNCH_KERNELS && net->launch_mode != FF_LAUNCH_FUSED)
-        return FF_ERR_INVALID_ARG;
-    w->fused_ok = !w->chain && w->k <= FU_MAX_LAYERS && w->B <= FU_MAX_B;
-    double macs = 0.0;
-    int64_t fwd_tiles = 0, dw_tiles = 0;
-    for (int i = 0; i < w->k && w->fused_ok; ++i) {
-        const Dims& d = w->d[i];
-        const ff_layer_desc& L = net->layers[i];
-        if (d.kind != FF_DENSE || L.role != FF_ROLE_LAYER || L.skip != FF_SKIP_NONE || L.input_back != 0 || d.n_chunks != 1)
-            w->fused_ok = 0;
-        // (the kernel indexes with 32 bits)
-        if (d.N * pitch8(d.K) > (int64_t(1) << 30) || d.K * pitch8(d.B) > (int64_t(1) << 30) || d.N * pitch8(d.B) > (int64_t(1) << 30))
-            w->fused_ok = 0;
-        macs += (double)d.B * (double)d.K * (double)d.N;
-        fwd_tiles = max(fwd_tiles, 2 * ((d.B + 31) / 32) * ((d.N + 31) / 32));
-        dw_tiles += ((d.N + 31) / 32) * ((d.K + 31) / 32);
-    }
-    w->fused_auto = w->fused_ok && macs <= (double)(int64_t(1) << 27);   // 41 M for 784 -> 500 -> 500 at 64 samples
-    // workgroups: one per forward tile (both passes), and enough wavefronts (8 per workgroup) to take the weight-gradient
-    // tiles of all layers in one round; an even number
-    w->fused_wgs = (int)min((int64_t)256, max(max((int64_t)32, fwd_tiles), (dw_tiles + FU_THREADS / 64 - 1) / (FU_THREADS / 64)));
-    w->fused_wgs = (w->fused_wgs + 1) & ~1;
     for (int i = 0; i < w->k; ++i) w->off_fgy[i] = w->st_fgy[i] = 0;
     if (net->launch_mode == FF_LAUNCH_FUSED && !w->fused_ok) return FF_ERR_UNSUPPORTED;
     if (w->fused_ok && net->launch_mode != FF_LAUNCH_KERNELS && (w->fused_auto || net->launch_mode == FF_LAUNCH_FUSED)) {
@@ -1050,6 +1078,36 @@ size_t ff_workspace_bytes(const ff_net_desc* net)
 
 // One iteration of Algorithm 1.  step_dev == null: the step number is `step`; otherwise it is read from device
 // memory by the kernels (and advanced by one at the end when `advance` is set).
+// Streams and events of the update-chain lanes: lane 0 is the caller's stream, lanes 1 .. MAX_LANES - 1 are streams
+// the library creates once per device (default priority, non-blocking) and keeps until the process ends.  A step forks
+// them off the caller's stream with an event after the look-ahead kernel and joins them back before it returns, so for
+// the caller the step is still one piece of work in stream order (also under graph capture, where fork and join
+// become graph edges).
+struct LanePool {
+    hipStream_t st[MAX_LANES - 1];
+    hipEvent_t fork, join[MAX_LANES - 1];
+    bool ready;
+};
+static LanePool g_lanes[MAX_DEVICES];
+static std::mutex g_lanes_mutex;
+
+static LanePool* lanes_of_current_device(bool may_create)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_lanes_mutex);
+    LanePool& p = g_lanes[dev];
+    if (p.ready) return &p;
+    if (!may_create) return nullptr;
+    bool ok = hipEventCreateWithFlags(&p.fork, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < MAX_LANES - 1 && ok; ++i)
+        ok = hipStreamCreateWithFlags(&p.st[i], hipStreamNonBlocking) == hipSuccess &&
+             hipEventCreateWithFlags(&p.join[i], hipEventDisableTiming) == hipSuccess;
+    if (!ok) return nullptr;   // (whatever was created stays allocated; the step then runs on one stream)
+    p.ready = true;
+    return &p;
+}
+
 static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* state, const float* x_pos,
                                  const float* x_neg, float theta, float lambda, float lr, uint64_t seed, uint64_t step,
                                  uint64_t* step_dev, int32_t advance, float* loss, float* goodness, void* ws,
@@ -1315,12 +1373,74 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
     // ---- per layer: int8 local gradient, int8 weight gradient, update (Algorithm 1, inner loop) ----
     // weights of layer `t` from the transposed int8 gradient in the scratch (quantised for layer `gl`): weight-gradient
     // contraction per pass and chunk, combined update, requantisation
+    // ---- lanes: which stream and which copy of the chain scratch a layer's update chain uses
+    hipStream_t lane_stream[MAX_LANES] = {s, s, s};
+    int n_lanes = 1;
+    LanePool* pool = nullptr;
+    if (w.lanes > 1 && !w.chain) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        const bool capturing = hipStreamIsCapturing(s, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone;
+        pool = lanes_of_current_device(!capturing);   // nothing is created while a graph is being captured
+        if (pool) {
+            n_lanes = w.lanes;
+            for (int l = 1; l < n_lanes; ++l) lane_stream[l] = pool->st[l - 1];
+        }
+    }
+    int lane_of[MAX_LAYERS];
+    {
+        // longest chain first onto the lane with the least work so far (cost ~ multiply-adds of the layer)
+        double load[MAX_LANES] = {0.0, 0.0, 0.0};
+        bool placed[MAX_LAYERS];
+        for (int i = 0; i < k; ++i) { placed[i] = false; lane_of[i] = 0; }
+        for (int n = 0; n < k && n_lanes > 1; ++n) {
+            int best = -1;
+            double bc = -1.0;
+            for (int i = 0; i < k; ++i) {
+                const double c = (double)w.d[i].M * (double)w.d[i].K * (double)w.d[i].N;
+                if (!placed[i] && c > bc) { bc = c; best = i; }
+            }
+            int l = 0;
+            for (int j = 1; j < n_lanes; ++j)
+                if (load[j] < load[l]) l = j;
+            placed[best] = true;
+            lane_of[best] = l;
+            load[l] += bc;
+        }
+        // a projection is updated by the chain of the block's second convolution
+        for (int i = 0; i < k; ++i)
+            if (w.d[i].skip == FF_SKIP_PROJECTION && i >= 2) lane_of[i - 2] = lane_of[i];
+    }
+    if (n_lanes > 1) {
+        if (hipEventRecord(pool->fork, s) != hipSuccess) return FF_ERR_HIP;
+        for (int l = 1; l < n_lanes; ++l)
+            if (hipStreamWaitEvent(lane_stream[l], pool->fork, 0) != hipSuccess) return FF_ERR_HIP;
+    }
+    // every way out of the function from here on joins the lanes back into the caller's stream
+    struct Join {
+        LanePool* pool;
+        hipStream_t* st;
+        int n;
+        bool failed = false;
+        ~Join()
+        {
+            for (int l = 1; l < n; ++l) {
+                if (hipEventRecord(pool->join[l - 1], st[l]) != hipSuccess) failed = true;
+                if (hipStreamWaitEvent(st[0], pool->join[l - 1], 0) != hipSuccess) failed = true;
+            }
+            n = 1;
+        }
+    };
+
     auto wgrad_update = [&](int t, int gl) -> ff_status {
         const Dims& d = w.d[t];
+        const int lane = lane_of[gl];
+        hipStream_t s = lane_stream[lane];                        // (shadows the caller's stream inside the chain)
+        char* base = (char*)ws + (size_t)lane * w.lane_stride;   // lane-scoped scratch: gy, dw, col, part, wbmax
+        char* const base0 = (char*)ws;                            // what lives outside the lanes
         const bool dense = d.kind == FF_DENSE || d.pointwise;   // layers that keep a transposed copy of their input
         const int64_t dw_elems = (int64_t)(w.dw_bytes / sizeof(int32_t));
         const ff_status ws_ = run_wgrad(d, (const int8_t*)(base + w.off_gy), (int64_t)w.st_gy,
-                                        dense ? (const int8_t*)(base + w.off_aqt[t]) : (const int8_t*)(base + w.off_aq[t]),
+                                        dense ? (const int8_t*)(base0 + w.off_aqt[t]) : (const int8_t*)(base0 + w.off_aq[t]),
                                         dense ? (int64_t)w.st_aqt[t] : (int64_t)w.st_aq[t], (int8_t*)(base + w.off_col),
                                         (int64_t)w.st_col, (int32_t*)(base + w.off_part),
                                         (int64_t)(w.st_part / sizeof(int32_t)), (int32_t*)(base + w.off_dw),
@@ -1521,12 +1641,16 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         return FF_OK;
     }
 
+    {
+    Join join{pool, lane_stream, n_lanes};
     for (int i = 0; i < k; ++i) {
         const Dims& d = w.d[i];
         if (d.role == FF_ROLE_PROJECTION) continue;   // updated with the gradient of the block output, layer i + 2
         const bool with_proj = d.skip == FF_SKIP_PROJECTION && trained(i - 2);
         if (!trained(i) && !with_proj) continue;      // frozen layer: forward only
         const ff_layer_desc& L = net->layers[i];
+        hipStream_t ls = lane_stream[lane_of[i]];
+        char* const lbase = base + (size_t)lane_of[i] * w.lane_stride;   // this chain's copy of the scratch
         QuantArgs a;
         memset(&a, 0, sizeof(a));
         int src = QSRC_GRAD;
@@ -1558,18 +1682,18 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         a.rows = d.M;
         a.cols = d.N;
         if (d.kind == FF_DWCONV2D) {   // the depthwise weight gradient reads the gradient row-major
-            a.q = (int8_t*)(base + w.off_gy);
+            a.q = (int8_t*)(lbase + w.off_gy);
             a.st_q = (int64_t)w.st_gy;
             a.ldq = pitch8(d.N);
         } else {
-            a.q_t = (int8_t*)(base + w.off_gy);
+            a.q_t = (int8_t*)(lbase + w.off_gy);
             a.st_qt = (int64_t)w.st_gy;
             a.ldqt = pitch8(d.M);
         }
         a.scale = s_g + 2 * i;
         a.st_scale = 1;
         a.nb = 2;
-        HIPCHK_T(FF_K_QUANT_GRAD, launch_quantize(src, a, s));
+        HIPCHK_T(FF_K_QUANT_GRAD, launch_quantize(src, a, ls));
 
         if (trained(i)) {
             const ff_status us = wgrad_update(i, i);
@@ -1580,6 +1704,7 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
             if (us != FF_OK) return us;
         }
     }
+    }   // (the lanes are joined here)
     if (step_dev && advance) HIPCHK_T(FF_K_SMALL, launch_advance_u64(step_dev, s));
     return FF_OK;
 }

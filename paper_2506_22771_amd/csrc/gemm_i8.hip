@@ -44,6 +44,12 @@ constexpr int BK = 128;  // reduction bytes per LDS stage
 #ifndef FF_SPLIT_ISSUE
 #define FF_SPLIT_ISSUE 1
 #endif
+#ifndef FF_DEEP
+// 1: tiles smaller than 256 x 256 use three or four LDS stages (two or three copies in flight).  Measured: the contraction
+// launches get 4-5 % shorter on their own, but the steps of the small and convolution configurations get 2-3 % longer
+// (a workgroup that holds most of the LDS keeps the next kernel's workgroups off the compute unit while the launch drains).
+#define FF_DEEP 0
+#endif
 #ifndef FF_STAGED_EPI
 #define FF_STAGED_EPI 1   // 1: interior tiles leave through LDS as whole rows (see the epilogue)
 #endif
@@ -101,7 +107,12 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     constexpr int EROW = WTN * 4 + 16;
     constexpr int ESLICE = EROWS * EROW;
     constexpr int EOFF = PREFETCH ? STAGE_BYTES : 0;
-    constexpr int LDS_BYTES = 2 * STAGE_BYTES > EOFF + WM * WN * ESLICE ? 2 * STAGE_BYTES : EOFF + WM * WN * ESLICE;
+    // LDS stages: two for the big tile (128 KB); the smaller tiles, whose launches are short chains of reduction steps
+    // that each wait for a round trip to memory, keep up to three copies in flight
+    constexpr int NS = (FF_DEEP && !(BM == 256 && BN == 256)) ? (4 * STAGE_BYTES <= 160 * 1024 ? 4 : 3) : 2;
+    constexpr int CH = CH_P + CH_Q;   // copy instructions of one thread per reduction step
+    static_assert((NS - 1) * CH < 64, "vmcnt range");
+    constexpr int LDS_BYTES = NS * STAGE_BYTES > EOFF + WM * WN * ESLICE ? NS * STAGE_BYTES : EOFF + WM * WN * ESLICE;
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
     __shared__ __attribute__((aligned(16))) int8_t lds[LDS_BYTES];
 
@@ -253,15 +264,14 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
         if (kt0 + 1 < nk) issue(kt0 + 1, 1);
         ldfrag(0, lds, 0);
     } else {
-    // both stages are free at the start of a tile: the copies of the first two steps go out together, so that only
+    // all stages are free at the start of a tile: the copies of the first NS steps go out together, so that only
     // one round trip to memory is exposed (copies complete in issue order)
     issue(kt0, 0);
-    if (kt0 + 1 < nk) {
-        issue(kt0 + 1, 1);
-        wait_vmcnt<CH_P + CH_Q>();
-    } else {
-        wait_vmcnt<0>();
-    }
+#pragma unroll
+    for (int i = 1; i < NS; ++i)
+        if (kt0 + i < nk) issue(kt0 + i, i);
+    if (kt0 + NS - 1 < nk) wait_vmcnt<(NS - 1) * CH>();
+    else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     ldfrag(0, lds, 0);
     }
@@ -273,10 +283,11 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     if (kt0 + 1 < nk) issue(kt0 + 1, 1);
 #endif
     if (a.clk) ph1 = clock64();
+    int cur = 0;   // stage of step kt: (kt - kt0) % NS
     for (int kt = kt0; kt < nk; ++kt) {
-        const int cur = (kt - kt0) & 1;
+        const int nxt = cur + 1 == NS ? 0 : cur + 1;
         const int8_t* sb = lds + cur * STAGE_BYTES;
-        const int8_t* sn = lds + (cur ^ 1) * STAGE_BYTES;
+        const int8_t* sn = lds + nxt * STAGE_BYTES;
         ldfrag(1, sb, 1);
         mma(0);
         ldfrag(0, sb, 2);
@@ -284,7 +295,10 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
         ldfrag(1, sb, 3);
         mma(0);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        wait_vmcnt<0>();
+        // the copies of step kt + 1 must have landed; those of the NS - 2 steps after it may stay in flight (near the
+        // end of the reduction fewer are outstanding: wait for all)
+        if (NS > 2 && kt + NS - 1 < nk) wait_vmcnt<(NS - 2) * CH>();
+        else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
 #if FF_SPLIT_ISSUE
         // The copy instructions of a step keep the address unit busy for about a thousand clocks (64 KB at 64 bytes
@@ -292,15 +306,16 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
         // multiplies of the step, the other half after them, so that every SIMD has multiplies to run while the
         // copies queue up.
         const bool early = wave < WM * WN / 2;
-        if (early && kt + 2 < nk) issue(kt + 2, cur);
+        if (early && kt + NS < nk) issue(kt + NS, cur);
         if (kt + 1 < nk) ldfrag(0, sn, 0);
         mma(1);
-        if (!early && kt + 2 < nk) issue(kt + 2, cur);
+        if (!early && kt + NS < nk) issue(kt + NS, cur);
 #else
-        if (kt + 2 < nk) issue(kt + 2, cur);
+        if (kt + NS < nk) issue(kt + NS, cur);
         if (kt + 1 < nk) ldfrag(0, sn, 0);
         mma(1);
 #endif
+        cur = nxt;
     }
 
     // Epilogue.  A lane holds, per accumulator quad, four consecutive columns of ONE row, so a direct store

@@ -210,10 +210,17 @@ def test_launch_mode_validation(ff):
         descs = (ff.binding.LayerDesc * len(wl.layers))(*[ff.layer_desc(l, wl.batch) for l in wl.layers])
         return ff.lib().ff_workspace_bytes(C.byref(ff.binding.NetDesc(len(wl.layers), wl.batch, descs, None, 0, None, mode)))
 
-    assert nbytes("cfg1", 3) == 0 and nbytes("cfg1", -1) == 0
+    assert nbytes("cfg1", 4) == 0 and nbytes("cfg1", -1) == 0
     assert nbytes("cfg1", 2) == nbytes("cfg1", 0) > nbytes("cfg1", 1) > 0        # auto picks the single launch for cfg1
     assert nbytes("cfg5", 2) == 0 and nbytes("cfg5", 0) == nbytes("cfg5", 1) > 0  # 8192 samples per pass: too many
     assert nbytes("cfg3", 2) == 0 and nbytes("tiny_res", 2) == 0                  # convolutions, residual wiring
+    # update chains on several streams: every lane has its own chain scratch; auto picks lanes for stacks of small
+    # layers (three for cfg4 and cfg2, two for cfg3) and none for cfg5
+    assert nbytes("cfg4", 3) == nbytes("cfg4", 0) > nbytes("cfg4", 1) > 0
+    assert nbytes("cfg2", 3) == nbytes("cfg2", 0) > nbytes("cfg2", 1) > 0
+    assert nbytes("cfg3", 3) > nbytes("cfg3", 0) > nbytes("cfg3", 1) > 0
+    assert nbytes("cfg5", 3) > nbytes("cfg5", 1)
     wl = workload("tiny")
     descs = (ff.binding.LayerDesc * 2)(*[ff.layer_desc(l, wl.batch) for l in wl.layers])
     assert ff.lib().ff_workspace_bytes(C.byref(ff.binding.NetDesc(2, wl.batch, descs, None, 1, None, 2))) == 0   # chain + fused
+    assert ff.lib().ff_workspace_bytes(C.byref(ff.binding.NetDesc(2, wl.batch, descs, None, 1, None, 3))) == 0   # chain + lanes

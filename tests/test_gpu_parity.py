@@ -434,6 +434,44 @@ def test_train_step_launch_modes(ff, name, steps, mode):
     _run_steps(ff, workload(name), steps, launch_mode=mode)
 
 
+@pytest.mark.parametrize("mode", ["kernels", "lanes"])
+@pytest.mark.parametrize("name,steps", [("tiny_l2", 2), ("tiny_conv", 2), ("tiny_conv_s2", 2), ("tiny_res", 3), ("tiny_dw", 2),
+                                        ("tiny_cnn_head", 2)])
+def test_train_step_update_chains_on_one_or_several_streams(ff, name, steps, mode):
+    """The update chains of the layers (local gradient, weight gradient, update, requantise) on the caller's stream
+    alone, and spread over three streams with a chain scratch each -- dense, convolution, residual (a projection is
+    updated by the chain of its block's second convolution), depthwise and flattening stacks, each against the oracle.
+    FF_LAUNCH_AUTO, which the other tests use, picks the lanes for stacks of small layers."""
+    _run_steps(ff, workload(name), steps, launch_mode=mode)
+
+
+def test_train_step_lanes_with_frozen_layers_and_consecutive_steps(ff):
+    """Lanes with some layers frozen (their chains are skipped), five steps in a row without a host synchronisation in
+    between (the next step's forward pass must wait for every lane of the previous one), against the one-stream path."""
+    from paper_2506_22771_amd import schedule
+    wl = workload("tiny_res")
+    W = make_weights(wl)
+    xp, xn = make_inputs(wl)
+    B, k = wl.batch, len(wl.layers)
+    x = (torch.from_numpy(xp.reshape(B, -1)).cuda(), torch.from_numpy(xn.reshape(B, -1)).cuda())
+    out = {}
+    for mode in ("kernels", "lanes"):
+        st = schedule.TrainState.from_weights(wl.layers, B, W)
+        train = [1] * k
+        train[1] = 0
+        net = ff.Net(wl.layers, B, st.w_master, st.w_q, st.s_w, train_layer=train, launch_mode=mode)
+        ws = torch.empty(net.workspace_bytes(), dtype=torch.uint8, device="cuda")
+        loss, good = torch.empty((k, 2), device="cuda"), torch.empty((k, 2, B), device="cuda")
+        for step in range(5):
+            ff.ff_train_step(net, x[0], x[1], wl.theta, wl.lam, wl.lr, wl.sr_seed, step, loss, good, ws)
+        torch.cuda.synchronize()
+        out[mode] = ([w.clone() for w in st.w_master], [q.clone() for q in st.w_q], loss.clone(), good.clone())
+    for a, b in zip(out["kernels"][0] + out["kernels"][1], out["lanes"][0] + out["lanes"][1]):
+        assert torch.equal(a, b)
+    assert torch.equal(out["kernels"][2], out["lanes"][2]) and torch.equal(out["kernels"][3], out["lanes"][3])
+    assert torch.equal(out["kernels"][0][1].cpu(), torch.from_numpy(W[1].reshape(W[1].shape[0], -1)))   # frozen layer untouched
+
+
 def test_train_step_fused_live_and_per_layer_theta(ff):
     """The single-launch step with matched per-layer thresholds (both passes live, asserted on the oracle side), with
     and for a one-layer stack (frozen layers: the schedule tests run through this path too)."""
@@ -481,7 +519,8 @@ def test_fused_launch_mode_limits(ff):
         if name != "cfg2":
             assert mk("fused") == 0
         else:   # cfg2 qualifies structurally (dense, 1024 samples) but is far too large for FF_LAUNCH_AUTO to pick it
-            assert mk("fused") > mk("auto") == mk("kernels")
+            # (auto spreads its update chains over three streams instead: a chain scratch per lane)
+            assert mk("fused") > mk("kernels") and mk("auto") == mk("lanes") > mk("kernels")
 
 
 @pytest.mark.slow

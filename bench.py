@@ -288,19 +288,36 @@ def other_config(ff, torch, name, steps=10, warmup=3):
     net, d_xp, d_xn, loss, good, ws = st[:6]
     for i in range(warmup):
         ff.ff_train_step(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, i, loss, good, ws)
-    ms, kern = time_steps(ff, torch, wl, st, wl.theta, steps, warmup, ("gemm_fwd", "gemm_dw", "fused"))
+    ms, kern = time_steps(ff, torch, wl, st, wl.theta, steps, warmup, ("fused",))
     k, B = len(wl.layers), wl.batch
     ops = contraction_ops_per_step(wl)
-    g = gemm_figures(wl, kern)
     fused = kern["fused"]["launches_per_step"] > 0
-    out_extra = {}
+    # the same step as one kernel per operation on one stream (what FF_LAUNCH_AUTO does not pick for this stack unless
+    # the two times are equal), with events around the contraction launches: their share of the int8 peak
+    st_k = setup(ff, torch, wl, theta_layer=th, state=st, launch_mode="kernels")
+    for i in range(warmup):
+        ff.ff_train_step(st_k[0], d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, i, loss, good, st_k[5])
+    ms_k, kern_k = time_steps(ff, torch, wl, st_k, wl.theta, steps, warmup)
+    g = gemm_figures(wl, kern_k)
+    # one captured HIP graph of the default launch mode, replayed
+    step_dev = torch.tensor([2 * warmup + 2 * steps], dtype=torch.int64, device="cuda")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ff.ff_train_step_at(net, d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, step_dev, 1, loss, good, ws)
+    for _ in range(2):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms_g = (time.perf_counter() - t0) / steps * 1e3
+    del graph
+    out_extra = {"ms_per_step_graph_replay": round(ms_g, 4), "ms_per_step_per_operation_kernels_one_stream": round(ms_k, 4)}
+    if not fused:
+        out_extra["launch"] = ("one kernel per operation; update chains of different layers on several streams where "
+                               "FF_LAUNCH_AUTO chooses so (cfg2, cfg3, cfg4)")
     if fused:
-        # the step ran as one persistent launch (FF_LAUNCH_AUTO picks it for small dense stacks): time the
-        # per-operation kernels beside it
-        st_k = setup(ff, torch, wl, theta_layer=th, state=st, launch_mode="kernels")
-        for i in range(warmup):
-            ff.ff_train_step(st_k[0], d_xp, d_xn, wl.theta, wl.lam, wl.lr, wl.sr_seed, i, loss, good, st_k[5])
-        ms_k, _ = time_steps(ff, torch, wl, st_k, wl.theta, steps, warmup)
         # phase durations inside the launch (100 MHz stamps of its first workgroup), mean of 20 steps
         stamps = torch.zeros(32, dtype=torch.int64, device="cuda")
         ff.ff_timing_fused_stamps(stamps)
@@ -316,15 +333,15 @@ def other_config(ff, torch, name, steps=10, warmup=3):
         names = ["absmax_input"] + [n for i in range(k) for n in (f"quantise_{i}", f"forward_{i}")] + \
                 ["goodness_lookahead_gradquant", "wgrad_update", "requantise"]
         phases = {n: round(float(v) / 20, 2) for n, v in zip(names, acc)}
-        out_extra = {"launch": "single persistent launch (FF_LAUNCH_FUSED via FF_LAUNCH_AUTO)",
-                     "ms_per_step_per_operation_kernels": round(ms_k, 4),
-                     "phase_us_inside_the_launch": phases,
-                     "phase_note": "each phase but the last ends in a device-wide barrier across the 8 XCDs"}
+        out_extra.update({"launch": "single persistent launch (FF_LAUNCH_FUSED via FF_LAUNCH_AUTO)",
+                          "phase_us_inside_the_launch": phases,
+                          "phase_note": "each phase but the last ends in a device-wide barrier across the 8 XCDs"})
     return {"layers": k, "batch_per_pass": B, "ms_per_step": round(ms, 4), **out_extra,
             "samples_per_s_per_layer_step": round(2 * B * k / (ms * 1e-3), 1),
             "whole_step_int8_TOPs": round(ops / (ms * 1e-3) / 1e12, 1),
             "whole_step_frac_of_int8_peak": round(ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, 4),
-            "contraction_launches_frac_of_int8_peak": None if fused else round(g["achieved"] / INT8_MFMA_PEAK_TOPS, 4)}
+            "contraction_launches_frac_of_int8_peak": round(g["achieved"] / INT8_MFMA_PEAK_TOPS, 4),
+            "contraction_note": "from the one-stream per-operation pass (launch durations are only meaningful unoverlapped)"}
 
 
 def main() -> int:
@@ -548,7 +565,8 @@ def main() -> int:
         for name in ("cfg1", "cfg2", "cfg3", "cfg4"):
             oc[name] = other_config(ff, torch, name)
             torch.cuda.empty_cache()
-        oc["note"] = "eager launches, 10 steps after 3 warm-up steps, thresholds matched per layer; outside the timed region"
+        oc["note"] = ("ms_per_step: eager launches in the default launch mode (FF_LAUNCH_AUTO), 10 steps after 3 warm-up "
+                      "steps, thresholds matched per layer; outside the timed region")
         out["other_configs"] = oc
     if not args.no_cpu_baseline:
         sb = args.cpu_sample_batch or {"cfg5": 8192, "cfg2": 1024, "cfg1": 64, "cfg3": 64, "cfg4_plain": 32}.get(wl.name, min(B, 256))

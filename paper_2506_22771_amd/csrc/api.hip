@@ -307,7 +307,7 @@ static ff_status make_layout(const ff_net_desc* net, WsLayout* w)
         if (net->lookahead == FF_LOOKAHEAD_COEFF && w->k >= 2) {
             if (net->launch_mode == FF_LAUNCH_LANES) lanes = MAX_LANES;
             else if (net->launch_mode == FF_LAUNCH_AUTO && !w->fused_auto)
-                lanes = mean < 8589934592.0 ? 3 : (mean < 68719476736.0 ? 2 : 1);
+                lanes = mean < 8589934592.0 ? MAX_LANES : (mean < 68719476736.0 ? 2 : 1);
         } else if (net->launch_mode == FF_LAUNCH_LANES) {
             return FF_ERR_UNSUPPORTED;
         }
@@ -1374,7 +1374,8 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
     // weights of layer `t` from the transposed int8 gradient in the scratch (quantised for layer `gl`): weight-gradient
     // contraction per pass and chunk, combined update, requantisation
     // ---- lanes: which stream and which copy of the chain scratch a layer's update chain uses
-    hipStream_t lane_stream[MAX_LANES] = {s, s, s};
+    hipStream_t lane_stream[MAX_LANES];
+    for (int l = 0; l < MAX_LANES; ++l) lane_stream[l] = s;
     int n_lanes = 1;
     LanePool* pool = nullptr;
     if (w.lanes > 1 && !w.chain) {
@@ -1389,7 +1390,8 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
     int lane_of[MAX_LAYERS];
     {
         // longest chain first onto the lane with the least work so far (cost ~ multiply-adds of the layer)
-        double load[MAX_LANES] = {0.0, 0.0, 0.0};
+        double load[MAX_LANES];
+        for (int l = 0; l < MAX_LANES; ++l) load[l] = 0.0;
         bool placed[MAX_LAYERS];
         for (int i = 0; i < k; ++i) { placed[i] = false; lane_of[i] = 0; }
         for (int n = 0; n < k && n_lanes > 1; ++n) {

@@ -256,6 +256,9 @@ struct GemmArgs {
     // wtaps_only; row j of the contraction is (kh, kw, ci), the reduction runs over output pixels.  W_out % 16 == 0.
     int32_t conv, H, W, Cin, cpitch, ks, stride, pad, Ho, Wo;
     int64_t p_bytes;  // bytes of one implicit operand tensor (conv only; must be < 2^31)
+    // log2 of C_in (conv == 1), of H_out * W_out and of W_out (conv == 2) when those are powers of two, else -1: the
+    // loaders then index with shifts instead of integer divisions.  Filled in by launch_gemm_nt_i8.
+    int32_t cin_shift, hw_shift, wo_shift;
     // instrumentation (null normally): every workgroup adds the shader-clock cycles and the 100 MHz constant-clock
     // ticks it was alive to clk[0] and clk[1] (their ratio is the mean shader clock during the launch) and the
     // shader clocks of each tile by phase to clk[2..6] / clk[8..12]

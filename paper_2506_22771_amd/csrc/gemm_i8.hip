@@ -193,8 +193,11 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
         int8_t* base = lds + buf * STAGE_BYTES;
         if (CONV == 1) {
             const int k = k0 + kcol;
-            const int tap = k / a.Cin, ci0 = k - tap * a.Cin;
-            const int kh = tap / a.ks, kw = tap - kh * a.ks;
+            // (power-of-two channel counts and 3x3 kernels, the usual case, without integer divisions)
+            const int tap = a.cin_shift >= 0 ? k >> a.cin_shift : k / a.Cin;
+            const int ci0 = k - tap * a.Cin;
+            const int kh = a.ks == 3 ? (tap * 11) >> 5 : tap / a.ks;
+            const int kw = tap - kh * a.ks;
             const int dk = (kh * a.W + kw) * a.cpitch + ci0;
 #pragma unroll
             for (int s = 0; s < CH_P; ++s) {
@@ -210,8 +213,11 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
             // the chunk's 16 reduction positions are 16 consecutive output pixels of one output row (W_out % 16 == 0)
             const int m = k0 + kcol;
             const int hw = a.Ho * a.Wo;
-            const int b = m / hw, rem = m - b * hw;
-            const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
+            // (power-of-two maps, the usual case, without integer divisions)
+            const int b = a.hw_shift >= 0 ? m >> a.hw_shift : m / hw;
+            const int rem = m - b * hw;
+            const int ho = a.wo_shift >= 0 ? rem >> a.wo_shift : rem / a.Wo;
+            const int wo = rem - ho * a.Wo;
             const int hb = ho * a.stride;
             const int base_in = b * a.H * a.Wo + wo;
 #pragma unroll
@@ -628,8 +634,9 @@ hipError_t launch_reduce_splits(const int32_t* part, int splits, int64_t st_spli
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s)
+hipError_t launch_gemm_nt_i8(const GemmArgs& a_in, hipStream_t s)
 {
+    GemmArgs a = a_in;   // (the loaders' shift counts are filled in below)
     if (a.I <= 0 || a.J <= 0) return hipSuccess;
     // byte offsets of the operand copies are 32-bit (tile-relative for dense operands, tensor-relative for conv)
     if (a.ldp >= (int64_t(1) << 22) || a.ldq >= (int64_t(1) << 22)) return hipErrorInvalidValue;
@@ -639,6 +646,15 @@ hipError_t launch_gemm_nt_i8(const GemmArgs& a, hipStream_t s)
         return hipErrorInvalidValue;
     if (a.conv < 0 || a.conv > 2) return hipErrorInvalidValue;
     if (a.splits < 1 || (a.splits > 1 && (a.gsum || a.conv == 1))) return hipErrorInvalidValue;
+    auto shift_of = [](int v) {   // log2 of a power of two, else -1
+        if (v <= 0 || (v & (v - 1)) != 0) return -1;
+        int sh = 0;
+        while ((1 << sh) < v) ++sh;
+        return sh;
+    };
+    a.cin_shift = a.conv == 1 ? shift_of(a.Cin) : -1;
+    a.hw_shift = a.conv == 2 ? shift_of(a.Ho * a.Wo) : -1;
+    a.wo_shift = a.conv == 2 ? shift_of(a.Wo) : -1;
     GemmPlan p = gemm_plan(a.I, a.J, a.R, a.nb, a.splits > 1);
     const int bm = p.bm, bn = p.bn;
     if (bn == 256) {

@@ -145,7 +145,9 @@ typedef struct {
  *   the step remains one piece of work in stream order, also under graph capture (a capture started before the
  *   library's streams exist runs on the caller's stream alone).  Every lane has its own copy of the chain scratch in
  *   the workspace.  For stacks of many small layers, whose single launches leave compute units idle.  Not with
- *   FF_LOOKAHEAD_CHAIN (FF_ERR_UNSUPPORTED).  Same results, bit for bit.
+ *   FF_LOOKAHEAD_CHAIN (FF_ERR_UNSUPPORTED).  Same results, bit for bit.  The library's streams and their fork / join
+ *   events are shared by all calls on a device: steps that use lanes must not be issued from several host threads at
+ *   the same time (steps issued one after the other, on any streams, are fine).
  * FF_LAUNCH_AUTO: FF_LAUNCH_FUSED when the stack qualifies and one pass through it is at most 2^27 multiply-adds
  *   (784 -> 500 -> 500 at 64 samples is 41 M); else lanes when the layers are small -- three below 2^33 multiply-adds
  *   per layer and pass on average, two below 2^36 -- else FF_LAUNCH_KERNELS.

@@ -1194,11 +1194,38 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
     HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)base, (int64_t)(w.zero_bytes / 4), 0u, s));
     HIPCHK_T(FF_K_ABSMAX, launch_absmax(x_pos, st_x, 2, n_in, out_amax, s));
 
+    // ---- streams: the caller's, plus the library's own where the step runs independent work side by side
+    hipStream_t lane_stream[MAX_LANES];
+    for (int l = 0; l < MAX_LANES; ++l) lane_stream[l] = s;
+    int n_lanes = 1;
+    LanePool* pool = nullptr;
+    if (w.lanes > 1 && !w.chain) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        const bool capturing = hipStreamIsCapturing(s, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone;
+        pool = lanes_of_current_device(!capturing);   // nothing is created while a graph is being captured
+        if (pool) {
+            n_lanes = w.lanes;
+            for (int l = 1; l < n_lanes; ++l) lane_stream[l] = pool->st[l - 1];
+        }
+    }
+    const hipStream_t s_main = s;
+
     // ---- forward pass through all layers, both data sets together (Algorithm 1) -----------------
+    bool proj_pending = false;   // a projection's forward pass is running on the second stream
     for (int i = 0; i < k; ++i) {
         const Dims& d = w.d[i];
         const ff_layer_desc& L = net->layers[i];
         const bool dense = d.kind == FF_DENSE;
+        // The 1x1 projection of a residual block and the block's first convolution read the same input and do not
+        // depend on each other: with a second stream at hand the projection (quantiser + contraction; no patch
+        // scratch: it reads the input tensor directly) runs there, and the block's second convolution waits for it.
+        const bool side = n_lanes > 1 && d.role == FF_ROLE_PROJECTION && (d.implicit || d.pointwise) && !proj_pending;
+        hipStream_t s = s_main;
+        if (side) {
+            if (hipEventRecord(pool->fork, s_main) != hipSuccess || hipStreamWaitEvent(lane_stream[1], pool->fork, 0) != hipSuccess)
+                return FF_ERR_HIP;
+            s = lane_stream[1];
+        }
         QuantArgs a;
         memset(&a, 0, sizeof(a));
         int src;
@@ -1258,20 +1285,25 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         a.scale = s_a + 2 * i;
         a.st_scale = 1;
         a.nb = 2;
-        HIPCHK_T(FF_K_QUANT_ACT, launch_quantize(src, a, s));
-
         const bool plain = d.role == FF_ROLE_LAYER && d.skip == FF_SKIP_NONE;   // goodness straight from the accumulators
-        const ff_status fs = run_forward(d, L.relu ? 1 : 0, (const int8_t*)(base + w.off_aq[i]), (int64_t)w.st_aq[i],
-                                         state->w_q[i], (int32_t*)(base + w.off_acc[i]),
-                                         (int64_t)(w.st_acc[i] / sizeof(int32_t)),
-                                         plain ? gsum + (int64_t)i * 2 * B : nullptr, vmax + (int64_t)i * 2 * B, B,
-                                         (int8_t*)(base + w.off_col), (int64_t)w.st_col, 2, s);
+        ff_status fs = [&]() -> ff_status {
+            HIPCHK_T(FF_K_QUANT_ACT, launch_quantize(src, a, s));
+            return run_forward(d, L.relu ? 1 : 0, (const int8_t*)(base + w.off_aq[i]), (int64_t)w.st_aq[i], state->w_q[i],
+                               (int32_t*)(base + w.off_acc[i]), (int64_t)(w.st_acc[i] / sizeof(int32_t)),
+                               plain ? gsum + (int64_t)i * 2 * B : nullptr, vmax + (int64_t)i * 2 * B, B,
+                               (int8_t*)(base + w.off_col), (int64_t)w.st_col, 2, s);
+        }();
+        if (side) {   // (whatever happened on the second stream, it is joined back)
+            if (hipEventRecord(pool->join[0], s) != hipSuccess) fs = fs != FF_OK ? fs : FF_ERR_HIP;
+            proj_pending = true;
+            if (fs != FF_OK) (void)hipStreamWaitEvent(s_main, pool->join[0], 0);
+        }
         if (fs != FF_OK) return fs;
         if (d.role == FF_ROLE_PROJECTION) {
             // no activity of its own: zero coefficients (nothing enters the look-ahead sums), zero loss / goodness rows
-            HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(c + (int64_t)i * 2 * B), 2 * B, 0u, s));
-            HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(goodness + (int64_t)i * 2 * B), 2 * B, 0u, s));
-            HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(loss + 2 * i), 2, 0u, s));
+            HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(c + (int64_t)i * 2 * B), 2 * B, 0u, s_main));
+            HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(goodness + (int64_t)i * 2 * B), 2 * B, 0u, s_main));
+            HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(loss + 2 * i), 2, 0u, s_main));
             continue;
         }
         if (!plain) {
@@ -1307,6 +1339,10 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
             ra.ymax_bits = (uint32_t*)(vmax + (int64_t)i * 2 * B);
             ra.st_b = B;
             ra.nb = 2;
+            if (d.skip == FF_SKIP_PROJECTION && proj_pending) {   // the projection's accumulators are read from here on
+                if (hipStreamWaitEvent(s_main, pool->join[0], 0) != hipSuccess) return FF_ERR_HIP;
+                proj_pending = false;
+            }
             HIPCHK_T(FF_K_RESIDUAL, launch_residual_act(ra, s));
             GoodnessFxArgs fa;
             memset(&fa, 0, sizeof(fa));
@@ -1349,6 +1385,8 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         HIPCHK_T(FF_K_SMALL, launch_goodness_loss(ga, s));
     }
 
+    if (proj_pending && hipStreamWaitEvent(s_main, pool->join[0], 0) != hipSuccess) return FF_ERR_HIP;
+
     // ---- look-ahead coefficients of every layer (Eq. (3)/(4)) and the absmax of every local gradient
     if (!w.chain) {
         LookaheadArgs la;
@@ -1373,20 +1411,7 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
     // ---- per layer: int8 local gradient, int8 weight gradient, update (Algorithm 1, inner loop) ----
     // weights of layer `t` from the transposed int8 gradient in the scratch (quantised for layer `gl`): weight-gradient
     // contraction per pass and chunk, combined update, requantisation
-    // ---- lanes: which stream and which copy of the chain scratch a layer's update chain uses
-    hipStream_t lane_stream[MAX_LANES];
-    for (int l = 0; l < MAX_LANES; ++l) lane_stream[l] = s;
-    int n_lanes = 1;
-    LanePool* pool = nullptr;
-    if (w.lanes > 1 && !w.chain) {
-        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-        const bool capturing = hipStreamIsCapturing(s, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone;
-        pool = lanes_of_current_device(!capturing);   // nothing is created while a graph is being captured
-        if (pool) {
-            n_lanes = w.lanes;
-            for (int l = 1; l < n_lanes; ++l) lane_stream[l] = pool->st[l - 1];
-        }
-    }
+    // ---- lanes: which copy of the chain scratch and which stream a layer's update chain uses
     int lane_of[MAX_LAYERS];
     {
         // longest chain first onto the lane with the least work so far (cost ~ multiply-adds of the layer)

@@ -63,7 +63,7 @@ def test_step_at_equals_step(ff, name):
     assert int(step_dev.item()) == 8
 
 
-@pytest.mark.parametrize("name", ["tiny_l2", "cfg1", "tiny_conv16", "tiny/chain"])
+@pytest.mark.parametrize("name", ["tiny_l2", "cfg1", "tiny_conv16", "tiny_res", "tiny/chain"])
 def test_captured_graph_replays_match_eager_steps(ff, name):
     name, _, mode = name.partition("/")
     wl = workload(name)

@@ -364,6 +364,9 @@ def main() -> int:
                     help="also run one plain 1 GiB-read / 1 GiB-write elementwise kernel (torch.add) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run can be scaled against known traffic")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph-replay timing")
+    ap.add_argument("--timed-region-only", action="store_true",
+                    help="stop after the timed steps and print a short line (for rocprofv3 runs: the trace or the counters "
+                         "then cover the threshold set-up step, the warm-up and the timed steps only)")
     ap.add_argument("--launch-mode", choices=("auto", "kernels", "fused", "lanes"), default="auto",
                     help="kernels: one kernel per operation on one stream; lanes: the same, the update chains of "
                          "different layers on up to three streams; fused: the whole step as one persistent launch (small "
@@ -432,6 +435,15 @@ def main() -> int:
     ms_per_step, kern = time_steps(ff, torch, wl, st, wl.theta, args.steps, step_no)
     step_no += args.steps
     samples = 2 * B
+    if args.timed_region_only:
+        # for profiler runs: nothing but the set-up step, the warm-up and the timed steps is launched
+        g = gemm_figures(wl, kern)
+        print(json.dumps({"workload": wl.name, "ms_per_step": ms_per_step, "steps": args.steps, "warmup": args.warmup,
+                          "launch_mode": args.launch_mode, "lookahead": args.lookahead,
+                          "contraction_avg_launch_ms": g["avg_launch_ms"], "contraction_TOPs": g["achieved"],
+                          "fwd_TOPs": g["fwd_TOPs"], "dw_TOPs": g["dw_TOPs"],
+                          "contraction_frac_of_int8_peak": g["achieved"] / INT8_MFMA_PEAK_TOPS}))
+        return 0
 
     # ---- outside the timed region: the same K steps with every kernel class timed (the per-class breakdown) and the
     # shader-clock probe of the contraction launches switched on; then K replays of one captured HIP graph

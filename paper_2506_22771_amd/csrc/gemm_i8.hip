@@ -23,6 +23,12 @@
 //  * The Q tile feeds the MFMA "A" operand and the P tile the "B" operand, so that every lane ends up
 //    with one row i of C and four consecutive columns j per accumulator quad: 16-byte stores, and the
 //    per-row reductions stay inside a lane (one cross-half-wave shuffle at the end).
+//  * Large dense problems run as a persistent launch: one workgroup per compute unit walks over its
+//    share of the 256 x 256 tiles; the copies of a tile's first two reduction steps go out together, and
+//    those of the NEXT tile's first step are issued at the start of the epilogue, into the LDS stage
+//    that the accumulator staging does not use, so that their round trip runs under the stores.
+//  * Within a reduction step half of the wavefronts issue the next copies before the step's last
+//    multiplies and half after them: every SIMD keeps multiplying while the copy instructions queue up.
 #include "ff_internal.hpp"
 
 namespace ffi {

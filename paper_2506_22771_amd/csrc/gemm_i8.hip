@@ -108,11 +108,12 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
     constexpr int CH_P = BM * 8 / T, CH_Q = BN * 8 / T;
     constexpr int STAGE_BYTES = (BM + BN) * BK;
     static_assert(BM * 8 % T == 0 && BN * 8 % T == 0, "tile/threads mismatch");
-    // epilogue staging: one slice of EROWS rows of a wave's tile, rows padded by 16 bytes to spread the banks.  The big
-    // dense tile stages 16 rows at a time in the SECOND operand stage (and a little beyond it), which leaves the first
-    // stage free for the first copies of the workgroup's next tile (persistent launches); the others 32 rows from 0.
-    constexpr bool PREFETCH = FF_NEXT_TILE_PREFETCH && BM == 256 && BN == 256 && CONV == 0 && MODE != 2;
-    constexpr int EROWS = PREFETCH ? 16 : 32;
+    // epilogue staging: one slice of EROWS rows of a wave's tile, rows padded by 16 bytes to spread the banks.  The
+    // 256-row tiles stage in the SECOND operand stage (and a little beyond it; 16 rows at a time for the 256 x 256 tile,
+    // so that it fits), which leaves the first stage free for the first copies of the workgroup's next tile (persistent
+    // launches); the others 32 rows from 0.
+    constexpr bool PREFETCH = FF_NEXT_TILE_PREFETCH && BM == 256 && CONV != 2 && MODE != 2;
+    constexpr int EROWS = PREFETCH && BN == 256 ? 16 : 32;
     constexpr int EROW = WTN * 4 + 16;
     constexpr int ESLICE = EROWS * EROW;
     constexpr int EOFF = PREFETCH ? STAGE_BYTES : 0;
@@ -349,7 +350,21 @@ __global__ __launch_bounds__(WM* WN * 64) void k_gemm_nt_i8(GemmArgs a)
         const int tn = t + (int)gridDim.x;
         const int zn = tn / tiles_z, tzn = tn - zn * tiles_z;
         const int i0n = (tzn % tiles_i) * BM, j0n = (tzn / tiles_i) * BN;
-        rp = __builtin_amdgcn_make_buffer_rsrc((void*)(a.P + zn * a.st_p + (int64_t)i0n * a.ldp), 0, (int)(min(BM, a.I - i0n) * a.ldp), 0x00020000);
+        if (CONV == 1) {
+            // the pixel offsets of the current tile are not needed any more: those of the next one take their place
+            rp = __builtin_amdgcn_make_buffer_rsrc((void*)(a.P + zn * a.st_p), 0, (int)a.p_bytes, 0x00020000);
+#pragma unroll
+            for (int s = 0; s < CH_P; ++s) {
+                const int m = i0n + ((s * T + tid) >> 3);
+                const int b = m / (a.Ho * a.Wo), rem = m - b * (a.Ho * a.Wo);
+                const int ho = rem / a.Wo, wo = rem - ho * a.Wo;
+                hi0[s] = m < a.I ? ho * a.stride - a.pad : -(1 << 20);
+                wi0[s] = wo * a.stride - a.pad;
+                offP[s] = ((b * a.H + hi0[s]) * a.W + wi0[s]) * a.cpitch;
+            }
+        } else {
+            rp = __builtin_amdgcn_make_buffer_rsrc((void*)(a.P + zn * a.st_p + (int64_t)i0n * a.ldp), 0, (int)(min(BM, a.I - i0n) * a.ldp), 0x00020000);
+        }
         rq = __builtin_amdgcn_make_buffer_rsrc((void*)(a.Q + zn * a.st_q + (int64_t)j0n * a.ldq), 0, (int)(min(BN, a.J - j0n) * a.ldq), 0x00020000);
         issue(0, 0);
         prefetched = true;
@@ -513,10 +528,16 @@ static hipError_t launch_cfg(const GemmArgs& a, hipStream_t s)
     const int64_t ntiles = (int64_t)tiles_i * tiles_j * a.nb;
     if (ntiles > 0x7FFFFFFF) return hipErrorInvalidValue;
     const int mode = a.splits > 1 ? 2 : (a.gsum ? 1 : 0);
-    // persistent launch: one workgroup per compute unit when every compute unit has at least two whole tiles
+    // persistent launch (256-row tiles of dense and implicit-convolution operands): as many workgroups as fit the chip at
+    // once -- one per compute unit, two where a workgroup takes at most half of the LDS -- when each has at least two
+    // whole tiles
     int64_t gx = ntiles;
-    if (FF_PERSIST && BM == 256 && BN == 256 && a.conv == 0 && mode != 2 && ntiles >= 2 * num_cus() && ntiles % num_cus() == 0)
-        gx = num_cus();
+    if (FF_PERSIST && FF_NEXT_TILE_PREFETCH && BM == 256 && a.conv != 2 && mode != 2) {
+        const int stage = (BM + BN) * BK, eslice = (BN == 256 ? 16 : 32) * (BN / WN * 4 + 16);
+        const int lds = 2 * stage > stage + WM * WN * eslice ? 2 * stage : stage + WM * WN * eslice;   // as in the kernel
+        const int64_t resident = (int64_t)num_cus() * (lds <= 80 * 1024 ? 2 : 1);
+        if (ntiles >= 2 * resident && ntiles % resident == 0) gx = resident;
+    }
     const dim3 grid((unsigned)gx, (unsigned)a.splits, 1), block(WM * WN * 64);
     if (a.conv == 1) {
         if (mode == 1) hipLaunchKernelGGL((k_gemm_nt_i8<BM, BN, WM, WN, 1, 1>), grid, block, 0, s, a);

@@ -1287,6 +1287,13 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         a.nb = 2;
         const bool plain = d.role == FF_ROLE_LAYER && d.skip == FF_SKIP_NONE;   // goodness straight from the accumulators
         ff_status fs = [&]() -> ff_status {
+            if (d.role == FF_ROLE_PROJECTION) {
+                // no activity of its own: zero coefficients (nothing enters the look-ahead sums), zero loss / goodness rows
+                // (on the projection's own stream: nothing reads them before the look-ahead kernel)
+                HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(c + (int64_t)i * 2 * B), 2 * B, 0u, s));
+                HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(goodness + (int64_t)i * 2 * B), 2 * B, 0u, s));
+                HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(loss + 2 * i), 2, 0u, s));
+            }
             HIPCHK_T(FF_K_QUANT_ACT, launch_quantize(src, a, s));
             return run_forward(d, L.relu ? 1 : 0, (const int8_t*)(base + w.off_aq[i]), (int64_t)w.st_aq[i], state->w_q[i],
                                (int32_t*)(base + w.off_acc[i]), (int64_t)(w.st_acc[i] / sizeof(int32_t)),
@@ -1299,13 +1306,7 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
             if (fs != FF_OK) (void)hipStreamWaitEvent(s_main, pool->join[0], 0);
         }
         if (fs != FF_OK) return fs;
-        if (d.role == FF_ROLE_PROJECTION) {
-            // no activity of its own: zero coefficients (nothing enters the look-ahead sums), zero loss / goodness rows
-            HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(c + (int64_t)i * 2 * B), 2 * B, 0u, s_main));
-            HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(goodness + (int64_t)i * 2 * B), 2 * B, 0u, s_main));
-            HIPCHK_T(FF_K_SMALL, launch_fill_u32((uint32_t*)(loss + 2 * i), 2, 0u, s_main));
-            continue;
-        }
+        if (d.role == FF_ROLE_PROJECTION) continue;
         if (!plain) {
             ResidualArgs ra;
             memset(&ra, 0, sizeof(ra));
@@ -1437,25 +1438,22 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
         for (int i = 0; i < k; ++i)
             if (w.d[i].skip == FF_SKIP_PROJECTION && i >= 2) lane_of[i - 2] = lane_of[i];
     }
-    if (n_lanes > 1) {
-        if (hipEventRecord(pool->fork, s) != hipSuccess) return FF_ERR_HIP;
-        for (int l = 1; l < n_lanes; ++l)
-            if (hipStreamWaitEvent(lane_stream[l], pool->fork, 0) != hipSuccess) return FF_ERR_HIP;
-    }
-    // every way out of the function from here on joins the lanes back into the caller's stream
+    // joins the lanes back into the caller's stream: explicitly at the end of the chains, and on every early way out
     struct Join {
         LanePool* pool;
         hipStream_t* st;
         int n;
-        bool failed = false;
-        ~Join()
+        ff_status finish()
         {
+            bool ok = true;
             for (int l = 1; l < n; ++l) {
-                if (hipEventRecord(pool->join[l - 1], st[l]) != hipSuccess) failed = true;
-                if (hipStreamWaitEvent(st[0], pool->join[l - 1], 0) != hipSuccess) failed = true;
+                ok = hipEventRecord(pool->join[l - 1], st[l]) == hipSuccess && ok;
+                ok = hipStreamWaitEvent(st[0], pool->join[l - 1], 0) == hipSuccess && ok;
             }
             n = 1;
+            return ok ? FF_OK : FF_ERR_HIP;
         }
+        ~Join() { (void)finish(); }
     };
 
     auto wgrad_update = [&](int t, int gl) -> ff_status {
@@ -1670,6 +1668,11 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
 
     {
     Join join{pool, lane_stream, n_lanes};
+    if (n_lanes > 1) {   // fork: the lanes start where the caller's stream stands now (all forward passes, the look-ahead)
+        if (hipEventRecord(pool->fork, s) != hipSuccess) return FF_ERR_HIP;
+        for (int l = 1; l < n_lanes; ++l)
+            if (hipStreamWaitEvent(lane_stream[l], pool->fork, 0) != hipSuccess) return FF_ERR_HIP;
+    }
     for (int i = 0; i < k; ++i) {
         const Dims& d = w.d[i];
         if (d.role == FF_ROLE_PROJECTION) continue;   // updated with the gradient of the block output, layer i + 2
@@ -1731,7 +1734,9 @@ static ff_status train_step_impl(const ff_net_desc* net, const ff_net_state* sta
             if (us != FF_OK) return us;
         }
     }
-    }   // (the lanes are joined here)
+    const ff_status js = join.finish();
+    if (js != FF_OK) return js;
+    }
     if (step_dev && advance) HIPCHK_T(FF_K_SMALL, launch_advance_u64(step_dev, s));
     return FF_OK;
 }

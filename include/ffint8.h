@@ -29,9 +29,12 @@
  *    FF_ERR_HIP reports a failure of the HIP runtime itself (a launch that the
  *    runtime rejects); kernels enqueued before it have run.  The library never
  *    throws, aborts or prints.
- *  - int8 matrices are row-major with a row pitch of ff_pitch(cols) bytes
- *    (cols rounded up to 16); the pad bytes of every int8 tensor the library
- *    WRITES are zero, and every int8 tensor it READS must have zero pad bytes.
+ *  - int8 matrices are row-major with a row pitch of ff_pitch(cols) bytes:
+ *    cols rounded up to 16, and to 128 for rows longer than 512 bytes (those
+ *    then start on cache lines, which the contraction's 128-byte copies want;
+ *    784 -> 896, 2000 -> 2048).  The pad bytes of every int8 tensor the library
+ *    WRITES are zero, and every int8 tensor it READS must have zero pad bytes
+ *    up to cols rounded up to 16 (nothing reads a row beyond that).
  *    int32 matrices are row-major with a row pitch of ff_pitch32(cols)
  *    elements (cols rounded up to 4).  fp32 tensors are contiguous.
  *  - Base addresses: int8 / int32 / workspace buffers 16-byte aligned

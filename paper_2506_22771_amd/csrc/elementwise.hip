@@ -317,7 +317,9 @@ static void launch_quantize_t(const QuantArgs& a, hipStream_t s)
         hipLaunchKernelGGL((k_quantize<SRC, STOCH, true, 8>), grid, block, 0, s, a);
         return;
     }
-    const dim3 grid((unsigned)((a.cols + QTile<16>::COLS - 1) / QTile<16>::COLS),
+    // (column tiles up to the row pitch of q, so that its pad bytes are written too: zeros)
+    const int64_t span = a.q && a.ldq > a.cols ? a.ldq : a.cols;
+    const dim3 grid((unsigned)((span + QTile<16>::COLS - 1) / QTile<16>::COLS),
                     (unsigned)((a.rows + QTile<16>::ROWS - 1) / QTile<16>::ROWS), (unsigned)a.nb);
     if (vec) hipLaunchKernelGGL((k_quantize<SRC, STOCH, true>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((k_quantize<SRC, STOCH, SRC != QSRC_F32 && SRC != QSRC_F32_GRAD>), grid, block, 0, s, a);

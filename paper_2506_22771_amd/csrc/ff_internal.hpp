@@ -11,7 +11,14 @@
 namespace ffi {
 
 // ---- layout helpers -------------------------------------------------------------------------
-__host__ __device__ static inline int64_t pitch8(int64_t cols) { return (cols + 15) & ~int64_t(15); }
+// Row pitch of an int8 matrix in bytes: a multiple of 16 (the copy granule); rows longer than 512 bytes start on 128-byte
+// lines, so that the 128-byte chunks the contraction copies per reduction step never straddle two cache lines (reduction
+// lengths such as 784 or 2000 would otherwise cost every copy two line requests).  Kernels read a row only up to its
+// length rounded up to 16; the bytes after that are padding that nothing reads.
+__host__ __device__ static inline int64_t pitch8(int64_t cols)
+{
+    return cols <= 512 ? (cols + 15) & ~int64_t(15) : (cols + 127) & ~int64_t(127);
+}
 __host__ __device__ static inline int64_t pitch32(int64_t cols) { return (cols + 3) & ~int64_t(3); }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

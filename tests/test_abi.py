@@ -33,7 +33,9 @@ def test_every_declared_symbol_is_exported(ff):
 
 
 def test_pitch_and_tags(ff):
-    assert [ff.ff_pitch(c) for c in (0, 1, 16, 17, 500, 4096)] == [0, 16, 16, 32, 512, 4096]
+    assert [ff.ff_pitch(c) for c in (0, 1, 16, 17, 500, 512, 4096)] == [0, 16, 16, 32, 512, 512, 4096]
+    # rows longer than 512 bytes start on 128-byte lines
+    assert [ff.ff_pitch(c) for c in (513, 576, 784, 2000, 4097)] == [640, 640, 896, 2048, 4224]
     assert [ff.ff_pitch32(c) for c in (0, 1, 4, 5, 500)] == [0, 4, 4, 8, 500]
     from oracle import ff_oracle as O
     for args in [(0, 0, 0, 0), (3, 2, 1, 1), (1000, 19, 0, 1)]:
